@@ -1,0 +1,164 @@
+/*
+ * actq.h -- C ABI of libactq: per-group stochastic quantization of saved
+ * activations for activation-compressed training (ActNN, arXiv 2104.14129),
+ * written for one AMD MI355X (gfx950).
+ *
+ * The tensor is viewed as N samples x D features, sample-major and contiguous
+ * (Sec. 4.1: an activation H in R^{N x D}).  Each sample is cut into
+ * ng = ceil(D / G) groups of G consecutive features; groups never cross a
+ * sample, because the bit-width b_n is a per-sample quantity (Sec. 4.2).  The
+ * last group of a sample may be ragged when G does not divide D.
+ *
+ * Conventions shared by every call
+ *   - Return value: 0 (ACTQ_OK) or a negative actq_status.  A human-readable
+ *     text for the last failure on the calling thread is returned by
+ *     actq_last_error().
+ *   - "device" pointers are HIP device memory, "host" pointers ordinary memory.
+ *     The caller owns every buffer; the library allocates nothing, keeps no
+ *     state between calls and never frees or retains a pointer.
+ *   - Device calls are asynchronous on the HIP stream passed as `stream`
+ *     (a hipStream_t cast to void*, NULL = the default stream) and never
+ *     synchronise.  All argument validation happens on the host before any
+ *     launch; a call that fails validation launches nothing.
+ *   - Inputs must be finite.  Non-finite inputs are memory-safe but the codes
+ *     they produce are unspecified.
+ *   - Supported group size: G = 256.  Supported widths: b_n in {1, 2, 4, 8}.
+ *   - x / out must be aligned to 16 bytes, packed to 16 bytes, header to 8.
+ */
+#ifndef ACTQ_H
+#define ACTQ_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum actq_status {
+    ACTQ_OK = 0,
+    ACTQ_EINVAL = -1,      /* bad argument (null, size, alignment, G, dtype, bits) */
+    ACTQ_EINFEASIBLE = -2, /* allocate_bits: budget below one bit per element      */
+    ACTQ_EHIP = -3         /* the HIP runtime refused the launch                   */
+} actq_status;
+
+typedef enum actq_dtype {
+    ACTQ_F32 = 0, /* IEEE binary32 */
+    ACTQ_F16 = 1  /* IEEE binary16; widened exactly to binary32 before any arithmetic */
+} actq_dtype;
+
+/* Library version, major*10000 + minor*100 + patch. */
+int actq_version(void);
+
+/* Text of the last error raised on this thread ("" if none).  The pointer stays
+ * valid until the next failing call on the same thread. */
+const char* actq_last_error(void);
+
+/*
+ * Size of the compressed store (the "bit stream" of Sec. 5.1; the layout is
+ * this library's, the paper does not give one).
+ *
+ * Sample n occupies ng * G * b_n / 8 bytes starting at byte
+ * offsets_host[n] = sum_{m<n} ng * G * b_m / 8; *total_host receives the sum
+ * over all samples.  Inside a sample, group g starts at g * G * b_n / 8 and the
+ * code of in-group element j occupies bits [(j*b_n) mod 8, +b_n) of byte
+ * floor(j*b_n / 8): an LSB-first linear bit stream.  The padding codes of a
+ * ragged last group are zero.
+ *
+ * bits_host [N]    host, in   : b_n in {1,2,4,8}
+ * offsets_host [N] host, out  : may be NULL when only the total is wanted
+ * total_host       host, out  : may be NULL
+ * Errors: ACTQ_EINVAL on N <= 0, D <= 0, unsupported G, a width outside
+ * {1,2,4,8}, or both outputs NULL.
+ */
+int actq_packed_bytes(int64_t N, int64_t D, int32_t G, const uint8_t* bits_host,
+                      uint64_t* offsets_host, uint64_t* total_host);
+
+/*
+ * Per-group zero point Z = min and range R = max - min (Sec. 4.1).
+ *
+ * x      device, in  : N*D elements of dtype `dt`
+ * gmin   device, out : [N*ng] float, Z of every group; -0.0 is stored as +0.0
+ * grange device, out : [N*ng] float, R = max - min rounded to nearest
+ * Only the valid elements of a ragged group take part.
+ */
+int actq_group_stats(const void* x, actq_dtype dt, int64_t N, int64_t D, int32_t G,
+                     float* gmin, float* grange, void* stream);
+
+/*
+ * Forward pass: scale, round stochastically, pack (Sec. 4.1, Sec. 5.1), in one
+ * pass over x.
+ *
+ * For a group with zero point Z and range R and a sample with b bits,
+ * B = 2^b - 1:  inv = B / R,  scale = R / B  (binary32, round to nearest);
+ * a group whose R is zero, or whose B / R overflows, has inv = scale = 0.
+ * For every element: u = min((x - Z) * inv, B), two separately rounded
+ * binary32 operations; code = floor(u) + [noise < u - floor(u)].
+ *
+ * noise is uniform on a grid of 2^noise_bits points in [0,1), taken from
+ * Philox4x32-10 (Salmon et al., SC'11) keyed by `seed`, so a call is exactly
+ * reproducible.  With d the feature index inside sample n:
+ *   noise_bits = 24: counter (d>>2, n, lo32(tag), hi32(tag)), element d takes
+ *                    output word d&3 and noise = (word >> 8) * 2^-24;
+ *   noise_bits = 16: counter (d>>3, n, lo32(tag), hi32(tag)), element d takes
+ *                    word (d>>1)&3, low half if d is even, high half if odd,
+ *                    and noise = half * 2^-16.
+ * key = (lo32(seed), hi32(seed)).  `tag` separates tensors (layers) that share
+ * a seed.  Requires N < 2^32 and D < 2^34.
+ *
+ * x        device, in  : N*D elements of dtype `dt`
+ * bits     device, in  : [N] widths b_n in {1,2,4,8}
+ * offsets  device, in  : [N] byte offsets as produced by actq_packed_bytes
+ * packed   device, out : the bit stream; `packed_capacity` bytes are writable
+ * header   device, out : [N*ng][2] float, (Z, scale) of every group
+ *
+ * bits and offsets live on the device, so the host cannot check them: a sample
+ * whose width is not in {1,2,4,8} or whose byte range would leave
+ * [0, packed_capacity) is skipped (no byte of its output is written).
+ */
+int actq_quantize_pack(const void* x, actq_dtype dt, int64_t N, int64_t D, int32_t G,
+                       const uint8_t* bits, const uint64_t* offsets,
+                       uint64_t seed, uint64_t tag, int32_t noise_bits,
+                       void* packed, uint64_t packed_capacity, float* header,
+                       void* stream);
+
+/*
+ * Backward pass: unpack and dequantize (Sec. 4.1): h^ = code * scale + Z,
+ * evaluated as one fused multiply-add in binary32; binary16 output is the
+ * round-to-nearest-even conversion of that value.
+ *
+ * packed  device, in  : bit stream written by actq_quantize_pack
+ * header  device, in  : [N*ng][2] float (Z, scale)
+ * bits, offsets       : as for actq_quantize_pack; a sample that fails the same
+ *                       checks against `packed_capacity` is skipped
+ * out     device, out : N*D elements of dtype `out_dt`
+ */
+int actq_unpack_dequantize(const void* packed, uint64_t packed_capacity,
+                           const float* header, const uint8_t* bits,
+                           const uint64_t* offsets, int64_t N, int64_t D, int32_t G,
+                           void* out, actq_dtype out_dt, void* stream);
+
+/*
+ * Greedy solution of the bit-allocation problem (Sec. 4.2, Prob. (9); greedy
+ * with a binary heap as in Sec. 4.3): minimise sum_i w_i / B_i^2 subject to
+ * sum_i D_i * b_i <= budget_bits, B_i = 2^{b_i} - 1.
+ *
+ * Every item starts at 8 bits.  A move lowers one item one rung on the ladder
+ * 8 -> 4 -> 2 -> 1.  Its price is the variance it adds per bit it frees,
+ *   key = (double)w_i * c / (double)D_i,
+ *   c(8->4) = (1/225 - 1/65025)/4, c(4->2) = (1/9 - 1/225)/2, c(2->1) = 1 - 1/9,
+ * and while the budget is exceeded the move with the smallest (key, i) is
+ * applied.  The header cost of the groups is not part of the budget.
+ *
+ * w        host, in  : [M] sensitivities, finite and >= 0
+ * D        host, in  : [M] element counts, > 0
+ * bits_out host, out : [M]
+ * Errors: ACTQ_EINVAL on bad arguments; ACTQ_EINFEASIBLE when even one bit per
+ * element exceeds the budget (bits_out is then all ones).
+ */
+int actq_allocate_bits(const float* w, const int64_t* D, int64_t M,
+                       int64_t budget_bits, uint8_t* bits_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ACTQ_H */

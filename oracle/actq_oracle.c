@@ -1,0 +1,360 @@
+/*
+ * actq_oracle.c -- TEST INFRASTRUCTURE, not part of the product.
+ *
+ * A plain, slow CPU statement of what the activation-compression hot path of
+ * ActNN (arXiv 2104.14129) computes: per-group min/range, stochastic rounding
+ * to b-bit codes, a linear bit stream, dequantization, and the greedy bit
+ * allocator.  It follows the paper step by step (Sec. 4.1 for the quantizer,
+ * Sec. 4.2 Prob. (9) and Sec. 4.3 for the allocator) and shares no code,
+ * header, table or constant with the GPU library.  Only tests, the smoke check
+ * and the cpu_baseline leg of the benchmark may call it.
+ *
+ * Parity status: every function below is pinned by tests that do not depend on
+ * this file (see tests/test_oracle_*.py), except the *optimality* of the greedy
+ * allocator in general, which the paper itself calls a heuristic: that is
+ * "parity unpinned".
+ *
+ * Build: gcc -O2 -std=c11 -ffp-contract=off -fopenmp -shared -fPIC.
+ * -ffp-contract=off matters: the subtraction and the multiplication of the
+ * scaling step are two separately rounded binary32 operations.
+ * The loops over groups carry an OpenMP pragma; results do not depend on the
+ * thread count because the noise is a pure function of (seed, tag, n, d).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <string.h>
+
+#define ORC_OK 0
+#define ORC_EINVAL (-1)
+#define ORC_EINFEASIBLE (-2)
+
+/* ------------------------------------------------------------------------- */
+/* binary16 <-> binary32, written out by hand (this gcc has no _Float16).     */
+
+/* Exact widening of an IEEE binary16 bit pattern. */
+float orc_half_to_float(uint16_t h)
+{
+    uint32_t sign = (uint32_t)(h >> 15) & 1u;
+    int exp = (h >> 10) & 0x1f;
+    uint32_t man = h & 0x3ffu;
+    float v;
+    if (exp == 0) {
+        v = ldexpf((float)man, -24); /* zero or subnormal: man * 2^-24 */
+    } else if (exp == 31) {
+        v = man ? NAN : INFINITY;
+    } else {
+        v = ldexpf((float)(man | 0x400u), exp - 25); /* 1.man * 2^(exp-15) */
+    }
+    return sign ? -v : v;
+}
+
+/* Round-to-nearest-even narrowing of a binary32 value to binary16 bits. */
+uint16_t orc_float_to_half(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    uint16_t sign = (uint16_t)((u >> 16) & 0x8000u);
+    float a = fabsf(f);
+    if (isnan(f)) return (uint16_t)(sign | 0x7e00u);
+    if (a >= 65520.0f) return (uint16_t)(sign | 0x7c00u); /* rounds to infinity */
+    if (a < 6.103515625e-05f) {
+        /* below the smallest normal half: the result is an integer multiple of
+         * 2^-24; nearbyintf rounds half-way cases to even. */
+        float k = nearbyintf(ldexpf(a, 24));
+        return (uint16_t)(sign | (uint16_t)k); /* k == 1024 lands on the smallest normal */
+    }
+    int e;
+    float m = frexpf(a, &e);                 /* a = m * 2^e, m in [0.5, 1) */
+    float k = nearbyintf(ldexpf(m, 11));     /* 11 significant bits, in [1024, 2048] */
+    if (k == 2048.0f) { k = 1024.0f; e += 1; }
+    /* a = (k/1024) * 2^(e-1): biased exponent e-1+15 */
+    return (uint16_t)(sign | (uint16_t)((e + 14) << 10) | ((uint16_t)k & 0x3ffu));
+}
+
+static float load_elem(const void* x, int dtype, int64_t idx)
+{
+    if (dtype == 0) return ((const float*)x)[idx];
+    return orc_half_to_float(((const uint16_t*)x)[idx]);
+}
+
+/* ------------------------------------------------------------------------- */
+/* Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): ten rounds of two        */
+/* 32x32->64 multiplications; the key is bumped by the Weyl constants before   */
+/* every round but the first.                                                  */
+
+void orc_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        if (round > 0) {
+            k0 += 0x9E3779B9u;
+            k1 += 0xBB67AE85u;
+        }
+        uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* Uniform noise on a grid of 2^noise_bits points in [0,1) for feature d of
+ * sample n.  24 bits: one output word per element, four elements per counter.
+ * 16 bits: half a word per element, eight elements per counter. */
+float orc_noise(uint64_t seed, uint64_t tag, uint32_t n, uint64_t d, int noise_bits)
+{
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t ctr[4], out[4];
+    ctr[1] = n;
+    ctr[2] = (uint32_t)tag;
+    ctr[3] = (uint32_t)(tag >> 32);
+    if (noise_bits == 24) {
+        ctr[0] = (uint32_t)(d >> 2);
+        orc_philox4x32_10(ctr, key, out);
+        uint32_t r = out[d & 3];
+        return (float)(r >> 8) * 5.9604644775390625e-08f; /* 2^-24, exact */
+    }
+    ctr[0] = (uint32_t)(d >> 3);
+    orc_philox4x32_10(ctr, key, out);
+    uint32_t word = out[(d >> 1) & 3];
+    uint32_t r16 = (d & 1) ? (word >> 16) : (word & 0xffffu);
+    return (float)r16 * 1.52587890625e-05f; /* 2^-16, exact */
+}
+
+/* ------------------------------------------------------------------------- */
+
+static int width_ok(int b) { return b == 1 || b == 2 || b == 4 || b == 8; }
+
+int orc_packed_bytes(int64_t N, int64_t D, int32_t G, const uint8_t* bits,
+                     uint64_t* offsets, uint64_t* total)
+{
+    if (N <= 0 || D <= 0 || G <= 0 || (G % 8) != 0 || !bits) return ORC_EINVAL;
+    uint64_t ng = (uint64_t)((D + G - 1) / G);
+    uint64_t acc = 0;
+    for (int64_t n = 0; n < N; ++n) {
+        if (!width_ok(bits[n])) return ORC_EINVAL;
+        if (offsets) offsets[n] = acc;
+        acc += ng * (uint64_t)G * bits[n] / 8;
+    }
+    if (total) *total = acc;
+    return ORC_OK;
+}
+
+/* Sec. 4.1: zero point Z = min and range R = max - min of one group. */
+static void group_min_range(const void* x, int dtype, int64_t base, int64_t len,
+                            float* mn_out, float* range_out)
+{
+    float mn = load_elem(x, dtype, base);
+    float mx = mn;
+    for (int64_t j = 1; j < len; ++j) {
+        float v = load_elem(x, dtype, base + j);
+        if (v < mn) mn = v;
+        if (v > mx) mx = v;
+    }
+    mn = mn + 0.0f; /* -0.0 becomes +0.0: one canonical stored zero point */
+    *mn_out = mn;
+    *range_out = mx - mn;
+}
+
+int orc_group_stats(const void* x, int dtype, int64_t N, int64_t D, int32_t G,
+                    float* gmin, float* grange)
+{
+    if (!x || !gmin || !grange || N <= 0 || D <= 0 || G <= 0) return ORC_EINVAL;
+    int64_t ng = (D + G - 1) / G;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < N * ng; ++t) {
+        int64_t n = t / ng, g = t % ng;
+        int64_t len = (g * G + G <= D) ? G : D - g * G;
+        group_min_range(x, dtype, n * D + g * G, len, &gmin[t], &grange[t]);
+    }
+    return ORC_OK;
+}
+
+/* Sec. 4.1: the factor B / R of the scaling step and the stored step R / B.  A group
+ * whose range is zero, or so small that B / R overflows, is degenerate: both are 0,
+ * every code is 0 and dequantization returns Z. */
+static void group_scale(float B, float range, float* inv_out, float* scale_out)
+{
+    float inv = 0.0f, scale = 0.0f;
+    if (range != 0.0f) {
+        float cand = B / range;
+        if (isfinite(cand)) {
+            inv = cand;
+            scale = range / B;
+        }
+    }
+    *inv_out = inv;
+    *scale_out = scale;
+}
+
+/* Sec. 4.1: u = B (h - Z) / R in [0, B]; the code is ceil(u) with probability
+ * u - floor(u) and floor(u) otherwise, decided by comparing uniform noise with the
+ * fractional part. */
+static unsigned stochastic_code(float h, float mn, float inv, float B, float noise)
+{
+    float centred = h - mn;
+    float u = centred * inv;
+    if (u > B) u = B; /* the two roundings above can overshoot B by an ulp */
+    float fl = floorf(u);
+    float frac = u - fl; /* exact */
+    return (unsigned)fl + (noise < frac ? 1u : 0u);
+}
+
+/* Sec. 4.1: u = B (h - Z) / R scaled to [0, B], then stochastic rounding:
+ * ceil(u) with probability u - floor(u), floor(u) otherwise. */
+int orc_quantize_pack(const void* x, int dtype, int64_t N, int64_t D, int32_t G,
+                      const uint8_t* bits, const uint64_t* offsets,
+                      uint64_t seed, uint64_t tag, int32_t noise_bits,
+                      uint8_t* packed, float* header)
+{
+    if (!x || !bits || !offsets || !packed || !header) return ORC_EINVAL;
+    if (N <= 0 || D <= 0 || G <= 0 || (G % 8) != 0) return ORC_EINVAL;
+    if (noise_bits != 24 && noise_bits != 16) return ORC_EINVAL;
+    for (int64_t n = 0; n < N; ++n)
+        if (!width_ok(bits[n])) return ORC_EINVAL;
+    int64_t ng = (D + G - 1) / G;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < N * ng; ++t) {
+        int64_t n = t / ng, g = t % ng;
+        int b = bits[n];
+        float B = (float)((1 << b) - 1);
+        int64_t len = (g * G + G <= D) ? G : D - g * G;
+        float mn, range;
+        group_min_range(x, dtype, n * D + g * G, len, &mn, &range);
+
+        float inv, scale;
+        group_scale(B, range, &inv, &scale);
+        header[2 * t + 0] = mn;
+        header[2 * t + 1] = scale;
+
+        uint8_t* dst = packed + offsets[n] + (uint64_t)g * G * b / 8;
+        memset(dst, 0, (size_t)G * b / 8); /* padding codes of a ragged group are 0 */
+        for (int64_t j = 0; j < len; ++j) {
+            float h = load_elem(x, dtype, n * D + g * G + j);
+            float noise = orc_noise(seed, tag, (uint32_t)n, (uint64_t)(g * G + j), noise_bits);
+            unsigned code = stochastic_code(h, mn, inv, B, noise);
+            int64_t bitpos = j * b;
+            dst[bitpos / 8] |= (uint8_t)(code << (bitpos % 8));
+        }
+    }
+    return ORC_OK;
+}
+
+/* Sec. 4.1: h^ = code * R / B + Z with scale = R / B stored in the header. */
+int orc_unpack_dequantize(const uint8_t* packed, const float* header,
+                          const uint8_t* bits, const uint64_t* offsets,
+                          int64_t N, int64_t D, int32_t G, void* out, int out_dtype)
+{
+    if (!packed || !header || !bits || !offsets || !out) return ORC_EINVAL;
+    if (N <= 0 || D <= 0 || G <= 0 || (G % 8) != 0) return ORC_EINVAL;
+    for (int64_t n = 0; n < N; ++n)
+        if (!width_ok(bits[n])) return ORC_EINVAL;
+    int64_t ng = (D + G - 1) / G;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < N * ng; ++t) {
+        int64_t n = t / ng, g = t % ng;
+        int b = bits[n];
+        int64_t len = (g * G + G <= D) ? G : D - g * G;
+        float mn = header[2 * t + 0];
+        float scale = header[2 * t + 1];
+        const uint8_t* src = packed + offsets[n] + (uint64_t)g * G * b / 8;
+        for (int64_t j = 0; j < len; ++j) {
+            int64_t bitpos = j * b;
+            unsigned code = (src[bitpos / 8] >> (bitpos % 8)) & ((1u << b) - 1u);
+            float v = fmaf((float)code, scale, mn);
+            if (out_dtype == 0)
+                ((float*)out)[n * D + g * G + j] = v;
+            else
+                ((uint16_t*)out)[n * D + g * G + j] = orc_float_to_half(v);
+        }
+    }
+    return ORC_OK;
+}
+
+/* Codes alone (no packing), for tests that look at the rounding itself. */
+int orc_quantize_codes(const void* x, int dtype, int64_t N, int64_t D, int32_t G,
+                       const uint8_t* bits, uint64_t seed, uint64_t tag,
+                       int32_t noise_bits, uint8_t* codes)
+{
+    if (!x || !bits || !codes || N <= 0 || D <= 0 || G <= 0) return ORC_EINVAL;
+    int64_t ng = (D + G - 1) / G;
+    for (int64_t n = 0; n < N; ++n)
+        if (!width_ok(bits[n])) return ORC_EINVAL;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < N * ng; ++t) {
+        int64_t n = t / ng, g = t % ng;
+        float B = (float)((1 << bits[n]) - 1);
+        int64_t len = (g * G + G <= D) ? G : D - g * G;
+        float mn, range;
+        group_min_range(x, dtype, n * D + g * G, len, &mn, &range);
+        float inv, scale;
+        group_scale(B, range, &inv, &scale);
+        for (int64_t j = 0; j < len; ++j) {
+            float h = load_elem(x, dtype, n * D + g * G + j);
+            float noise = orc_noise(seed, tag, (uint32_t)n, (uint64_t)(g * G + j), noise_bits);
+            codes[n * D + g * G + j] = (uint8_t)stochastic_code(h, mn, inv, B, noise);
+        }
+    }
+    return ORC_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Sec. 4.3: start every item at 8 bits and keep applying the cheapest move    */
+/* until the budget of Prob. (9) holds.  A move is one rung of 8->4->2->1; its  */
+/* price is the variance added, w (1/B_new^2 - 1/B_old^2), per bit freed,       */
+/* D (b_old - b_new).  Plain repeated linear scan: no heap, no sort.           */
+
+static double move_price(float w, int64_t D, int b_now)
+{
+    double c;
+    if (b_now == 8) c = (1.0 / 225.0 - 1.0 / 65025.0) / 4.0;
+    else if (b_now == 4) c = (1.0 / 9.0 - 1.0 / 225.0) / 2.0;
+    else c = 1.0 - 1.0 / 9.0;
+    return ((double)w * c) / (double)D;
+}
+
+int orc_allocate_bits(const float* w, const int64_t* D, int64_t M,
+                      int64_t budget_bits, uint8_t* bits_out)
+{
+    if (!w || !D || !bits_out || M <= 0 || budget_bits < 0) return ORC_EINVAL;
+    for (int64_t i = 0; i < M; ++i)
+        if (!(w[i] >= 0.0f) || !isfinite(w[i]) || D[i] <= 0) return ORC_EINVAL;
+    /* 128-bit-safe enough: sum of D*8 stays far below 2^63 for any real tensor */
+    int64_t used = 0;
+    for (int64_t i = 0; i < M; ++i) {
+        bits_out[i] = 8;
+        used += 8 * D[i];
+    }
+    while (used > budget_bits) {
+        int64_t best = -1;
+        double best_price = 0.0;
+        for (int64_t i = 0; i < M; ++i) {
+            if (bits_out[i] == 1) continue;
+            double price = move_price(w[i], D[i], bits_out[i]);
+            if (best < 0 || price < best_price) { /* ties: the lowest index wins */
+                best = i;
+                best_price = price;
+            }
+        }
+        if (best < 0) return ORC_EINFEASIBLE; /* everything already at one bit */
+        int nb = bits_out[best] / 2;
+        used -= D[best] * (bits_out[best] - nb);
+        bits_out[best] = (uint8_t)nb;
+    }
+    return ORC_OK;
+}
+
+/* The objective of Prob. (9), sum_i w_i / B_i^2, in double precision. */
+double orc_objective(const float* w, const uint8_t* bits, int64_t M)
+{
+    double acc = 0.0;
+    for (int64_t i = 0; i < M; ++i) {
+        double B = (double)((1 << bits[i]) - 1);
+        acc += (double)w[i] / (B * B);
+    }
+    return acc;
+}

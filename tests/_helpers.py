@@ -1,0 +1,74 @@
+"""Small test-side utilities (no method arithmetic shared with the oracle or the kernels)."""
+from __future__ import annotations
+
+import os
+import shutil
+import subprocess
+from fractions import Fraction
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def round_fraction_to_f32(fr: Fraction) -> np.float32:
+    """Correctly rounded (nearest, ties to even) binary32 value of an exact rational."""
+    if fr == 0:
+        return np.float32(0.0)
+    cand = np.float32(float(fr))          # may be off by one ulp (double rounding)
+    best = None
+    for c in (np.nextafter(cand, np.float32(-np.inf)), cand, np.nextafter(cand, np.float32(np.inf))):
+        if not np.isfinite(c):
+            continue
+        err = abs(Fraction(float(c)) - fr)
+        even = (int(np.float32(c).view(np.uint32)) & 1) == 0
+        key = (err, 0 if even else 1)
+        if best is None or key < best[0]:
+            best = (key, c)
+    return np.float32(best[1])
+
+
+_WITNESS = None
+
+
+def philox_witness():
+    """Path of the compiled rocRAND host witness, or None when hipcc / rocRAND are absent."""
+    global _WITNESS
+    if _WITNESS is not None:
+        return _WITNESS or None
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    src = os.path.join(ROOT, "tests", "witness", "rocrand_philox_witness.cpp")
+    out = os.path.join(ROOT, "tests", "witness", "rocrand_philox_witness.bin")
+    if not os.path.exists(hipcc) or not os.path.exists("/opt/rocm/include/rocrand/rocrand_philox4x32_10.h"):
+        _WITNESS = ""
+        return None
+    if not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(src):
+        r = subprocess.run([hipcc, "--offload-host-only", "-O1", "-o", out, src],
+                           capture_output=True, text=True)
+        if r.returncode != 0:
+            _WITNESS = ""
+            return None
+    _WITNESS = out
+    return out
+
+
+def witness_words(queries):
+    """queries: list of (seed, subsequence, offset) -> uint32 array [len, 4] from rocRAND."""
+    exe = philox_witness()
+    assert exe is not None
+    text = "".join(f"{s:#x} {sub:#x} {off:#x}\n" for s, sub, off in queries)
+    r = subprocess.run([exe], input=text, capture_output=True, text=True, check=True)
+    rows = [[int(t, 16) for t in line.split()] for line in r.stdout.strip().splitlines()]
+    return np.array(rows, dtype=np.uint32).reshape(len(queries), 4)
+
+
+def witness_noise_words(seed: int, tag: int, n: int, counter0: int) -> np.ndarray:
+    """The four Philox words at counter (counter0, n, lo32(tag), hi32(tag)), key = seed.
+
+    rocRAND's state is a 128-bit counter whose low 64 bits advance by offset/4 and whose
+    high 64 bits hold the subsequence, and its key is the seed: so subsequence = tag and
+    offset = 4 * (counter0 + n * 2^32).
+    """
+    off = 4 * (counter0 + (n << 32))
+    assert off < (1 << 64)
+    return witness_words([(seed, tag, off)])[0]
