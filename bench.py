@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the activation-compression hot path on one MI355X.
+
+One *step* is one pass of the whole path over one batch that is already resident in HBM:
+  group_stats  ->  allocate_bits (host, greedy)  ->  quantize_pack  ->  unpack_dequantize.
+The default workload is the ResNet-50 stage-1 post-ReLU activation, fp32 [128,256,56,56],
+G = 256, per-sample widths in {1,2,4,8} averaging 2.0 bits.  `value` is input-activation
+bytes per second through the whole step; the per-kernel figures and the HBM roofline of
+the slowest kernel are reported beside it, and the CPU oracle is timed as a baseline.
+
+Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=30)
+    p.add_argument("--warmup", type=int, default=5)
+    p.add_argument("--workload", default="r50_stage1", choices=["r50_stage1", "tiny", "r50_stem_f16", "fpn"])
+    p.add_argument("--noise-bits", type=int, default=24, choices=[24, 16])
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    return p.parse_args()
+
+
+def algorithmic_bytes(N, D, ng, elem_bytes, code_bytes):
+    """Bytes each kernel must move per launch: input or output tensor, bit stream, 8-byte headers."""
+    tensor = N * D * elem_bytes
+    hdr = N * ng * 8
+    return {
+        "group_stats": tensor + hdr,
+        "quantize_pack": tensor + code_bytes + hdr,
+        "unpack_dequantize": code_bytes + hdr + tensor,
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (the path shards with no exchange; "
+              "see DESIGN.md); --gpus N with N > 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2104_14129_amd import binding as B
+    from paper_2104_14129_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    wl = {"r50_stage1": synth.r50_stage1, "tiny": synth.tiny, "r50_stem_f16": synth.r50_stem_f16,
+          "fpn": synth.fpn}[args.workload]()
+    N, D, ng, G = wl.N, wl.D, wl.ng, wl.G
+    x_np = synth.make_input(wl).reshape(N, D)
+    x = torch.from_numpy(x_np).to(dev)
+
+    # sensitivities whose greedy allocation at a 2.0-bit budget is the workload's width multiset
+    w_host = synth.tiered_sensitivities(wl.bits, seed=7)
+    D_host = np.full(N, D, dtype=np.int64)
+    budget = int(round(float(wl.bits.astype(np.float64).mean()) * N * D))
+
+    gmin = torch.empty((N, ng), dtype=torch.float32, device=dev)
+    grange = torch.empty((N, ng), dtype=torch.float32, device=dev)
+    _, worst_total = B.packed_bytes(N, D, np.full(N, 8, dtype=np.uint8), G)
+    packed_buf = torch.empty(worst_total, dtype=torch.uint8, device=dev)
+    header = torch.empty((N, ng, 2), dtype=torch.float32, device=dev)
+    out = torch.empty((N, D), dtype=x.dtype, device=dev)
+    bits_pin = torch.empty(N, dtype=torch.uint8, pin_memory=True)
+    offs_pin = torch.empty(N, dtype=torch.int64, pin_memory=True)
+    bits_dev = torch.empty(N, dtype=torch.uint8, device=dev)
+    offs_dev = torch.empty(N, dtype=torch.int64, device=dev)
+    stream = torch.cuda.current_stream()
+
+    state = {}
+
+    def step(events=None):
+        def mark(name, when):
+            if events is not None:
+                e = torch.cuda.Event(enable_timing=True)
+                e.record(stream)
+                events.setdefault(name, []).append((when, e))
+
+        mark("group_stats", 0)
+        B.group_stats(x, gmin, grange, G, stream=stream)
+        mark("group_stats", 1)
+        bits = B.allocate_bits(w_host, D_host, budget)
+        offsets, total = B.packed_bytes(N, D, bits, G)
+        bits_pin.numpy()[:] = bits
+        offs_pin.numpy()[:] = offsets.view(np.int64)
+        bits_dev.copy_(bits_pin, non_blocking=True)
+        offs_dev.copy_(offs_pin, non_blocking=True)
+        packed = packed_buf[:total]
+        mark("quantize_pack", 0)
+        B.quantize_pack(x, bits_dev, offs_dev, packed, header, wl.philox_seed, wl.tag, args.noise_bits, G, stream=stream)
+        mark("quantize_pack", 1)
+        mark("unpack_dequantize", 0)
+        B.unpack_dequantize(packed, header, bits_dev, offs_dev, out, G, stream=stream)
+        mark("unpack_dequantize", 1)
+        state["bits"], state["total"] = bits, total
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    assert np.array_equal(state["bits"], wl.bits), "allocator did not return the workload's widths"
+
+    events = {}
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    kernel_ms = {}
+    for name, marks in events.items():
+        starts = [e for when, e in marks if when == 0]
+        stops = [e for when, e in marks if when == 1]
+        kernel_ms[name] = float(np.mean([a.elapsed_time(b) for a, b in zip(starts, stops)]))
+
+    in_bytes = N * D * wl.elem_bytes
+    alg = algorithmic_bytes(N, D, ng, wl.elem_bytes, state["total"])
+    per_kernel = {k: {"ms": kernel_ms[k], "input_GBps": in_bytes / kernel_ms[k] / 1e6,
+                      "algorithmic_GBps": alg[k] / kernel_ms[k] / 1e6,
+                      "frac_of_hbm_peak": alg[k] / kernel_ms[k] / 1e6 / HBM_PEAK_GBS} for k in kernel_ms}
+    dominant = max(kernel_ms, key=kernel_ms.get)
+    achieved = alg[dominant] / kernel_ms[dominant] / 1e6
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                "algorithmic_bytes_per_launch": alg[dominant], "avg_launch_ms": kernel_ms[dominant]}
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        import oracle
+        t = time.perf_counter()
+        oracle.group_stats(x_np, G)
+        opacked, oheader, ooff = oracle.quantize_pack(x_np, wl.bits, wl.philox_seed, wl.tag, G, args.noise_bits)
+        oracle.unpack_dequantize(opacked, oheader, wl.bits, ooff, N, D, G, out_dtype=x_np.dtype)
+        cpu_s = time.perf_counter() - t
+        cpu_baseline = {"value": in_bytes / cpu_s / 1e9, "unit": "GB/s", "cores": oracle.threads(),
+                        "kind": "oracle",
+                        "sample": f"one full step (group_stats + quantize_pack + unpack_dequantize) on the whole "
+                                  f"workload, {N * D} elements, {cpu_s:.2f} s"}
+
+    result = {
+        "metric": "quantize+pack and unpack+dequant GB/s (fp32 input); % of HBM peak",
+        "value": in_bytes / (ms_per_step * 1e-3) / 1e9,
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": wl.dtype,
+        "data": "synthetic",
+        "config": {"workload": wl.name, "G": G, "mean_bits": float(wl.bits.astype(np.float64).mean()),
+                   "noise_bits": args.noise_bits,
+                   "step": "group_stats + allocate_bits(host) + quantize_pack + unpack_dequantize"},
+        "kernels": per_kernel,
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+    }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

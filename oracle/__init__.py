@@ -60,6 +60,10 @@ def lib() -> ctypes.CDLL:
         L.orc_group_stats.argtypes = [vp, c.c_int, i64, i64, i32, vp, vp]
         L.orc_quantize_pack.restype = c.c_int
         L.orc_quantize_pack.argtypes = [vp, c.c_int, i64, i64, i32, vp, vp, u64, u64, i32, vp, vp]
+        L.orc_quantize_group.restype = c.c_int
+        L.orc_quantize_group.argtypes = [vp, c.c_int, i64, i64, i32, c.c_int, u64, u64, c.c_uint32, u64, i32, vp, vp]
+        L.orc_dequantize_group.restype = c.c_int
+        L.orc_dequantize_group.argtypes = [vp, vp, c.c_int, i64, vp, c.c_int, i64]
         L.orc_quantize_codes.restype = c.c_int
         L.orc_quantize_codes.argtypes = [vp, c.c_int, i64, i64, i32, vp, u64, u64, i32, vp]
         L.orc_unpack_dequantize.restype = c.c_int
@@ -168,6 +172,30 @@ def quantize_pack(x: np.ndarray, bits, seed: int, tag: int = 0, G: int = 256,
     if rc != OK:
         raise OracleError(rc, "quantize_pack")
     return packed, header, offsets
+
+
+def quantize_group(xg: np.ndarray, b: int, seed: int, tag: int, n: int, d_start: int,
+                   G: int = 256, noise_bits: int = 24):
+    """One group (len(xg) <= G valid elements of sample n starting at feature d_start):
+    returns (bytes uint8[G*b/8], header float32[2])."""
+    xg = np.ascontiguousarray(xg).reshape(-1)
+    dst = np.zeros(G * b // 8, dtype=np.uint8)
+    hd = np.zeros(2, dtype=np.float32)
+    rc = lib().orc_quantize_group(_p(xg), _dtype_code(xg), 0, xg.size, G, b, seed, tag, n, d_start,
+                                  noise_bits, _p(dst), _p(hd))
+    if rc != OK:
+        raise OracleError(rc, "quantize_group")
+    return dst, hd
+
+
+def dequantize_group(src: np.ndarray, hd: np.ndarray, b: int, length: int, out_dtype=np.float32) -> np.ndarray:
+    src = np.ascontiguousarray(src, dtype=np.uint8)
+    hd = np.ascontiguousarray(hd, dtype=np.float32)
+    out = np.empty(length, dtype=out_dtype)
+    rc = lib().orc_dequantize_group(_p(src), _p(hd), b, length, _p(out), _dtype_code(out), 0)
+    if rc != OK:
+        raise OracleError(rc, "dequantize_group")
+    return out
 
 
 def quantize_codes(x: np.ndarray, bits, seed: int, tag: int = 0, G: int = 256,

@@ -206,6 +206,33 @@ static unsigned stochastic_code(float h, float mn, float inv, float B, float noi
 
 /* Sec. 4.1: u = B (h - Z) / R scaled to [0, B], then stochastic rounding:
  * ceil(u) with probability u - floor(u), floor(u) otherwise. */
+/* One group: `len` valid elements starting at element index `first` of buffer x, being
+ * features d_start .. d_start+len-1 of sample n.  Writes G*b/8 bytes of bit stream (the
+ * padding codes of a ragged group are 0) and the two header floats (Z, R / B). */
+int orc_quantize_group(const void* x, int dtype, int64_t first, int64_t len, int32_t G, int b,
+                       uint64_t seed, uint64_t tag, uint32_t n, uint64_t d_start,
+                       int32_t noise_bits, uint8_t* dst, float* header2)
+{
+    if (!x || !dst || !header2 || len <= 0 || len > G || !width_ok(b)) return ORC_EINVAL;
+    if (noise_bits != 24 && noise_bits != 16) return ORC_EINVAL;
+    float B = (float)((1 << b) - 1);
+    float mn, range;
+    group_min_range(x, dtype, first, len, &mn, &range);
+    float inv, scale;
+    group_scale(B, range, &inv, &scale);
+    header2[0] = mn;
+    header2[1] = scale;
+    memset(dst, 0, (size_t)G * b / 8);
+    for (int64_t j = 0; j < len; ++j) {
+        float h = load_elem(x, dtype, first + j);
+        float noise = orc_noise(seed, tag, n, d_start + (uint64_t)j, noise_bits);
+        unsigned code = stochastic_code(h, mn, inv, B, noise);
+        int64_t bitpos = j * b;
+        dst[bitpos / 8] |= (uint8_t)(code << (bitpos % 8));
+    }
+    return ORC_OK;
+}
+
 int orc_quantize_pack(const void* x, int dtype, int64_t N, int64_t D, int32_t G,
                       const uint8_t* bits, const uint64_t* offsets,
                       uint64_t seed, uint64_t tag, int32_t noise_bits,
@@ -221,25 +248,28 @@ int orc_quantize_pack(const void* x, int dtype, int64_t N, int64_t D, int32_t G,
     for (int64_t t = 0; t < N * ng; ++t) {
         int64_t n = t / ng, g = t % ng;
         int b = bits[n];
-        float B = (float)((1 << b) - 1);
         int64_t len = (g * G + G <= D) ? G : D - g * G;
-        float mn, range;
-        group_min_range(x, dtype, n * D + g * G, len, &mn, &range);
-
-        float inv, scale;
-        group_scale(B, range, &inv, &scale);
-        header[2 * t + 0] = mn;
-        header[2 * t + 1] = scale;
-
         uint8_t* dst = packed + offsets[n] + (uint64_t)g * G * b / 8;
-        memset(dst, 0, (size_t)G * b / 8); /* padding codes of a ragged group are 0 */
-        for (int64_t j = 0; j < len; ++j) {
-            float h = load_elem(x, dtype, n * D + g * G + j);
-            float noise = orc_noise(seed, tag, (uint32_t)n, (uint64_t)(g * G + j), noise_bits);
-            unsigned code = stochastic_code(h, mn, inv, B, noise);
-            int64_t bitpos = j * b;
-            dst[bitpos / 8] |= (uint8_t)(code << (bitpos % 8));
-        }
+        orc_quantize_group(x, dtype, n * D + g * G, len, G, b, seed, tag, (uint32_t)n,
+                           (uint64_t)(g * G), noise_bits, dst, &header[2 * t]);
+    }
+    return ORC_OK;
+}
+
+/* One group of the backward pass: `len` values from G*b/8 bytes and (Z, scale). */
+int orc_dequantize_group(const uint8_t* src, const float* header2, int b, int64_t len,
+                         void* out, int out_dtype, int64_t first)
+{
+    if (!src || !header2 || !out || len <= 0 || !width_ok(b)) return ORC_EINVAL;
+    float mn = header2[0], scale = header2[1];
+    for (int64_t j = 0; j < len; ++j) {
+        int64_t bitpos = j * b;
+        unsigned code = (src[bitpos / 8] >> (bitpos % 8)) & ((1u << b) - 1u);
+        float v = fmaf((float)code, scale, mn);
+        if (out_dtype == 0)
+            ((float*)out)[first + j] = v;
+        else
+            ((uint16_t*)out)[first + j] = orc_float_to_half(v);
     }
     return ORC_OK;
 }
@@ -259,18 +289,8 @@ int orc_unpack_dequantize(const uint8_t* packed, const float* header,
         int64_t n = t / ng, g = t % ng;
         int b = bits[n];
         int64_t len = (g * G + G <= D) ? G : D - g * G;
-        float mn = header[2 * t + 0];
-        float scale = header[2 * t + 1];
         const uint8_t* src = packed + offsets[n] + (uint64_t)g * G * b / 8;
-        for (int64_t j = 0; j < len; ++j) {
-            int64_t bitpos = j * b;
-            unsigned code = (src[bitpos / 8] >> (bitpos % 8)) & ((1u << b) - 1u);
-            float v = fmaf((float)code, scale, mn);
-            if (out_dtype == 0)
-                ((float*)out)[n * D + g * G + j] = v;
-            else
-                ((uint16_t*)out)[n * D + g * G + j] = orc_float_to_half(v);
-        }
+        orc_dequantize_group(src, &header[2 * t], b, len, out, out_dtype, n * D + g * G);
     }
     return ORC_OK;
 }

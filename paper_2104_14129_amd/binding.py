@@ -1,0 +1,185 @@
+"""ctypes binding of libactq's C ABI (include/actq.h): argument marshalling only.
+
+Every function takes torch tensors (device memory and streams are PyTorch's) or numpy
+arrays for the host-side calls, checks dtypes / contiguity, and forwards raw pointers.
+There is no CPU fallback: if the HIP library cannot be loaded the import of the symbols
+fails with an error.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libactq.so")
+
+ACTQ_OK, ACTQ_EINVAL, ACTQ_EINFEASIBLE, ACTQ_EHIP = 0, -1, -2, -3
+ACTQ_F32, ACTQ_F16 = 0, 1
+G_DEFAULT = 256
+
+EXPORTS = ("actq_version", "actq_last_error", "actq_packed_bytes", "actq_group_stats",
+           "actq_quantize_pack", "actq_unpack_dequantize", "actq_allocate_bits")
+
+
+class ActqError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"libactq error {code}: {message}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads libactq.so (building it first only when no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from . import build as _build
+        _build.build()
+    L = ctypes.CDLL(LIB_PATH)
+    c = ctypes
+    vp, i64, i32, u64 = c.c_void_p, c.c_int64, c.c_int32, c.c_uint64
+    L.actq_version.restype = c.c_int
+    L.actq_version.argtypes = []
+    L.actq_last_error.restype = c.c_char_p
+    L.actq_last_error.argtypes = []
+    L.actq_packed_bytes.restype = c.c_int
+    L.actq_packed_bytes.argtypes = [i64, i64, i32, vp, vp, vp]
+    L.actq_group_stats.restype = c.c_int
+    L.actq_group_stats.argtypes = [vp, c.c_int, i64, i64, i32, vp, vp, vp]
+    L.actq_quantize_pack.restype = c.c_int
+    L.actq_quantize_pack.argtypes = [vp, c.c_int, i64, i64, i32, vp, vp, u64, u64, i32, vp, u64, vp, vp]
+    L.actq_unpack_dequantize.restype = c.c_int
+    L.actq_unpack_dequantize.argtypes = [vp, u64, vp, vp, vp, i64, i64, i32, vp, c.c_int, vp]
+    L.actq_allocate_bits.restype = c.c_int
+    L.actq_allocate_bits.argtypes = [vp, vp, i64, i64, vp]
+    _lib = L
+    return L
+
+
+def _check(rc: int) -> None:
+    if rc != ACTQ_OK:
+        raise ActqError(rc, lib().actq_last_error().decode())
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _dtype_code(t) -> int:
+    torch = _torch()
+    if t.dtype == torch.float32:
+        return ACTQ_F32
+    if t.dtype == torch.float16:
+        return ACTQ_F16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _dev(t, dtype=None, name="tensor"):
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    torch = _torch()
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream
+
+
+def _view2d(x):
+    return int(x.shape[0]), int(x.numel() // x.shape[0])
+
+
+def version() -> int:
+    return lib().actq_version()
+
+
+def last_error() -> str:
+    return lib().actq_last_error().decode()
+
+
+def packed_bytes(N: int, D: int, bits_host, G: int = G_DEFAULT):
+    """Host: (offsets uint64[N], total bytes) of the bit stream for widths bits_host."""
+    bits = np.ascontiguousarray(bits_host, dtype=np.uint8)
+    if bits.shape != (N,):
+        raise ValueError("bits must have shape [N]")
+    offsets = np.zeros(N, dtype=np.uint64)
+    total = ctypes.c_uint64(0)
+    _check(lib().actq_packed_bytes(N, D, G, bits.ctypes.data, offsets.ctypes.data, ctypes.addressof(total)))
+    return offsets, int(total.value)
+
+
+def group_stats(x, gmin=None, grange=None, G: int = G_DEFAULT, stream=None):
+    """Device: per-group (min, range) of x viewed as [N, D]; returns float32 [N, ng] tensors."""
+    torch = _torch()
+    N, D = _view2d(x)
+    ng = (D + G - 1) // G
+    if gmin is None:
+        gmin = torch.empty((N, ng), dtype=torch.float32, device=x.device)
+    if grange is None:
+        grange = torch.empty((N, ng), dtype=torch.float32, device=x.device)
+    if gmin.numel() != N * ng or grange.numel() != N * ng:
+        raise ValueError("gmin / grange must hold N*ng floats")
+    _check(lib().actq_group_stats(_dev(x, name="x"), _dtype_code(x), N, D, G,
+                                  _dev(gmin, torch.float32, "gmin"), _dev(grange, torch.float32, "grange"),
+                                  _stream(stream)))
+    return gmin, grange
+
+
+def quantize_pack(x, bits, offsets, packed, header, seed: int, tag: int = 0, noise_bits: int = 24,
+                  G: int = G_DEFAULT, stream=None):
+    """Device: writes the bit stream into `packed` (uint8) and (Z, scale) into `header`."""
+    torch = _torch()
+    N, D = _view2d(x)
+    ng = (D + G - 1) // G
+    if bits.numel() != N or offsets.numel() != N:
+        raise ValueError("bits and offsets must have N entries")
+    if header.numel() != N * ng * 2:
+        raise ValueError("header must hold N*ng*2 floats")
+    _check(lib().actq_quantize_pack(_dev(x, name="x"), _dtype_code(x), N, D, G,
+                                    _dev(bits, torch.uint8, "bits"), _dev(offsets, torch.int64, "offsets"),
+                                    seed & (2 ** 64 - 1), tag & (2 ** 64 - 1), noise_bits,
+                                    _dev(packed, torch.uint8, "packed"), packed.numel(),
+                                    _dev(header, torch.float32, "header"), _stream(stream)))
+    return packed, header
+
+
+def unpack_dequantize(packed, header, bits, offsets, out, G: int = G_DEFAULT, stream=None):
+    """Device: reconstructs `out` ([N, ...] float32 or float16) from the bit stream."""
+    torch = _torch()
+    N, D = _view2d(out)
+    ng = (D + G - 1) // G
+    if bits.numel() != N or offsets.numel() != N:
+        raise ValueError("bits and offsets must have N entries")
+    if header.numel() != N * ng * 2:
+        raise ValueError("header must hold N*ng*2 floats")
+    _check(lib().actq_unpack_dequantize(_dev(packed, torch.uint8, "packed"), packed.numel(),
+                                        _dev(header, torch.float32, "header"),
+                                        _dev(bits, torch.uint8, "bits"), _dev(offsets, torch.int64, "offsets"),
+                                        N, D, G, _dev(out, name="out"), _dtype_code(out), _stream(stream)))
+    return out
+
+
+def allocate_bits(w_host, D_host, budget_bits: int) -> np.ndarray:
+    """Host: greedy widths in {1,2,4,8} for sensitivities w and sizes D under a bit budget."""
+    w = np.ascontiguousarray(w_host, dtype=np.float32)
+    D = np.ascontiguousarray(D_host, dtype=np.int64)
+    if w.ndim != 1 or D.shape != w.shape:
+        raise ValueError("w and D must be 1-D arrays of equal length")
+    bits = np.zeros(w.shape[0], dtype=np.uint8)
+    rc = lib().actq_allocate_bits(w.ctypes.data, D.ctypes.data, w.shape[0], int(budget_bits), bits.ctypes.data)
+    if rc != ACTQ_OK:
+        err = ActqError(rc, lib().actq_last_error().decode())
+        err.bits = bits
+        raise err
+    return bits

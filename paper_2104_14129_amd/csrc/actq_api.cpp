@@ -1,0 +1,177 @@
+// Host side of libactq: argument validation, size arithmetic, the greedy bit allocator,
+// and the extern "C" entry points declared in actq.h.  Nothing here touches the GPU
+// except through the launchers of the kernel file.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <queue>
+#include <utility>
+#include <vector>
+
+#include "actq_internal.h"
+
+namespace actq {
+
+static thread_local char g_error[512] = "";
+
+int fail(int code, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof(g_error), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+static bool width_ok(unsigned b) { return b == 1 || b == 2 || b == 4 || b == 8; }
+
+static bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// Shape checks common to the three device calls.
+static int check_view(const char* who, int64_t N, int64_t D, int32_t G)
+{
+    if (N <= 0 || D <= 0) return fail(ACTQ_EINVAL, "%s: N and D must be positive (N=%lld, D=%lld)", who, (long long)N, (long long)D);
+    if (G != kGroup) return fail(ACTQ_EINVAL, "%s: unsupported group size G=%d (only %d)", who, G, kGroup);
+    if (N >= (int64_t(1) << 32)) return fail(ACTQ_EINVAL, "%s: N must be below 2^32", who);
+    if (D >= (int64_t(1) << 34)) return fail(ACTQ_EINVAL, "%s: D must be below 2^34", who);
+    int64_t ng = (D + G - 1) / G;
+    // total groups and total elements must fit the 64-bit index arithmetic comfortably
+    if (N > (int64_t(1) << 62) / (ng * G)) return fail(ACTQ_EINVAL, "%s: N*D too large", who);
+    return ACTQ_OK;
+}
+
+static int check_dtype(const char* who, int dt)
+{
+    if (dt != ACTQ_F32 && dt != ACTQ_F16) return fail(ACTQ_EINVAL, "%s: unknown dtype %d", who, dt);
+    return ACTQ_OK;
+}
+
+}  // namespace actq
+
+using namespace actq;
+
+extern "C" {
+
+int actq_version(void) { return 100; }
+
+const char* actq_last_error(void) { return g_error; }
+
+int actq_packed_bytes(int64_t N, int64_t D, int32_t G, const uint8_t* bits_host,
+                      uint64_t* offsets_host, uint64_t* total_host)
+{
+    if (int rc = check_view("actq_packed_bytes", N, D, G)) return rc;
+    if (!bits_host) return fail(ACTQ_EINVAL, "actq_packed_bytes: bits_host is null");
+    if (!offsets_host && !total_host) return fail(ACTQ_EINVAL, "actq_packed_bytes: both outputs are null");
+    const uint64_t ng = static_cast<uint64_t>((D + G - 1) / G);
+    const uint64_t group_bytes_per_bit = static_cast<uint64_t>(G) / 8;
+    for (int64_t n = 0; n < N; ++n)
+        if (!width_ok(bits_host[n]))
+            return fail(ACTQ_EINVAL, "actq_packed_bytes: bits[%lld]=%u is not one of 1,2,4,8", (long long)n, bits_host[n]);
+    uint64_t acc = 0;
+    for (int64_t n = 0; n < N; ++n) {
+        if (offsets_host) offsets_host[n] = acc;
+        acc += ng * group_bytes_per_bit * bits_host[n];
+    }
+    if (total_host) *total_host = acc;
+    return ACTQ_OK;
+}
+
+int actq_group_stats(const void* x, actq_dtype dt, int64_t N, int64_t D, int32_t G,
+                     float* gmin, float* grange, void* stream)
+{
+    if (int rc = check_view("actq_group_stats", N, D, G)) return rc;
+    if (int rc = check_dtype("actq_group_stats", dt)) return rc;
+    if (!x || !gmin || !grange) return fail(ACTQ_EINVAL, "actq_group_stats: null pointer");
+    if (!aligned(x, 16)) return fail(ACTQ_EINVAL, "actq_group_stats: x must be 16-byte aligned");
+    if (!aligned(gmin, 4) || !aligned(grange, 4)) return fail(ACTQ_EINVAL, "actq_group_stats: outputs must be 4-byte aligned");
+    return launch_group_stats(x, dt, N, D, gmin, grange, stream);
+}
+
+int actq_quantize_pack(const void* x, actq_dtype dt, int64_t N, int64_t D, int32_t G,
+                       const uint8_t* bits, const uint64_t* offsets, uint64_t seed,
+                       uint64_t tag, int32_t noise_bits, void* packed,
+                       uint64_t packed_capacity, float* header, void* stream)
+{
+    if (int rc = check_view("actq_quantize_pack", N, D, G)) return rc;
+    if (int rc = check_dtype("actq_quantize_pack", dt)) return rc;
+    if (!x || !bits || !offsets || !packed || !header) return fail(ACTQ_EINVAL, "actq_quantize_pack: null pointer");
+    if (noise_bits != 24 && noise_bits != 16) return fail(ACTQ_EINVAL, "actq_quantize_pack: noise_bits must be 24 or 16, got %d", noise_bits);
+    if (!aligned(x, 16)) return fail(ACTQ_EINVAL, "actq_quantize_pack: x must be 16-byte aligned");
+    if (!aligned(packed, 16)) return fail(ACTQ_EINVAL, "actq_quantize_pack: packed must be 16-byte aligned");
+    if (!aligned(header, 8)) return fail(ACTQ_EINVAL, "actq_quantize_pack: header must be 8-byte aligned");
+    if (!aligned(offsets, 8)) return fail(ACTQ_EINVAL, "actq_quantize_pack: offsets must be 8-byte aligned");
+    const uint64_t ng = static_cast<uint64_t>((D + G - 1) / G);
+    if (packed_capacity < static_cast<uint64_t>(N) * ng * (G / 8))
+        return fail(ACTQ_EINVAL, "actq_quantize_pack: packed_capacity %llu is below one bit per element", (unsigned long long)packed_capacity);
+    return launch_quantize_pack(x, dt, N, D, bits, offsets, seed, tag, noise_bits, packed,
+                                packed_capacity, header, stream);
+}
+
+int actq_unpack_dequantize(const void* packed, uint64_t packed_capacity, const float* header,
+                           const uint8_t* bits, const uint64_t* offsets, int64_t N, int64_t D,
+                           int32_t G, void* out, actq_dtype out_dt, void* stream)
+{
+    if (int rc = check_view("actq_unpack_dequantize", N, D, G)) return rc;
+    if (int rc = check_dtype("actq_unpack_dequantize", out_dt)) return rc;
+    if (!packed || !header || !bits || !offsets || !out) return fail(ACTQ_EINVAL, "actq_unpack_dequantize: null pointer");
+    if (!aligned(out, 16)) return fail(ACTQ_EINVAL, "actq_unpack_dequantize: out must be 16-byte aligned");
+    if (!aligned(packed, 16)) return fail(ACTQ_EINVAL, "actq_unpack_dequantize: packed must be 16-byte aligned");
+    if (!aligned(header, 8)) return fail(ACTQ_EINVAL, "actq_unpack_dequantize: header must be 8-byte aligned");
+    if (!aligned(offsets, 8)) return fail(ACTQ_EINVAL, "actq_unpack_dequantize: offsets must be 8-byte aligned");
+    return launch_unpack_dequantize(packed, packed_capacity, header, bits, offsets, N, D, out,
+                                    out_dt, stream);
+}
+
+// Greedy allocator of Sec. 4.3 on the ladder 8 -> 4 -> 2 -> 1.  The heap holds, for
+// every item that can still be lowered, the price of its next move; ties go to the
+// lowest item index.  An item's successive prices strictly increase, so popping the
+// cheapest move and pushing the item's next one visits moves in globally sorted order.
+int actq_allocate_bits(const float* w, const int64_t* D, int64_t M, int64_t budget_bits,
+                       uint8_t* bits_out)
+{
+    if (!w || !D || !bits_out) return fail(ACTQ_EINVAL, "actq_allocate_bits: null pointer");
+    if (M <= 0) return fail(ACTQ_EINVAL, "actq_allocate_bits: M must be positive");
+    if (budget_bits < 0) return fail(ACTQ_EINVAL, "actq_allocate_bits: negative budget");
+    __int128 used = 0;
+    for (int64_t i = 0; i < M; ++i) {
+        if (!(w[i] >= 0.0f) || !std::isfinite(w[i]))
+            return fail(ACTQ_EINVAL, "actq_allocate_bits: w[%lld] must be finite and >= 0", (long long)i);
+        if (D[i] <= 0) return fail(ACTQ_EINVAL, "actq_allocate_bits: D[%lld] must be positive", (long long)i);
+        used += static_cast<__int128>(D[i]) * 8;
+    }
+    // variance added per bit freed, for a unit of w / D
+    const double step_price[3] = {
+        (1.0 / 225.0 - 1.0 / 65025.0) / 4.0,  // 8 -> 4
+        (1.0 / 9.0 - 1.0 / 225.0) / 2.0,      // 4 -> 2
+        1.0 - 1.0 / 9.0,                      // 2 -> 1
+    };
+    auto price = [&](int64_t i, int b_now) {
+        const double c = b_now == 8 ? step_price[0] : (b_now == 4 ? step_price[1] : step_price[2]);
+        return (static_cast<double>(w[i]) * c) / static_cast<double>(D[i]);
+    };
+    for (int64_t i = 0; i < M; ++i) bits_out[i] = 8;
+    const __int128 budget = budget_bits;
+    if (used <= budget) return ACTQ_OK;
+
+    using Move = std::pair<double, int64_t>;  // (price, item): lexicographic order is the rule
+    std::vector<Move> init;
+    init.reserve(static_cast<size_t>(M));
+    for (int64_t i = 0; i < M; ++i) init.emplace_back(price(i, 8), i);
+    std::priority_queue<Move, std::vector<Move>, std::greater<Move>> heap(std::greater<Move>(), std::move(init));
+    while (used > budget) {
+        if (heap.empty()) {
+            return fail(ACTQ_EINFEASIBLE, "actq_allocate_bits: budget %lld is below one bit per element", (long long)budget_bits);
+        }
+        const int64_t i = heap.top().second;
+        heap.pop();
+        const int b_now = bits_out[i];
+        const int b_new = b_now / 2;
+        used -= static_cast<__int128>(D[i]) * (b_now - b_new);
+        bits_out[i] = static_cast<uint8_t>(b_new);
+        if (b_new > 1) heap.emplace(price(i, b_new), i);
+    }
+    return ACTQ_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,29 @@
+// Internal declarations shared by the host-side API file and the kernel file of libactq.
+#ifndef ACTQ_INTERNAL_H
+#define ACTQ_INTERNAL_H
+
+#include <cstdint>
+
+#include "actq.h"
+
+namespace actq {
+
+constexpr int kGroup = 256;  // the one supported group size: one wavefront x 4 elements
+
+// Records a message for actq_last_error() and returns `code`.
+int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+
+// Launchers (kernels file).  Arguments are already validated.  Each returns ACTQ_OK or
+// ACTQ_EHIP after recording the HIP error text.
+int launch_group_stats(const void* x, int dtype, int64_t N, int64_t D, float* gmin,
+                       float* grange, void* stream);
+int launch_quantize_pack(const void* x, int dtype, int64_t N, int64_t D, const uint8_t* bits,
+                         const uint64_t* offsets, uint64_t seed, uint64_t tag, int noise_bits,
+                         void* packed, uint64_t capacity, float* header, void* stream);
+int launch_unpack_dequantize(const void* packed, uint64_t capacity, const float* header,
+                             const uint8_t* bits, const uint64_t* offsets, int64_t N,
+                             int64_t D, void* out, int out_dtype, void* stream);
+
+}  // namespace actq
+
+#endif

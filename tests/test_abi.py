@@ -1,0 +1,129 @@
+"""The C ABI library loads, exports every symbol declared in include/actq.h, and rejects
+bad arguments on the host before any launch (no GPU needed: nothing here computes)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2104_14129_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x1000  # a non-null, 16-byte aligned address that is never dereferenced by validation
+
+
+def test_every_declared_symbol_is_exported():
+    header = open(os.path.join(ROOT, "include", "actq.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(actq_[a-z_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS)
+    L = B.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert B.version() >= 100
+
+
+def test_packed_bytes_and_its_errors():
+    off, total = B.packed_bytes(4, 1000, [1, 2, 4, 8])
+    assert list(off) == [0, 128, 384, 896] and total == 1920
+    with pytest.raises(B.ActqError) as e:
+        B.packed_bytes(2, 512, [2, 3])
+    assert e.value.code == B.ACTQ_EINVAL and "bits[1]" in str(e.value)
+    L = B.lib()
+    bits = np.array([2], dtype=np.uint8)
+    tot = ctypes.c_uint64()
+    assert L.actq_packed_bytes(1, 512, 128, bits.ctypes.data, None, ctypes.addressof(tot)) == B.ACTQ_EINVAL
+    assert "group size" in B.last_error()
+    assert L.actq_packed_bytes(0, 512, 256, bits.ctypes.data, None, ctypes.addressof(tot)) == B.ACTQ_EINVAL
+    assert L.actq_packed_bytes(1, 512, 256, bits.ctypes.data, None, None) == B.ACTQ_EINVAL
+    assert L.actq_packed_bytes(1, 512, 256, None, None, ctypes.addressof(tot)) == B.ACTQ_EINVAL
+
+
+def test_device_calls_validate_before_launching():
+    L = B.lib()
+    E = B.ACTQ_EINVAL
+    # group_stats
+    assert L.actq_group_stats(None, 0, 1, 256, 256, FAKE, FAKE, None) == E
+    assert L.actq_group_stats(FAKE, 0, 0, 256, 256, FAKE, FAKE, None) == E
+    assert L.actq_group_stats(FAKE, 0, 1, 256, 64, FAKE, FAKE, None) == E
+    assert L.actq_group_stats(FAKE, 7, 1, 256, 256, FAKE, FAKE, None) == E
+    assert L.actq_group_stats(FAKE + 4, 0, 1, 256, 256, FAKE, FAKE, None) == E
+    assert "aligned" in B.last_error()
+    # quantize_pack: order is x, dt, N, D, G, bits, offsets, seed, tag, noise_bits, packed, capacity, header, stream
+    ok = [FAKE, 0, 2, 512, 256, FAKE, FAKE, 1, 0, 24, FAKE, 1 << 20, FAKE, None]
+    for idx, bad in [(0, None), (5, None), (6, None), (10, None), (12, None), (2, -1), (3, 0), (4, 512),
+                     (1, 3), (9, 12), (0, FAKE + 2), (10, FAKE + 8), (12, FAKE + 4), (11, 10), (2, 1 << 32),
+                     (3, 1 << 34)]:
+        args = list(ok)
+        args[idx] = bad
+        assert L.actq_quantize_pack(*args) == E, (idx, bad)
+        assert B.last_error()
+    # unpack_dequantize: packed, capacity, header, bits, offsets, N, D, G, out, out_dt, stream
+    ok = [FAKE, 1 << 20, FAKE, FAKE, FAKE, 2, 512, 256, FAKE, 0, None]
+    for idx, bad in [(0, None), (2, None), (3, None), (4, None), (8, None), (5, 0), (6, -5), (7, 8), (9, 2),
+                     (8, FAKE + 4), (0, FAKE + 1)]:
+        args = list(ok)
+        args[idx] = bad
+        assert L.actq_unpack_dequantize(*args) == E, (idx, bad)
+
+
+def test_allocate_bits_errors():
+    w = np.ones(3, dtype=np.float32)
+    D = np.full(3, 256, dtype=np.int64)
+    with pytest.raises(B.ActqError) as e:
+        B.allocate_bits(w, D, 3 * 256 - 1)
+    assert e.value.code == B.ACTQ_EINFEASIBLE and list(e.value.bits) == [1, 1, 1]
+    for bad_w in ([-1, 1, 1], [np.nan, 1, 1], [np.inf, 1, 1]):
+        with pytest.raises(B.ActqError) as e:
+            B.allocate_bits(np.array(bad_w, dtype=np.float32), D, 10 ** 6)
+        assert e.value.code == B.ACTQ_EINVAL
+    with pytest.raises(B.ActqError):
+        B.allocate_bits(w, np.array([256, 0, 256], dtype=np.int64), 10 ** 6)
+    L = B.lib()
+    out = np.zeros(3, dtype=np.uint8)
+    assert L.actq_allocate_bits(None, D.ctypes.data, 3, 100, out.ctypes.data) == B.ACTQ_EINVAL
+    assert L.actq_allocate_bits(w.ctypes.data, D.ctypes.data, 0, 100, out.ctypes.data) == B.ACTQ_EINVAL
+    assert L.actq_allocate_bits(w.ctypes.data, D.ctypes.data, 3, -1, out.ctypes.data) == B.ACTQ_EINVAL
+
+
+def test_allocate_bits_matches_the_oracle_bit_for_bit():
+    """Host logic of the library against the oracle: identical widths, including ties,
+    zero sensitivities, unequal sizes and the infeasible case."""
+    import oracle
+    rng = np.random.default_rng(0)
+    for t in range(300):
+        M = int(rng.integers(1, 300))
+        w = rng.lognormal(0, 2, M).astype(np.float32)
+        if t % 3 == 0:
+            w[rng.integers(0, M, M // 3 + 1)] = w[0]       # ties
+        if t % 5 == 0:
+            w[rng.integers(0, M, M // 4 + 1)] = 0.0        # free items
+        D = rng.choice([256, 512, 1024, 25088, 802816], M).astype(np.int64)
+        budget = int(rng.uniform(0.9, 8.5) * D.sum())
+        try:
+            got, gc = B.allocate_bits(w, D, budget), 0
+        except B.ActqError as e:
+            got, gc = e.bits, e.code
+        try:
+            want, wc = oracle.allocate_bits(w, D, budget), 0
+        except oracle.OracleError as e:
+            want, wc = e.bits, e.code
+        assert gc == wc
+        assert np.array_equal(got, want), t
+
+
+def test_allocate_bits_full_sweep_size():
+    """M = 53 layers x 256 samples, sizes of the ResNet-50 sweep, 2.0-bit budget."""
+    import oracle
+    from paper_2104_14129_amd import synth
+    shapes = synth.resnet50_conv_input_shapes()
+    N = 256
+    D = np.repeat(np.array([c * h * w for c, h, w in shapes], dtype=np.int64), N)
+    w = synth.lognormal_sensitivities(D.size, seed=5)
+    budget = 2 * int(D.sum())
+    got = B.allocate_bits(w, D, budget)
+    want = oracle.allocate_bits(w, D, budget)
+    assert np.array_equal(got, want)
+    used = int((got.astype(np.int64) * D).sum())
+    assert used <= budget and budget - used < 4 * D.max()
