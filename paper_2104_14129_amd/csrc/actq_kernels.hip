@@ -3,11 +3,24 @@
 // Sec. 4.1 and Sec. 5.1).
 //
 // Work decomposition.  The group size is 256 = one 64-lane wavefront x 4 consecutive
-// elements per lane, so one 128-bit load per lane brings in a whole group, and the
-// min / max of a group is a wavefront reduction with no LDS traffic.  A *tile* is
-// kTileGroups consecutive groups of one sample; tiles never cross a sample, so the
-// width b_n is uniform over a tile and every branch on it is divergence-free.  A
-// wavefront owns a run of consecutive tiles (a contiguous span of HBM) and exits.
+// elements per lane, so one 128-bit load per lane brings in a whole group.  A *tile* is
+// four consecutive groups of one sample (4 KiB of binary32 input, four loads in flight per
+// lane); tiles never cross a sample, so the width b_n is uniform over a tile and every
+// branch on it is divergence-free.  One wavefront handles one tile (or a short run of
+// consecutive tiles) and exits: on this part many short-lived wavefronts stream HBM
+// faster than a few long-lived ones.
+//
+// The path is bound by HBM only if the integer work of the noise generator stays hidden,
+// so the per-group bookkeeping is kept off the vector ALU as far as possible:
+//   * the min and max of the four groups are reduced *together*: eight partial values per
+//     lane are folded by a transposing butterfly (v_permlane32_swap, v_permlane16_swap,
+//     DPP row_ror:8) that halves the number of live values at every step, so the whole
+//     tile costs 18 cross-lane operations instead of 48, and group g's result lands in
+//     row g (lanes 16g..16g+15) of the wavefront;
+//   * the two IEEE divisions per group (B / R and R / B) are therefore done once per tile,
+//     each row working on its own group, and broadcast with v_readlane;
+//   * packed codes go through a wavefront-private LDS slice so that the bit stream leaves
+//     as one fully coalesced store per tile whatever the width.
 //
 // This file must be compiled with -ffp-contract=off: the scaling step is a subtraction
 // and a multiplication that are rounded separately.
@@ -47,35 +60,49 @@ __device__ __forceinline__ uint32_t dpp_u32(uint32_t v)
 constexpr int kDppXor1 = 0xB1;         // quad_perm [1,0,3,2]
 constexpr int kDppXor2 = 0x4E;         // quad_perm [2,3,0,1]
 constexpr int kDppHalfMirror = 0x141;  // lane i <-> 7-i inside each 8 lanes
-constexpr int kDppMirror = 0x140;      // lane i <-> 15-i inside each 16 lanes
+constexpr int kDppXor8 = 0x128;        // row_ror:8, lane i <-> i^8 inside each 16 lanes
 
-// min / max of a value over the wavefront, returned in every lane.  Inputs are finite.
-__device__ __forceinline__ float wave_min(float v)
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+
+// min over lanes {l, l^32} of a (kept in lanes 0..31) and of b (kept in lanes 32..63)
+__device__ __forceinline__ float fold32(float a, float b)
 {
-    v = fminf(v, dpp_f32<kDppXor1>(v));
-    v = fminf(v, dpp_f32<kDppXor2>(v));
-    v = fminf(v, dpp_f32<kDppHalfMirror>(v));
-    v = fminf(v, dpp_f32<kDppMirror>(v));
-    const int iv = __float_as_int(v);
-    const float r0 = __int_as_float(__builtin_amdgcn_readlane(iv, 0));
-    const float r1 = __int_as_float(__builtin_amdgcn_readlane(iv, 16));
-    const float r2 = __int_as_float(__builtin_amdgcn_readlane(iv, 32));
-    const float r3 = __int_as_float(__builtin_amdgcn_readlane(iv, 48));
-    return fminf(fminf(r0, r1), fminf(r2, r3));
+    const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    return fminf(__uint_as_float(r.x), __uint_as_float(r.y));
 }
 
-__device__ __forceinline__ float wave_max(float v)
+// min over lanes {l, l^16} of a (kept in rows 0 and 2) and of b (kept in rows 1 and 3)
+__device__ __forceinline__ float fold16(float a, float b)
 {
-    v = fmaxf(v, dpp_f32<kDppXor1>(v));
-    v = fmaxf(v, dpp_f32<kDppXor2>(v));
-    v = fmaxf(v, dpp_f32<kDppHalfMirror>(v));
-    v = fmaxf(v, dpp_f32<kDppMirror>(v));
-    const int iv = __float_as_int(v);
-    const float r0 = __int_as_float(__builtin_amdgcn_readlane(iv, 0));
-    const float r1 = __int_as_float(__builtin_amdgcn_readlane(iv, 16));
-    const float r2 = __int_as_float(__builtin_amdgcn_readlane(iv, 32));
-    const float r3 = __int_as_float(__builtin_amdgcn_readlane(iv, 48));
-    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
+    const u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    return fminf(__uint_as_float(r.x), __uint_as_float(r.y));
+}
+
+// Joint reduction of the four groups of a tile.  lo[u] / hi[u] are the lane-local minimum
+// and maximum of group u.  On return every lane of row u (lanes 16u..16u+15) holds the
+// wavefront-wide minimum and maximum of group u.  Inputs are finite.
+__device__ __forceinline__ void tile_min_max(const float (&lo)[4], const float (&hi)[4], int lane,
+                                             float& row_min, float& row_max)
+{
+    // max(x) = -min(-x): all eight values are folded with min; value 2u is lo[u], 2u+1 is -hi[u]
+    float c[4];
+    c[0] = fold32(lo[0], lo[2]);    // values 0 | 4
+    c[1] = fold32(-hi[0], -hi[2]);  // values 1 | 5
+    c[2] = fold32(lo[1], lo[3]);    // values 2 | 6
+    c[3] = fold32(-hi[1], -hi[3]);  // values 3 | 7
+    float d[2];
+    d[0] = fold16(c[0], c[2]);      // value (lane>>4)*2
+    d[1] = fold16(c[1], c[3]);      // value (lane>>4)*2 + 1
+    const bool upper = (lane & 8) != 0;
+    const float keep = upper ? d[1] : d[0];
+    const float give = upper ? d[0] : d[1];
+    float e = fminf(keep, dpp_f32<kDppXor8>(give));  // value lane>>3, still to fold over lane bits 0..2
+    e = fminf(e, dpp_f32<kDppXor1>(e));
+    e = fminf(e, dpp_f32<kDppXor2>(e));
+    e = fminf(e, dpp_f32<kDppHalfMirror>(e));
+    const float other = dpp_f32<kDppXor8>(e);
+    row_min = upper ? other : e;
+    row_max = -(upper ? e : other);
 }
 
 // ------------------------------------------------------------------------------------
@@ -153,60 +180,75 @@ struct Io<_Float16> {
     static __device__ __forceinline__ void store1(_Float16* p, float v) { *p = narrow(v); }
 };
 
-// Geometry shared by the kernels.  All of it is wavefront-uniform.
+// Launch geometry.  grid.x covers the tiles of one sample, grid.y * grid.z the samples, so
+// no kernel ever divides a linear index.  Everything here is wavefront-uniform.
 struct Geometry {
-    int64_t D;              // features per sample
-    uint32_t ng;            // groups per sample
-    uint32_t tiles_per_sample;
-    uint32_t tiles;         // N * tiles_per_sample
-    uint32_t tiles_per_wave;
+    int64_t D;                  // features per sample
+    uint32_t N;                 // samples
+    uint32_t ng;                // groups per sample
+    uint32_t tiles_per_sample;  // ceil(ng / 4)
+    uint32_t tiles_per_wave;    // consecutive tiles handled by one wavefront
+    uint32_t grid_y;            // samples per grid.z slice
 };
 
-struct TileCursor {
-    uint32_t n;   // sample
-    uint32_t g0;  // first group of the tile inside the sample
-};
+// First tile (inside its sample) and sample of this wavefront; false if it has no work.
+__device__ __forceinline__ bool wave_work(const Geometry& geo, uint32_t& n, uint32_t& tile_begin,
+                                          uint32_t& tile_end)
+{
+    const uint32_t wave = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6)));
+    n = blockIdx.z * geo.grid_y + blockIdx.y;
+    tile_begin = (blockIdx.x * kWavesPerBlock + wave) * geo.tiles_per_wave;
+    tile_end = min(tile_begin + geo.tiles_per_wave, geo.tiles_per_sample);
+    return n < geo.N && tile_begin < geo.tiles_per_sample;
+}
 
-// Loads the lane's four elements of group g (sample base xs).  VEC: the group is full
-// and 16-byte (8 for binary16) aligned.  Otherwise every element is guarded; elements
-// past D read as +inf in lo[] and -inf in hi[] so that they drop out of min and max.
+// Loads the lane's four elements of up to four groups.  VEC: every group of the tensor is
+// full and 16-byte (8 for binary16) aligned.  Otherwise every element is guarded.
 template <typename T, bool VEC>
-__device__ __forceinline__ void load_group(const T* xs, int64_t d0, int64_t D, float (&v)[4],
-                                           bool (&ok)[4])
+__device__ __forceinline__ void load_tile(const T* xs, uint32_t g0, int groups, int lane, int64_t D,
+                                          float (&v)[kTileGroups][4], bool (&ok)[kTileGroups][4])
 {
-    if (VEC) {
-        Io<T>::load4(xs + d0, v);
-        ok[0] = ok[1] = ok[2] = ok[3] = true;
-    } else {
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            ok[k] = d0 + k < D;
-            v[k] = ok[k] ? Io<T>::load1(xs + d0 + k) : 0.0f;
+    for (int u = 0; u < kTileGroups; ++u) {
+        const int64_t d0 = (static_cast<int64_t>(g0 + u) << 8) + lane * 4;
+        if (VEC) {
+            if (u < groups) {
+                Io<T>::load4(xs + d0, v[u]);
+            } else {
+                v[u][0] = v[u][1] = v[u][2] = v[u][3] = 0.0f;
+            }
+            ok[u][0] = ok[u][1] = ok[u][2] = ok[u][3] = true;
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                ok[u][k] = u < groups && d0 + k < D;
+                v[u][k] = ok[u][k] ? Io<T>::load1(xs + d0 + k) : 0.0f;
+            }
         }
     }
 }
 
+// Lane-local minimum and maximum of each group.  Guarded-out elements drop out; a group
+// with no valid element in this lane yields (+inf, -inf).
 template <bool VEC>
-__device__ __forceinline__ void lane_min_max(const float (&v)[4], const bool (&ok)[4], float& lo, float& hi)
+__device__ __forceinline__ void lane_min_max(const float (&v)[kTileGroups][4], const bool (&ok)[kTileGroups][4],
+                                             float (&lo)[kTileGroups], float (&hi)[kTileGroups])
 {
-    if (VEC) {
-        lo = fminf(fminf(v[0], v[1]), fminf(v[2], v[3]));
-        hi = fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3]));
-    } else {
-        lo = __builtin_inff();
-        hi = -__builtin_inff();
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            lo = ok[k] ? fminf(lo, v[k]) : lo;
-            hi = ok[k] ? fmaxf(hi, v[k]) : hi;
+    for (int u = 0; u < kTileGroups; ++u) {
+        if (VEC) {
+            lo[u] = fminf(fminf(v[u][0], v[u][1]), fminf(v[u][2], v[u][3]));
+            hi[u] = fmaxf(fmaxf(v[u][0], v[u][1]), fmaxf(v[u][2], v[u][3]));
+        } else {
+            lo[u] = __builtin_inff();
+            hi[u] = -__builtin_inff();
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                lo[u] = ok[u][k] ? fminf(lo[u], v[u][k]) : lo[u];
+                hi[u] = ok[u][k] ? fmaxf(hi[u], v[u][k]) : hi[u];
+            }
         }
     }
-}
-
-__device__ __forceinline__ uint32_t wave_index()
-{
-    const uint32_t w = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
-    return static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(w)));
 }
 
 // ------------------------------------------------------------------------------------
@@ -218,54 +260,77 @@ __global__ __launch_bounds__(kBlock) void group_stats_kernel(const T* __restrict
                                                              float* __restrict__ grange)
 {
     const int lane = threadIdx.x & (kWave - 1);
-    const uint32_t first = wave_index() * geo.tiles_per_wave;
-    if (first >= geo.tiles) return;
-    const uint32_t last = min(first + geo.tiles_per_wave, geo.tiles);
-    uint32_t n = first / geo.tiles_per_sample;
-    uint32_t g0 = (first - n * geo.tiles_per_sample) * kTileGroups;
-    for (uint32_t tile = first; tile < last; ++tile) {
-        const T* xs = x + static_cast<int64_t>(n) * geo.D;
+    uint32_t n, tile, tile_end;
+    if (!wave_work(geo, n, tile, tile_end)) return;
+    const T* xs = x + static_cast<int64_t>(n) * geo.D;
+    for (; tile < tile_end; ++tile) {
+        const uint32_t g0 = tile * kTileGroups;
         const int groups = static_cast<int>(min(static_cast<uint32_t>(kTileGroups), geo.ng - g0));
         float v[kTileGroups][4];
         bool ok[kTileGroups][4];
-#pragma unroll
-        for (int u = 0; u < kTileGroups; ++u)
-            if (u < groups)
-                load_group<T, VEC>(xs, (static_cast<int64_t>(g0 + u) << 8) + lane * 4, geo.D, v[u], ok[u]);
-#pragma unroll
-        for (int u = 0; u < kTileGroups; ++u) {
-            if (u < groups) {
-                float lo, hi;
-                lane_min_max<VEC>(v[u], ok[u], lo, hi);
-                const float mn = wave_min(lo) + 0.0f;  // -0.0 -> +0.0
-                const float mx = wave_max(hi);
-                if (lane == 0) {
-                    const int64_t gi = static_cast<int64_t>(n) * geo.ng + g0 + u;
-                    gmin[gi] = mn;
-                    grange[gi] = mx - mn;
-                }
-            }
+        load_tile<T, VEC>(xs, g0, groups, lane, geo.D, v, ok);
+        float lo[kTileGroups], hi[kTileGroups];
+        lane_min_max<VEC>(v, ok, lo, hi);
+        float mn, mx;
+        tile_min_max(lo, hi, lane, mn, mx);
+        mn += 0.0f;  // -0.0 -> +0.0
+        const int row = lane >> 4;
+        if ((lane & 15) == 0 && row < groups) {
+            const int64_t gi = static_cast<int64_t>(n) * geo.ng + g0 + row;
+            gmin[gi] = mn;
+            grange[gi] = mx - mn;
         }
-        g0 += kTileGroups;
-        if (g0 >= geo.ng) { g0 = 0; ++n; }
     }
 }
 
 // ------------------------------------------------------------------------------------
 // Sec. 4.1 + Sec. 5.1: scale, round stochastically, pack.
 
-// OR of `piece << (bits_per_lane * (lane % lanes_per_word))` over each cluster of lanes
-// that share a 32-bit word of the stream; every lane of the cluster receives the word.
-template <int B>
-__device__ __forceinline__ uint32_t gather_word(uint32_t piece, int lane)
+// Orders the compiler's view of a wavefront-private LDS hand-over (write by one lane, read
+// by another lane of the same wavefront).  The hardware executes one wavefront's LDS
+// instructions in order, so no instruction is emitted.
+__device__ __forceinline__ void wave_lds_handover()
 {
-    constexpr int lanes_per_word = 8 / B;  // 4*B bits per lane
-    if (lanes_per_word == 1) return piece;
-    uint32_t w = piece << ((lane & (lanes_per_word - 1)) * (4 * B));
-    w |= dpp_u32<kDppXor1>(w);
-    if (lanes_per_word >= 4) w |= dpp_u32<kDppXor2>(w);
-    if (lanes_per_word >= 8) w |= dpp_u32<kDppHalfMirror>(w);
-    return w;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Noise words for the lane's four elements of each group of the tile, as integers on a grid
+// of 2^NOISE_BITS points.
+template <int NOISE_BITS>
+__device__ __forceinline__ void tile_noise(uint32_t n, uint32_t g0, int lane, uint32_t k0, uint32_t k1,
+                                           uint32_t tag0, uint32_t tag1, uint32_t (&rnd)[kTileGroups][4])
+{
+    if (NOISE_BITS == 24) {
+        // counter = feature index / 4: one call per lane per group
+#pragma unroll
+        for (int u = 0; u < kTileGroups; ++u) {
+            uint32_t r[4];
+            philox4x32_10(((g0 + u) << 6) + lane, n, tag0, tag1, k0, k1, r);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) rnd[u][k] = r[k] >> 8;
+        }
+    } else {
+        // counter = feature index / 8: one call serves two neighbouring lanes of one group.
+        // Even lanes generate for group 2p, odd lanes for group 2p+1, and the pair trades
+        // the halves it does not need, so each lane makes one call per two groups.
+        const bool odd = (lane & 1) != 0;
+#pragma unroll
+        for (int p = 0; p < kTileGroups / 2; ++p) {
+            uint32_t r[4];
+            philox4x32_10(((g0 + 2 * p + (odd ? 1u : 0u)) << 5) + (lane >> 1), n, tag0, tag1, k0, k1, r);
+            // the partner needs words 2,3 of an even lane's call and words 0,1 of an odd lane's
+            const uint32_t got0 = dpp_u32<kDppXor1>(odd ? r[0] : r[2]);
+            const uint32_t got1 = dpp_u32<kDppXor1>(odd ? r[1] : r[3]);
+            const uint32_t a0 = odd ? got0 : r[0], a1 = odd ? got1 : r[1];  // group 2p
+            const uint32_t b0 = odd ? r[2] : got0, b1 = odd ? r[3] : got1;  // group 2p+1
+            rnd[2 * p][0] = a0 & 0xffffu; rnd[2 * p][1] = a0 >> 16;
+            rnd[2 * p][2] = a1 & 0xffffu; rnd[2 * p][3] = a1 >> 16;
+            rnd[2 * p + 1][0] = b0 & 0xffffu; rnd[2 * p + 1][1] = b0 >> 16;
+            rnd[2 * p + 1][2] = b1 & 0xffffu; rnd[2 * p + 1][3] = b1 >> 16;
+        }
+    }
 }
 
 template <typename T, int NOISE_BITS, bool VEC, int B>
@@ -273,76 +338,93 @@ __device__ __forceinline__ void quantize_tile(const T* xs, int64_t D, uint32_t n
                                               int groups, uint32_t ng, int lane, uint32_t k0,
                                               uint32_t k1, uint32_t tag0, uint32_t tag1,
                                               uint8_t* __restrict__ dst_sample,
-                                              float* __restrict__ header)
+                                              float* __restrict__ header, uint32_t* stage)
 {
     constexpr float kB = static_cast<float>((1 << B) - 1);
+    constexpr float kNoiseGrid = NOISE_BITS == 24 ? 16777216.0f : 65536.0f;
     float v[kTileGroups][4];
     bool ok[kTileGroups][4];
-#pragma unroll
-    for (int u = 0; u < kTileGroups; ++u)
-        if (u < groups)
-            load_group<T, VEC>(xs, (static_cast<int64_t>(g0 + u) << 8) + lane * 4, D, v[u], ok[u]);
+    load_tile<T, VEC>(xs, g0, groups, lane, D, v, ok);
 
+    // noise does not depend on the data: issue it while the loads are in flight
+    uint32_t rnd[kTileGroups][4];
+    tile_noise<NOISE_BITS>(n, g0, lane, k0, k1, tag0, tag1, rnd);
+
+    float lo[kTileGroups], hi[kTileGroups];
+    lane_min_max<VEC>(v, ok, lo, hi);
+    float mn, mx;
+    tile_min_max(lo, hi, lane, mn, mx);
+    mn += 0.0f;  // -0.0 -> +0.0
+    const float range = mx - mn;
+    float inv = kB / range;
+    float scale = range / kB;
+    if (!(range != 0.0f) || !__builtin_isfinite(inv)) {  // constant group, or B / R overflows
+        inv = 0.0f;
+        scale = 0.0f;
+    }
+    const int row = lane >> 4;
+    if ((lane & 15) == 0 && row < groups) {
+        f32x2 h;
+        h.x = mn;
+        h.y = scale;
+        __builtin_nontemporal_store(h, reinterpret_cast<f32x2*>(header + 2 * (static_cast<int64_t>(n) * ng + g0 + row)));
+    }
+
+    uint32_t piece[kTileGroups];
 #pragma unroll
     for (int u = 0; u < kTileGroups; ++u) {
-        if (u >= groups) continue;
-        const uint32_t g = g0 + u;
-        float lo, hi;
-        lane_min_max<VEC>(v[u], ok[u], lo, hi);
-        const float mn = wave_min(lo) + 0.0f;
-        const float range = wave_max(hi) - mn;
-        float inv = kB / range;
-        float scale = range / kB;
-        if (!(range != 0.0f) || !__builtin_isfinite(inv)) {
-            inv = 0.0f;
-            scale = 0.0f;
-        }
-        if (lane == 0) {
-            f32x2 h;
-            h.x = mn;
-            h.y = scale;
-            *reinterpret_cast<f32x2*>(header + 2 * (static_cast<int64_t>(n) * ng + g)) = h;
-        }
-
-        // noise: one Philox call covers 4 (24-bit) or 8 (16-bit) consecutive features
-        uint32_t r[4];
-        const uint32_t d0 = (g << 8) + lane * 4;  // feature index of the lane's first element, < 2^34 / ... see launcher
-        uint32_t rnd[4];
-        if (NOISE_BITS == 24) {
-            philox4x32_10((g << 6) + lane, n, tag0, tag1, k0, k1, r);
-#pragma unroll
-            for (int k = 0; k < 4; ++k) rnd[k] = r[k] >> 8;
-        } else {
-            philox4x32_10((g << 5) + (lane >> 1), n, tag0, tag1, k0, k1, r);
-            const uint32_t wa = (lane & 1) ? r[2] : r[0];
-            const uint32_t wb = (lane & 1) ? r[3] : r[1];
-            rnd[0] = wa & 0xffffu;
-            rnd[1] = wa >> 16;
-            rnd[2] = wb & 0xffffu;
-            rnd[3] = wb >> 16;
-        }
-        (void)d0;
-        constexpr float kNoiseScale = NOISE_BITS == 24 ? 5.9604644775390625e-08f : 1.52587890625e-05f;
-
-        uint32_t piece = 0;
+        const float mn_u = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(mn), 16 * u));
+        const float inv_u = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(inv), 16 * u));
+        piece[u] = 0;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            const float centred = v[u][k] - mn;
-            float uu = centred * inv;
-            uu = fminf(uu, kB);
-            const float fl = floorf(uu);
-            const float frac = uu - fl;
-            const float noise = static_cast<float>(rnd[k]) * kNoiseScale;
-            uint32_t q = static_cast<uint32_t>(fl) + (noise < frac ? 1u : 0u);
+            const float centred = v[u][k] - mn_u;
+            float scaled = centred * inv_u;
+            scaled = fminf(scaled, kB);  // the two roundings can overshoot B by an ulp
+            const float frac = __builtin_amdgcn_fractf(scaled);  // exact for scaled >= 0
+            uint32_t q = static_cast<uint32_t>(scaled);          // truncation = floor
+            q += (static_cast<float>(rnd[u][k]) < frac * kNoiseGrid) ? 1u : 0u;
             if (!VEC) q = ok[u][k] ? q : 0u;
-            piece |= q << (k * B);
+            piece[u] |= q << (k * B);
         }
-        const uint32_t word = gather_word<B>(piece, lane);
-        constexpr int lanes_per_word = 8 / B;
-        if ((lane & (lanes_per_word - 1)) == 0) {
-            uint32_t* dst = reinterpret_cast<uint32_t*>(dst_sample + static_cast<uint64_t>(g) * (32 * B));
-            dst[lane / lanes_per_word] = word;
+    }
+
+    // the bit stream of the tile is 4 * 32 * B contiguous bytes
+    uint8_t* dst_tile = dst_sample + static_cast<uint64_t>(g0) * (32 * B);
+    if (B == 8) {
+#pragma unroll
+        for (int u = 0; u < kTileGroups; ++u)
+            if (u < groups)
+                __builtin_nontemporal_store(piece[u], reinterpret_cast<uint32_t*>(dst_tile) + u * 64 + lane);
+    } else if (B == 4) {
+        uint16_t* s16 = reinterpret_cast<uint16_t*>(stage);
+#pragma unroll
+        for (int u = 0; u < kTileGroups; ++u) s16[u * 64 + lane] = static_cast<uint16_t>(piece[u]);
+        wave_lds_handover();
+        const u32x2 w = reinterpret_cast<const u32x2*>(stage)[lane];
+        if (lane * 8 < groups * 128)
+            __builtin_nontemporal_store(w, reinterpret_cast<u32x2*>(dst_tile) + lane);
+    } else if (B == 2) {
+        uint8_t* s8 = reinterpret_cast<uint8_t*>(stage);
+#pragma unroll
+        for (int u = 0; u < kTileGroups; ++u) s8[u * 64 + lane] = static_cast<uint8_t>(piece[u]);
+        wave_lds_handover();
+        const uint32_t w = stage[lane];
+        if (lane * 4 < groups * 64)
+            __builtin_nontemporal_store(w, reinterpret_cast<uint32_t*>(dst_tile) + lane);
+    } else {
+        // B == 1: a lane holds a nibble per group; neighbours merge into a byte first
+        const uint32_t nib = piece[0] | (piece[1] << 8) | (piece[2] << 16) | (piece[3] << 24);
+        const uint32_t both = nib | (dpp_u32<kDppXor1>(nib) << 4);  // valid in even lanes
+        uint8_t* s8 = reinterpret_cast<uint8_t*>(stage);
+        if ((lane & 1) == 0) {
+#pragma unroll
+            for (int u = 0; u < kTileGroups; ++u) s8[u * 32 + (lane >> 1)] = static_cast<uint8_t>(both >> (8 * u));
         }
+        wave_lds_handover();
+        const uint16_t w = reinterpret_cast<const uint16_t*>(stage)[lane];
+        if (lane * 2 < groups * 32)
+            __builtin_nontemporal_store(w, reinterpret_cast<uint16_t*>(dst_tile) + lane);
     }
 }
 
@@ -352,32 +434,28 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(
     const uint64_t* __restrict__ offsets, uint32_t k0, uint32_t k1, uint32_t tag0, uint32_t tag1,
     uint8_t* __restrict__ packed, uint64_t capacity, float* __restrict__ header)
 {
+    __shared__ uint32_t stage_all[kWavesPerBlock][256];  // 1 KiB per wavefront, private to it
     const int lane = threadIdx.x & (kWave - 1);
-    const uint32_t first = wave_index() * geo.tiles_per_wave;
-    if (first >= geo.tiles) return;
-    const uint32_t last = min(first + geo.tiles_per_wave, geo.tiles);
-    uint32_t n = first / geo.tiles_per_sample;
-    uint32_t g0 = (first - n * geo.tiles_per_sample) * kTileGroups;
-    for (uint32_t tile = first; tile < last; ++tile) {
-        const T* xs = x + static_cast<int64_t>(n) * geo.D;
+    uint32_t n, tile, tile_end;
+    if (!wave_work(geo, n, tile, tile_end)) return;
+    uint32_t* stage = stage_all[__builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6))];
+    const T* xs = x + static_cast<int64_t>(n) * geo.D;
+    const uint32_t b = bits[n];
+    const uint64_t off = offsets[n];
+    const uint64_t bytes = static_cast<uint64_t>(geo.ng) * 32u * b;
+    // a sample whose width or byte range is invalid is skipped, nothing is written
+    if ((off & 31u) != 0 || off > capacity || bytes > capacity - off) return;
+    uint8_t* dst = packed + off;
+    for (; tile < tile_end; ++tile) {
+        const uint32_t g0 = tile * kTileGroups;
         const int groups = static_cast<int>(min(static_cast<uint32_t>(kTileGroups), geo.ng - g0));
-        const uint32_t b = bits[n];
-        const uint64_t off = offsets[n];
-        const uint64_t bytes = static_cast<uint64_t>(geo.ng) * 32u * b;
-        // a sample whose width or byte range is invalid is skipped, nothing is written
-        const bool fits = (off & 3u) == 0 && off <= capacity && bytes <= capacity - off;
-        if (fits) {
-            uint8_t* dst = packed + off;
-            switch (b) {
-                case 1: quantize_tile<T, NOISE_BITS, VEC, 1>(xs, geo.D, n, g0, groups, geo.ng, lane, k0, k1, tag0, tag1, dst, header); break;
-                case 2: quantize_tile<T, NOISE_BITS, VEC, 2>(xs, geo.D, n, g0, groups, geo.ng, lane, k0, k1, tag0, tag1, dst, header); break;
-                case 4: quantize_tile<T, NOISE_BITS, VEC, 4>(xs, geo.D, n, g0, groups, geo.ng, lane, k0, k1, tag0, tag1, dst, header); break;
-                case 8: quantize_tile<T, NOISE_BITS, VEC, 8>(xs, geo.D, n, g0, groups, geo.ng, lane, k0, k1, tag0, tag1, dst, header); break;
-                default: break;
-            }
+        switch (b) {
+            case 1: quantize_tile<T, NOISE_BITS, VEC, 1>(xs, geo.D, n, g0, groups, geo.ng, lane, k0, k1, tag0, tag1, dst, header, stage); break;
+            case 2: quantize_tile<T, NOISE_BITS, VEC, 2>(xs, geo.D, n, g0, groups, geo.ng, lane, k0, k1, tag0, tag1, dst, header, stage); break;
+            case 4: quantize_tile<T, NOISE_BITS, VEC, 4>(xs, geo.D, n, g0, groups, geo.ng, lane, k0, k1, tag0, tag1, dst, header, stage); break;
+            case 8: quantize_tile<T, NOISE_BITS, VEC, 8>(xs, geo.D, n, g0, groups, geo.ng, lane, k0, k1, tag0, tag1, dst, header, stage); break;
+            default: return;
         }
-        g0 += kTileGroups;
-        if (g0 >= geo.ng) { g0 = 0; ++n; }
     }
 }
 
@@ -390,7 +468,7 @@ __device__ __forceinline__ void dequantize_tile(const uint8_t* __restrict__ src_
                                                 uint32_t n, uint32_t g0, int groups, uint32_t ng,
                                                 int lane)
 {
-    constexpr int lanes_per_word = 8 / B;
+    constexpr int lanes_per_word = 8 / B;  // a lane's four codes are 4*B bits of a 32-bit word
     constexpr uint32_t code_mask = (1u << B) - 1u;
     uint32_t word[kTileGroups];
     f32x2 hd[kTileGroups];
@@ -431,54 +509,48 @@ __global__ __launch_bounds__(kBlock) void unpack_dequantize_kernel(
     T* __restrict__ out)
 {
     const int lane = threadIdx.x & (kWave - 1);
-    const uint32_t first = wave_index() * geo.tiles_per_wave;
-    if (first >= geo.tiles) return;
-    const uint32_t last = min(first + geo.tiles_per_wave, geo.tiles);
-    uint32_t n = first / geo.tiles_per_sample;
-    uint32_t g0 = (first - n * geo.tiles_per_sample) * kTileGroups;
-    for (uint32_t tile = first; tile < last; ++tile) {
-        T* os = out + static_cast<int64_t>(n) * geo.D;
+    uint32_t n, tile, tile_end;
+    if (!wave_work(geo, n, tile, tile_end)) return;
+    T* os = out + static_cast<int64_t>(n) * geo.D;
+    const uint32_t b = bits[n];
+    const uint64_t off = offsets[n];
+    const uint64_t bytes = static_cast<uint64_t>(geo.ng) * 32u * b;
+    if ((off & 31u) != 0 || off > capacity || bytes > capacity - off) return;
+    const uint8_t* src = packed + off;
+    for (; tile < tile_end; ++tile) {
+        const uint32_t g0 = tile * kTileGroups;
         const int groups = static_cast<int>(min(static_cast<uint32_t>(kTileGroups), geo.ng - g0));
-        const uint32_t b = bits[n];
-        const uint64_t off = offsets[n];
-        const uint64_t bytes = static_cast<uint64_t>(geo.ng) * 32u * b;
-        const bool fits = (off & 3u) == 0 && off <= capacity && bytes <= capacity - off;
-        if (fits) {
-            const uint8_t* src = packed + off;
-            switch (b) {
-                case 1: dequantize_tile<T, VEC, 1>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
-                case 2: dequantize_tile<T, VEC, 2>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
-                case 4: dequantize_tile<T, VEC, 4>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
-                case 8: dequantize_tile<T, VEC, 8>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
-                default: break;
-            }
+        switch (b) {
+            case 1: dequantize_tile<T, VEC, 1>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
+            case 2: dequantize_tile<T, VEC, 2>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
+            case 4: dequantize_tile<T, VEC, 4>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
+            case 8: dequantize_tile<T, VEC, 8>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
+            default: return;
         }
-        g0 += kTileGroups;
-        if (g0 >= geo.ng) { g0 = 0; ++n; }
     }
 }
 
 // ------------------------------------------------------------------------------------
 // Host-side launch geometry.
 
-int make_geometry(const char* who, int64_t N, int64_t D, Geometry* geo, dim3* grid)
+int make_geometry(const char* who, int64_t N, int64_t D, uint32_t tiles_per_wave, Geometry* geo, dim3* grid)
 {
     const int64_t ng = (D + kGroup - 1) / kGroup;
     const int64_t tps = (ng + kTileGroups - 1) / kTileGroups;
-    const int64_t tiles = N * tps;
-    if (tiles >= (int64_t(1) << 31)) return fail(ACTQ_EINVAL, "%s: tensor too large for one launch (%lld tiles)", who, (long long)tiles);
     geo->D = D;
+    geo->N = static_cast<uint32_t>(N);
     geo->ng = static_cast<uint32_t>(ng);
     geo->tiles_per_sample = static_cast<uint32_t>(tps);
-    geo->tiles = static_cast<uint32_t>(tiles);
-    // enough wavefronts to fill 256 CUs several times over, at most 8 tiles (32 KiB of
-    // binary32 input) per wavefront
-    int64_t tpw = tiles / (256 * 4 * 16);
-    if (tpw < 1) tpw = 1;
-    if (tpw > 8) tpw = 8;
-    geo->tiles_per_wave = static_cast<uint32_t>(tpw);
-    const int64_t waves = (tiles + tpw - 1) / tpw;
-    *grid = dim3(static_cast<unsigned>((waves + kWavesPerBlock - 1) / kWavesPerBlock));
+    geo->tiles_per_wave = tiles_per_wave;
+    const int64_t waves = (tps + tiles_per_wave - 1) / tiles_per_wave;
+    const int64_t gx = (waves + kWavesPerBlock - 1) / kWavesPerBlock;
+    const int64_t gy = N < 65535 ? N : 65535;
+    const int64_t gz = (N + gy - 1) / gy;
+    if (gx >= (int64_t(1) << 31) || gz > 65535)
+        return fail(ACTQ_EINVAL, "%s: tensor too large for one launch (grid %lld x %lld x %lld)", who,
+                    (long long)gx, (long long)gy, (long long)gz);
+    geo->grid_y = static_cast<uint32_t>(gy);
+    *grid = dim3(static_cast<unsigned>(gx), static_cast<unsigned>(gy), static_cast<unsigned>(gz));
     return ACTQ_OK;
 }
 
@@ -492,6 +564,11 @@ int check_launch(const char* who)
 // Vector path: every group is full and every sample base keeps the 128-bit alignment.
 bool vector_ok(int64_t D) { return D % kGroup == 0; }
 
+// Tiles per wavefront.  Reads stream fastest with one tile per wavefront; the write-heavy
+// dequantizer prefers a longer run per wavefront.
+constexpr uint32_t kTilesPerWaveRead = 1;
+constexpr uint32_t kTilesPerWaveWrite = 1;
+
 }  // namespace
 
 int launch_group_stats(const void* x, int dtype, int64_t N, int64_t D, float* gmin, float* grange,
@@ -499,7 +576,7 @@ int launch_group_stats(const void* x, int dtype, int64_t N, int64_t D, float* gm
 {
     Geometry geo;
     dim3 grid;
-    if (int rc = make_geometry("actq_group_stats", N, D, &geo, &grid)) return rc;
+    if (int rc = make_geometry("actq_group_stats", N, D, kTilesPerWaveRead, &geo, &grid)) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool vec = vector_ok(D);
     if (dtype == ACTQ_F32) {
@@ -537,7 +614,7 @@ int launch_quantize_pack(const void* x, int dtype, int64_t N, int64_t D, const u
 {
     Geometry geo;
     dim3 grid;
-    if (int rc = make_geometry("actq_quantize_pack", N, D, &geo, &grid)) return rc;
+    if (int rc = make_geometry("actq_quantize_pack", N, D, kTilesPerWaveRead, &geo, &grid)) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool vec = vector_ok(D);
     if (dtype == ACTQ_F32)
@@ -553,7 +630,7 @@ int launch_unpack_dequantize(const void* packed, uint64_t capacity, const float*
 {
     Geometry geo;
     dim3 grid;
-    if (int rc = make_geometry("actq_unpack_dequantize", N, D, &geo, &grid)) return rc;
+    if (int rc = make_geometry("actq_unpack_dequantize", N, D, kTilesPerWaveWrite, &geo, &grid)) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool vec = vector_ok(D);
     auto* pk = static_cast<const uint8_t*>(packed);
