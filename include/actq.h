@@ -23,7 +23,8 @@
  *   - Inputs must be finite.  Non-finite inputs are memory-safe but the codes
  *     they produce are unspecified.
  *   - Supported group size: G = 256.  Supported widths: b_n in {1, 2, 4, 8}.
- *   - x / out must be aligned to 16 bytes, packed to 16 bytes, header to 8.
+ *   - x / out must be aligned to 16 bytes, packed to 16 bytes, header and offsets to 8,
+ *     bits (device) to 4.
  */
 #ifndef ACTQ_H
 #define ACTQ_H

@@ -101,6 +101,7 @@ int actq_quantize_pack(const void* x, actq_dtype dt, int64_t N, int64_t D, int32
     if (!aligned(packed, 16)) return fail(ACTQ_EINVAL, "actq_quantize_pack: packed must be 16-byte aligned");
     if (!aligned(header, 8)) return fail(ACTQ_EINVAL, "actq_quantize_pack: header must be 8-byte aligned");
     if (!aligned(offsets, 8)) return fail(ACTQ_EINVAL, "actq_quantize_pack: offsets must be 8-byte aligned");
+    if (!aligned(bits, 4)) return fail(ACTQ_EINVAL, "actq_quantize_pack: bits must be 4-byte aligned");
     const uint64_t ng = static_cast<uint64_t>((D + G - 1) / G);
     if (packed_capacity < static_cast<uint64_t>(N) * ng * (G / 8))
         return fail(ACTQ_EINVAL, "actq_quantize_pack: packed_capacity %llu is below one bit per element", (unsigned long long)packed_capacity);
@@ -119,6 +120,7 @@ int actq_unpack_dequantize(const void* packed, uint64_t packed_capacity, const f
     if (!aligned(packed, 16)) return fail(ACTQ_EINVAL, "actq_unpack_dequantize: packed must be 16-byte aligned");
     if (!aligned(header, 8)) return fail(ACTQ_EINVAL, "actq_unpack_dequantize: header must be 8-byte aligned");
     if (!aligned(offsets, 8)) return fail(ACTQ_EINVAL, "actq_unpack_dequantize: offsets must be 8-byte aligned");
+    if (!aligned(bits, 4)) return fail(ACTQ_EINVAL, "actq_unpack_dequantize: bits must be 4-byte aligned");
     return launch_unpack_dequantize(packed, packed_capacity, header, bits, offsets, N, D, out,
                                     out_dt, stream);
 }

@@ -212,11 +212,12 @@ __device__ __forceinline__ void load_tile(const T* xs, uint32_t g0, int groups, 
     for (int u = 0; u < kTileGroups; ++u) {
         const int64_t d0 = (static_cast<int64_t>(g0 + u) << 8) + lane * 4;
         if (VEC) {
-            if (u < groups) {
-                Io<T>::load4(xs + d0, v[u]);
-            } else {
-                v[u][0] = v[u][1] = v[u][2] = v[u][3] = 0.0f;
-            }
+            // A group past the end of the sample re-reads the tile's first group (valid memory;
+            // its results are never stored).  Keeping the load unconditional keeps the number
+            // of loads per tile fixed, which is what lets the wait for a tile's data be a
+            // counted wait that leaves the next tile's loads in flight.
+            const int64_t d_safe = u < groups ? d0 : (static_cast<int64_t>(g0) << 8) + lane * 4;
+            Io<T>::load4(xs + d_safe, v[u]);
             ok[u][0] = ok[u][1] = ok[u][2] = ok[u][3] = true;
         } else {
 #pragma unroll
@@ -249,6 +250,15 @@ __device__ __forceinline__ void lane_min_max(const float (&v)[kTileGroups][4], c
             }
         }
     }
+}
+
+// Width of sample n through the scalar data path: the 32-bit word that holds bits[n] (the
+// array is 4-byte aligned, so the word shares a page with bits[n] and the load cannot fault
+// even when N is not a multiple of four), then a shift.
+__device__ __forceinline__ uint32_t load_width(const uint8_t* __restrict__ bits, uint32_t n)
+{
+    const uint32_t word = reinterpret_cast<const uint32_t*>(bits)[n >> 2];
+    return (word >> ((n & 3u) * 8u)) & 0xffu;
 }
 
 // ------------------------------------------------------------------------------------
@@ -333,29 +343,24 @@ __device__ __forceinline__ void tile_noise(uint32_t n, uint32_t g0, int lane, ui
     }
 }
 
-template <typename T, int NOISE_BITS, bool VEC, int B>
-__device__ __forceinline__ void quantize_tile(const T* xs, int64_t D, uint32_t n, uint32_t g0,
-                                              int groups, uint32_t ng, int lane, uint32_t k0,
-                                              uint32_t k1, uint32_t tag0, uint32_t tag1,
-                                              uint8_t* __restrict__ dst_sample,
-                                              float* __restrict__ header, uint32_t* stage)
+// The lane's share of one tile: four elements of each of up to four groups, widened to
+// binary32, and which of them exist.
+struct TileRegs {
+    float v[kTileGroups][4];
+    bool ok[kTileGroups][4];
+};
+
+template <int NOISE_BITS, bool VEC, int B>
+__device__ __forceinline__ void encode_tile(const TileRegs& td, const uint32_t (&rnd)[kTileGroups][4],
+                                            float row_min, float row_max, uint32_t n, uint32_t g0,
+                                            int groups, uint32_t ng, int lane,
+                                            uint8_t* __restrict__ dst_sample,
+                                            float* __restrict__ header, uint32_t* stage)
 {
     constexpr float kB = static_cast<float>((1 << B) - 1);
     constexpr float kNoiseGrid = NOISE_BITS == 24 ? 16777216.0f : 65536.0f;
-    float v[kTileGroups][4];
-    bool ok[kTileGroups][4];
-    load_tile<T, VEC>(xs, g0, groups, lane, D, v, ok);
-
-    // noise does not depend on the data: issue it while the loads are in flight
-    uint32_t rnd[kTileGroups][4];
-    tile_noise<NOISE_BITS>(n, g0, lane, k0, k1, tag0, tag1, rnd);
-
-    float lo[kTileGroups], hi[kTileGroups];
-    lane_min_max<VEC>(v, ok, lo, hi);
-    float mn, mx;
-    tile_min_max(lo, hi, lane, mn, mx);
-    mn += 0.0f;  // -0.0 -> +0.0
-    const float range = mx - mn;
+    const float mn = row_min;
+    const float range = row_max - mn;
     float inv = kB / range;
     float scale = range / kB;
     if (!(range != 0.0f) || !__builtin_isfinite(inv)) {  // constant group, or B / R overflows
@@ -378,13 +383,13 @@ __device__ __forceinline__ void quantize_tile(const T* xs, int64_t D, uint32_t n
         piece[u] = 0;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            const float centred = v[u][k] - mn_u;
+            const float centred = td.v[u][k] - mn_u;
             float scaled = centred * inv_u;
             scaled = fminf(scaled, kB);  // the two roundings can overshoot B by an ulp
             const float frac = __builtin_amdgcn_fractf(scaled);  // exact for scaled >= 0
             uint32_t q = static_cast<uint32_t>(scaled);          // truncation = floor
             q += (static_cast<float>(rnd[u][k]) < frac * kNoiseGrid) ? 1u : 0u;
-            if (!VEC) q = ok[u][k] ? q : 0u;
+            if (!VEC) q = td.ok[u][k] ? q : 0u;
             piece[u] |= q << (k * B);
         }
     }
@@ -426,36 +431,114 @@ __device__ __forceinline__ void quantize_tile(const T* xs, int64_t D, uint32_t n
         if (lane * 2 < groups * 32)
             __builtin_nontemporal_store(w, reinterpret_cast<uint16_t*>(dst_tile) + lane);
     }
+    wave_lds_handover();  // the slice is reused by the next tile of this wavefront
 }
 
+// Geometry of the streaming quantizer.  The launch holds at most as many wavefronts as the
+// chip keeps resident; wavefront w handles the linear tiles w, w + waves, w + 2*waves, ...
+// (linear tile = sample * tiles_per_sample + tile-in-sample), so at any moment the
+// resident wavefronts sweep one contiguous window of HBM.
+struct StreamGeometry {
+    int64_t D;
+    uint32_t N;
+    uint32_t ng;
+    uint32_t tiles_per_sample;
+    uint32_t total_tiles;
+    uint32_t step_n, step_t;  // waves = step_n * tiles_per_sample + step_t
+};
+
+// Position of a wavefront in its sequence of tiles, with the scalar facts of the sample.
+struct Cursor {
+    uint32_t n, t;   // sample, tile inside the sample
+    uint32_t b;      // width of the sample
+    uint64_t off;    // byte offset of the sample in the bit stream
+};
+
+template <typename T, bool VEC>
+__device__ __forceinline__ void fetch(const T* __restrict__ x, const StreamGeometry& geo,
+                                      const uint8_t* __restrict__ bits, const uint64_t* __restrict__ offsets,
+                                      int lane, Cursor& c, TileRegs& r)
+{
+    const int groups = static_cast<int>(min(static_cast<uint32_t>(kTileGroups), geo.ng - c.t * kTileGroups));
+    load_tile<T, VEC>(x + static_cast<int64_t>(c.n) * geo.D, c.t * kTileGroups, groups, lane, geo.D, r.v, r.ok);
+    c.b = load_width(bits, c.n);
+    c.off = offsets[c.n];
+}
+
+// Next tile of the wavefront; false (and the cursor unchanged) when there is none.
+__device__ __forceinline__ bool advance(const StreamGeometry& geo, Cursor& c)
+{
+    uint32_t n2 = c.n + geo.step_n, t2 = c.t + geo.step_t;
+    if (t2 >= geo.tiles_per_sample) { t2 -= geo.tiles_per_sample; ++n2; }
+    if (n2 >= geo.N) return false;
+    c.n = n2;
+    c.t = t2;
+    return true;
+}
+
+template <int NOISE_BITS, bool VEC>
+__device__ __forceinline__ void quantize_one(const TileRegs& r, const Cursor& c, const StreamGeometry& geo,
+                                             int lane, uint32_t k0, uint32_t k1, uint32_t tag0, uint32_t tag1,
+                                             uint8_t* __restrict__ packed, uint64_t capacity,
+                                             float* __restrict__ header, uint32_t* stage)
+{
+    const uint32_t g0 = c.t * kTileGroups;
+    const int groups = static_cast<int>(min(static_cast<uint32_t>(kTileGroups), geo.ng - g0));
+    uint32_t rnd[kTileGroups][4];
+    tile_noise<NOISE_BITS>(c.n, g0, lane, k0, k1, tag0, tag1, rnd);
+    float lo[kTileGroups], hi[kTileGroups];
+    lane_min_max<VEC>(r.v, r.ok, lo, hi);
+    float row_min, row_max;
+    tile_min_max(lo, hi, lane, row_min, row_max);
+    row_min += 0.0f;  // -0.0 -> +0.0
+    // a sample whose width or byte range is invalid is skipped, nothing is written
+    const uint64_t bytes = static_cast<uint64_t>(geo.ng) * 32u * c.b;
+    if ((c.off & 31u) != 0 || c.off > capacity || bytes > capacity - c.off) return;
+    uint8_t* dst = packed + c.off;
+    switch (c.b) {
+        case 1: encode_tile<NOISE_BITS, VEC, 1>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, stage); break;
+        case 2: encode_tile<NOISE_BITS, VEC, 2>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, stage); break;
+        case 4: encode_tile<NOISE_BITS, VEC, 4>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, stage); break;
+        case 8: encode_tile<NOISE_BITS, VEC, 8>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, stage); break;
+        default: break;
+    }
+}
+
+// The quantizer is a software pipeline: while a wavefront works on one tile (noise,
+// reduction, rounding, packing: all vector-ALU work) the HBM loads of its next tile are
+// already in flight, so every resident wavefront keeps 4 KiB of reads outstanding at all
+// times and the ALU work hides under the memory time instead of adding to it.  Two
+// register sets alternate (no copies); a wavefront without a next tile re-reads its
+// current one, so that every step issues the same number of loads.
 template <typename T, int NOISE_BITS, bool VEC>
 __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(
-    const T* __restrict__ x, Geometry geo, const uint8_t* __restrict__ bits,
+    const T* __restrict__ x, StreamGeometry geo, const uint8_t* __restrict__ bits,
     const uint64_t* __restrict__ offsets, uint32_t k0, uint32_t k1, uint32_t tag0, uint32_t tag1,
     uint8_t* __restrict__ packed, uint64_t capacity, float* __restrict__ header)
 {
     __shared__ uint32_t stage_all[kWavesPerBlock][256];  // 1 KiB per wavefront, private to it
     const int lane = threadIdx.x & (kWave - 1);
-    uint32_t n, tile, tile_end;
-    if (!wave_work(geo, n, tile, tile_end)) return;
-    uint32_t* stage = stage_all[__builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6))];
-    const T* xs = x + static_cast<int64_t>(n) * geo.D;
-    const uint32_t b = bits[n];
-    const uint64_t off = offsets[n];
-    const uint64_t bytes = static_cast<uint64_t>(geo.ng) * 32u * b;
-    // a sample whose width or byte range is invalid is skipped, nothing is written
-    if ((off & 31u) != 0 || off > capacity || bytes > capacity - off) return;
-    uint8_t* dst = packed + off;
-    for (; tile < tile_end; ++tile) {
-        const uint32_t g0 = tile * kTileGroups;
-        const int groups = static_cast<int>(min(static_cast<uint32_t>(kTileGroups), geo.ng - g0));
-        switch (b) {
-            case 1: quantize_tile<T, NOISE_BITS, VEC, 1>(xs, geo.D, n, g0, groups, geo.ng, lane, k0, k1, tag0, tag1, dst, header, stage); break;
-            case 2: quantize_tile<T, NOISE_BITS, VEC, 2>(xs, geo.D, n, g0, groups, geo.ng, lane, k0, k1, tag0, tag1, dst, header, stage); break;
-            case 4: quantize_tile<T, NOISE_BITS, VEC, 4>(xs, geo.D, n, g0, groups, geo.ng, lane, k0, k1, tag0, tag1, dst, header, stage); break;
-            case 8: quantize_tile<T, NOISE_BITS, VEC, 8>(xs, geo.D, n, g0, groups, geo.ng, lane, k0, k1, tag0, tag1, dst, header, stage); break;
-            default: return;
-        }
+    const uint32_t wave_in_block = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6)));
+    const uint32_t w = blockIdx.x * kWavesPerBlock + wave_in_block;
+    if (w >= geo.total_tiles) return;
+    uint32_t* stage = stage_all[wave_in_block];
+
+    Cursor ca, cb;
+    ca.n = w / geo.tiles_per_sample;
+    ca.t = w - ca.n * geo.tiles_per_sample;
+    TileRegs ra, rb;
+    fetch<T, VEC>(x, geo, bits, offsets, lane, ca, ra);
+    for (;;) {
+        cb = ca;
+        const bool more_b = advance(geo, cb);
+        fetch<T, VEC>(x, geo, bits, offsets, lane, cb, rb);
+        quantize_one<NOISE_BITS, VEC>(ra, ca, geo, lane, k0, k1, tag0, tag1, packed, capacity, header, stage);
+        if (!more_b) break;
+        ca = cb;
+        const bool more_a = advance(geo, ca);
+        fetch<T, VEC>(x, geo, bits, offsets, lane, ca, ra);
+        quantize_one<NOISE_BITS, VEC>(rb, cb, geo, lane, k0, k1, tag0, tag1, packed, capacity, header, stage);
+        if (!more_a) break;
     }
 }
 
@@ -512,7 +595,7 @@ __global__ __launch_bounds__(kBlock) void unpack_dequantize_kernel(
     uint32_t n, tile, tile_end;
     if (!wave_work(geo, n, tile, tile_end)) return;
     T* os = out + static_cast<int64_t>(n) * geo.D;
-    const uint32_t b = bits[n];
+    const uint32_t b = load_width(bits, n);
     const uint64_t off = offsets[n];
     const uint64_t bytes = static_cast<uint64_t>(geo.ng) * 32u * b;
     if ((off & 31u) != 0 || off > capacity || bytes > capacity - off) return;
@@ -591,36 +674,82 @@ int launch_group_stats(const void* x, int dtype, int64_t N, int64_t D, float* gm
     return check_launch("actq_group_stats");
 }
 
-template <typename T>
-static void launch_quantize_typed(const T* x, const Geometry& geo, dim3 grid, hipStream_t s, bool vec,
-                                  int noise_bits, const uint8_t* bits, const uint64_t* offsets,
-                                  uint64_t seed, uint64_t tag, uint8_t* packed, uint64_t capacity,
-                                  float* header)
+// Resident wavefronts the chip holds for a kernel: occupancy (blocks per CU) x CUs x 4.
+template <typename K>
+static int resident_blocks(K kernel, int* out)
 {
+    int device = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&device) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kBlock, 0) != hipSuccess || cus <= 0 || per_cu <= 0)
+        return fail(ACTQ_EHIP, "actq_quantize_pack: cannot query the device: %s", hipGetErrorString(hipGetLastError()));
+    *out = cus * per_cu;
+    return ACTQ_OK;
+}
+
+template <typename T, int NOISE_BITS, bool VEC>
+static int launch_quantize_variant(const T* x, StreamGeometry geo, hipStream_t s, const uint8_t* bits,
+                                   const uint64_t* offsets, uint64_t seed, uint64_t tag, uint8_t* packed,
+                                   uint64_t capacity, float* header)
+{
+    static int blocks_cache[16] = {0};  // per device; a pure function of the device and the kernel
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) return fail(ACTQ_EHIP, "actq_quantize_pack: no current device");
+    int resident = 0;
+    if (device >= 0 && device < 16 && blocks_cache[device] > 0) {
+        resident = blocks_cache[device];
+    } else {
+        if (int rc = resident_blocks(quantize_pack_kernel<T, NOISE_BITS, VEC>, &resident)) return rc;
+        if (device >= 0 && device < 16) blocks_cache[device] = resident;
+    }
+    const uint32_t want = (geo.total_tiles + kWavesPerBlock - 1) / kWavesPerBlock;
+    const uint32_t blocks = want < static_cast<uint32_t>(resident) ? want : static_cast<uint32_t>(resident);
+    const uint32_t waves = blocks * kWavesPerBlock;
+    geo.step_n = waves / geo.tiles_per_sample;
+    geo.step_t = waves % geo.tiles_per_sample;
     const uint32_t k0 = static_cast<uint32_t>(seed), k1 = static_cast<uint32_t>(seed >> 32);
     const uint32_t t0 = static_cast<uint32_t>(tag), t1 = static_cast<uint32_t>(tag >> 32);
+    quantize_pack_kernel<T, NOISE_BITS, VEC><<<dim3(blocks), kBlock, 0, s>>>(x, geo, bits, offsets, k0, k1, t0, t1, packed, capacity, header);
+    return ACTQ_OK;
+}
+
+template <typename T>
+static int launch_quantize_typed(const T* x, const StreamGeometry& geo, hipStream_t s, bool vec,
+                                 int noise_bits, const uint8_t* bits, const uint64_t* offsets,
+                                 uint64_t seed, uint64_t tag, uint8_t* packed, uint64_t capacity,
+                                 float* header)
+{
     if (noise_bits == 24) {
-        if (vec) quantize_pack_kernel<T, 24, true><<<grid, kBlock, 0, s>>>(x, geo, bits, offsets, k0, k1, t0, t1, packed, capacity, header);
-        else quantize_pack_kernel<T, 24, false><<<grid, kBlock, 0, s>>>(x, geo, bits, offsets, k0, k1, t0, t1, packed, capacity, header);
-    } else {
-        if (vec) quantize_pack_kernel<T, 16, true><<<grid, kBlock, 0, s>>>(x, geo, bits, offsets, k0, k1, t0, t1, packed, capacity, header);
-        else quantize_pack_kernel<T, 16, false><<<grid, kBlock, 0, s>>>(x, geo, bits, offsets, k0, k1, t0, t1, packed, capacity, header);
+        if (vec) return launch_quantize_variant<T, 24, true>(x, geo, s, bits, offsets, seed, tag, packed, capacity, header);
+        return launch_quantize_variant<T, 24, false>(x, geo, s, bits, offsets, seed, tag, packed, capacity, header);
     }
+    if (vec) return launch_quantize_variant<T, 16, true>(x, geo, s, bits, offsets, seed, tag, packed, capacity, header);
+    return launch_quantize_variant<T, 16, false>(x, geo, s, bits, offsets, seed, tag, packed, capacity, header);
 }
 
 int launch_quantize_pack(const void* x, int dtype, int64_t N, int64_t D, const uint8_t* bits,
                          const uint64_t* offsets, uint64_t seed, uint64_t tag, int noise_bits,
                          void* packed, uint64_t capacity, float* header, void* stream)
 {
-    Geometry geo;
-    dim3 grid;
-    if (int rc = make_geometry("actq_quantize_pack", N, D, kTilesPerWaveRead, &geo, &grid)) return rc;
+    const int64_t ng = (D + kGroup - 1) / kGroup;
+    const int64_t tps = (ng + kTileGroups - 1) / kTileGroups;
+    if (N * tps >= (int64_t(1) << 32))
+        return fail(ACTQ_EINVAL, "actq_quantize_pack: tensor too large for one launch (%lld tiles)", (long long)(N * tps));
+    StreamGeometry geo;
+    geo.D = D;
+    geo.N = static_cast<uint32_t>(N);
+    geo.ng = static_cast<uint32_t>(ng);
+    geo.tiles_per_sample = static_cast<uint32_t>(tps);
+    geo.total_tiles = static_cast<uint32_t>(N * tps);
+    geo.step_n = geo.step_t = 0;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool vec = vector_ok(D);
+    int rc;
     if (dtype == ACTQ_F32)
-        launch_quantize_typed(static_cast<const float*>(x), geo, grid, s, vec, noise_bits, bits, offsets, seed, tag, static_cast<uint8_t*>(packed), capacity, header);
+        rc = launch_quantize_typed(static_cast<const float*>(x), geo, s, vec, noise_bits, bits, offsets, seed, tag, static_cast<uint8_t*>(packed), capacity, header);
     else
-        launch_quantize_typed(static_cast<const _Float16*>(x), geo, grid, s, vec, noise_bits, bits, offsets, seed, tag, static_cast<uint8_t*>(packed), capacity, header);
+        rc = launch_quantize_typed(static_cast<const _Float16*>(x), geo, s, vec, noise_bits, bits, offsets, seed, tag, static_cast<uint8_t*>(packed), capacity, header);
+    if (rc) return rc;
     return check_launch("actq_quantize_pack");
 }
 
