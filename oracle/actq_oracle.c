@@ -192,13 +192,23 @@ static void group_scale(float B, float range, float* inv_out, float* scale_out)
 }
 
 /* Sec. 4.1: u = B (h - Z) / R in [0, B]; the code is ceil(u) with probability
- * u - floor(u) and floor(u) otherwise, decided by comparing uniform noise with the
- * fractional part. */
-static unsigned stochastic_code(float h, float mn, float inv, float B, float noise)
+ * u - floor(u) and floor(u) otherwise.  Two realisations of that rule:
+ *   24-bit noise: compare the noise with the fractional part, code = floor(u) + [noise < frac];
+ *   16-bit noise: add the noise and floor, code = floor(u + noise), the sum being one binary32
+ *                 addition.  (floor(u + U) with U uniform on [0,1) rounds up exactly when
+ *                 U >= 1 - frac, i.e. with probability frac.)  With noise on a 2^-16 grid and
+ *                 u <= 255 the sum of an integer u and the noise is exact, so grid points keep
+ *                 their code, and u + noise <= B + 1 - 2^-16 is representable, so the code
+ *                 never exceeds B. */
+static unsigned stochastic_code(float h, float mn, float inv, float B, float noise, int noise_bits)
 {
     float centred = h - mn;
     float u = centred * inv;
     if (u > B) u = B; /* the two roundings above can overshoot B by an ulp */
+    if (noise_bits == 16) {
+        float shifted = u + noise;
+        return (unsigned)floorf(shifted);
+    }
     float fl = floorf(u);
     float frac = u - fl; /* exact */
     return (unsigned)fl + (noise < frac ? 1u : 0u);
@@ -226,7 +236,7 @@ int orc_quantize_group(const void* x, int dtype, int64_t first, int64_t len, int
     for (int64_t j = 0; j < len; ++j) {
         float h = load_elem(x, dtype, first + j);
         float noise = orc_noise(seed, tag, n, d_start + (uint64_t)j, noise_bits);
-        unsigned code = stochastic_code(h, mn, inv, B, noise);
+        unsigned code = stochastic_code(h, mn, inv, B, noise, noise_bits);
         int64_t bitpos = j * b;
         dst[bitpos / 8] |= (uint8_t)(code << (bitpos % 8));
     }
@@ -316,7 +326,7 @@ int orc_quantize_codes(const void* x, int dtype, int64_t N, int64_t D, int32_t G
         for (int64_t j = 0; j < len; ++j) {
             float h = load_elem(x, dtype, n * D + g * G + j);
             float noise = orc_noise(seed, tag, (uint32_t)n, (uint64_t)(g * G + j), noise_bits);
-            codes[n * D + g * G + j] = (uint8_t)stochastic_code(h, mn, inv, B, noise);
+            codes[n * D + g * G + j] = (uint8_t)stochastic_code(h, mn, inv, B, noise, noise_bits);
         }
     }
     return ORC_OK;

@@ -186,7 +186,11 @@ def test_brute_force_tiny_tensor_with_rational_arithmetic(b, noise_bits):
                 else:
                     w = int(words[k >> 1])
                     noise = Fraction((w >> 16) if (k & 1) else (w & 0xffff), 1 << 16)
-                q = fl + (1 if noise < frac else 0)
+                if noise_bits == 24:
+                    q = fl + (1 if noise < frac else 0)
+                else:
+                    # 16-bit noise is added to u in one binary32 addition (numpy's float32 add) and floored
+                    q = int(np.floor(np.float32(min(u32, np.float32(B))) + np.float32(float(noise))))
                 assert codes[n, d] == q, (n, d)
                 bitpos = j * b
                 want_bytes[int(offsets[n]) + g * G * b // 8 + bitpos // 8] |= q << (bitpos % 8)
@@ -341,10 +345,12 @@ def test_rounding_decisions_are_uncorrelated_across_elements(noise_bits):
     assert abs(c.mean()) < 5 / np.sqrt(S * c.size)
 
 
-def test_scaled_value_is_clamped_to_B_before_rounding():
+@pytest.mark.parametrize("noise_bits", [24, 16])
+def test_scaled_value_is_clamped_to_B_before_rounding(noise_bits):
     """The two roundings in (h - Z) * (B / R) can land one ulp above B for the group's
-    maximum.  Without the clamp that element would round up to B + 1 whenever its noise
-    is below that ulp; the test places the maximum exactly on such an element."""
+    maximum.  Without the clamp that element would get code B + 1 whenever its noise is
+    extreme enough (below that ulp when compared, within that ulp of 1 when added); the test
+    places the maximum exactly on such elements."""
     B = np.float32(255.0)
     rng = np.random.default_rng(0)
     r = None
@@ -356,8 +362,11 @@ def test_scaled_value_is_clamped_to_B_before_rounding():
     over = float(np.float32(r * np.float32(B / r))) - 255.0     # one ulp of 255 = 2^-16
     assert over > 0
     seed, D = 321, 1 << 18
-    hits = [d for d in range(D) if oracle.noise(seed, 0, 0, d, 24) < over]
-    assert hits, "no element with small enough noise; enlarge D"
+    if noise_bits == 24:
+        hits = [d for d in range(D) if oracle.noise(seed, 0, 0, d, 24) < over]
+    else:
+        hits = [d for d in range(D) if oracle.noise(seed, 0, 0, d, 16) >= 1.0 - over]
+    assert hits, "no element with extreme enough noise; enlarge D"
     x = np.zeros((1, D), dtype=np.float32)
     x[0, 1::2] = r / 2
     for d in hits:
@@ -365,7 +374,7 @@ def test_scaled_value_is_clamped_to_B_before_rounding():
         g = d // 256
         if x[0, g * 256:(g + 1) * 256].min() != 0.0:
             x[0, g * 256 + (1 if d % 256 == 0 else 0)] = 0.0
-    codes = oracle.quantize_codes(x, np.array([8], dtype=np.uint8), seed)
+    codes = oracle.quantize_codes(x, np.array([8], dtype=np.uint8), seed, noise_bits=noise_bits)
     assert all(codes[0, d] == 255 for d in hits)
 
 
