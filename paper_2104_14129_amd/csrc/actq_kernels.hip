@@ -358,7 +358,7 @@ __device__ __forceinline__ void encode_tile(const TileRegs& td, const uint32_t (
                                             float* __restrict__ header, uint32_t* stage)
 {
     constexpr float kB = static_cast<float>((1 << B) - 1);
-    constexpr float kNoiseGrid = NOISE_BITS == 24 ? 16777216.0f : 65536.0f;
+    constexpr float kNoiseGrid = 16777216.0f;  // 24-bit noise is compared as an integer with frac * 2^24
     const float mn = row_min;
     const float range = row_max - mn;
     float inv = kB / range;
@@ -386,9 +386,16 @@ __device__ __forceinline__ void encode_tile(const TileRegs& td, const uint32_t (
             const float centred = td.v[u][k] - mn_u;
             float scaled = centred * inv_u;
             scaled = fminf(scaled, kB);  // the two roundings can overshoot B by an ulp
-            const float frac = __builtin_amdgcn_fractf(scaled);  // exact for scaled >= 0
-            uint32_t q = static_cast<uint32_t>(scaled);          // truncation = floor
-            q += (static_cast<float>(rnd[u][k]) < frac * kNoiseGrid) ? 1u : 0u;
+            uint32_t q;
+            if (NOISE_BITS == 16) {
+                // add and floor: noise * 2^-16 is exact, so the fma is the single binary32
+                // addition u + noise; the sum is non-negative, truncation = floor
+                q = static_cast<uint32_t>(__builtin_fmaf(static_cast<float>(rnd[u][k]), 1.52587890625e-05f, scaled));
+            } else {
+                const float frac = __builtin_amdgcn_fractf(scaled);  // exact for scaled >= 0
+                q = static_cast<uint32_t>(scaled);                   // truncation = floor
+                q += (static_cast<float>(rnd[u][k]) < frac * kNoiseGrid) ? 1u : 0u;
+            }
             if (!VEC) q = td.ok[u][k] ? q : 0u;
             piece[u] |= q << (k * B);
         }
@@ -491,11 +498,19 @@ __device__ __forceinline__ void quantize_one(const TileRegs& r, const Cursor& c,
     float row_min, row_max;
     tile_min_max(lo, hi, lane, row_min, row_max);
     row_min += 0.0f;  // -0.0 -> +0.0
+    // Pin the order: the tile's HBM loads and the noise come before the wavefront looks at the
+    // sample's width and offset.  Without this the early exit below is hoisted to the top and a
+    // fresh wavefront first sits through dependent scalar loads before it issues any HBM load.
+    uint32_t b = c.b, off_lo = static_cast<uint32_t>(c.off), off_hi = static_cast<uint32_t>(c.off >> 32);
+    asm volatile("" : "+v"(row_min), "+v"(b), "+v"(off_lo), "+v"(off_hi));
+    b = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(b)));
+    const uint64_t off = static_cast<uint64_t>(static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(off_lo)))) |
+                         (static_cast<uint64_t>(static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(off_hi)))) << 32);
     // a sample whose width or byte range is invalid is skipped, nothing is written
-    const uint64_t bytes = static_cast<uint64_t>(geo.ng) * 32u * c.b;
-    if ((c.off & 31u) != 0 || c.off > capacity || bytes > capacity - c.off) return;
-    uint8_t* dst = packed + c.off;
-    switch (c.b) {
+    const uint64_t bytes = static_cast<uint64_t>(geo.ng) * 32u * b;
+    if ((off & 31u) != 0 || off > capacity || bytes > capacity - off) return;
+    uint8_t* dst = packed + off;
+    switch (b) {
         case 1: encode_tile<NOISE_BITS, VEC, 1>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, stage); break;
         case 2: encode_tile<NOISE_BITS, VEC, 2>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, stage); break;
         case 4: encode_tile<NOISE_BITS, VEC, 4>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, stage); break;
@@ -540,6 +555,28 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(
         quantize_one<NOISE_BITS, VEC>(rb, cb, geo, lane, k0, k1, tag0, tag1, packed, capacity, header, stage);
         if (!more_a) break;
     }
+}
+
+// One tile per wavefront (grid.x = tiles of a sample, grid.y * grid.z = samples): the
+// alternative launch shape of the same work.  Short-lived wavefronts lose the least HBM
+// bandwidth to the small writes of codes and headers, so this shape wins when the per-tile
+// ALU work is light enough to hide behind other wavefronts' loads (16-bit noise).
+template <typename T, int NOISE_BITS, bool VEC>
+__global__ __launch_bounds__(kBlock) void quantize_pack_tile_kernel(
+    const T* __restrict__ x, StreamGeometry geo, uint32_t grid_y, const uint8_t* __restrict__ bits,
+    const uint64_t* __restrict__ offsets, uint32_t k0, uint32_t k1, uint32_t tag0, uint32_t tag1,
+    uint8_t* __restrict__ packed, uint64_t capacity, float* __restrict__ header)
+{
+    __shared__ uint32_t stage_all[kWavesPerBlock][256];
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint32_t wave_in_block = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6)));
+    Cursor c;
+    c.n = blockIdx.z * grid_y + blockIdx.y;
+    c.t = blockIdx.x * kWavesPerBlock + wave_in_block;
+    if (c.n >= geo.N || c.t >= geo.tiles_per_sample) return;
+    TileRegs r;
+    fetch<T, VEC>(x, geo, bits, offsets, lane, c, r);
+    quantize_one<NOISE_BITS, VEC>(r, c, geo, lane, k0, k1, tag0, tag1, packed, capacity, header, stage_all[wave_in_block]);
 }
 
 // ------------------------------------------------------------------------------------
@@ -687,11 +724,26 @@ static int resident_blocks(K kernel, int* out)
     return ACTQ_OK;
 }
 
+// Launch shape per noise mode, from measurement on MI355X: the 24-bit comparison path is
+// bound by the vector ALU and gains from the persistent pipeline; the lighter 16-bit path is
+// bound by HBM and is fastest as one tile per wavefront.
+constexpr bool persistent_shape(int noise_bits) { return noise_bits == 24; }
+
 template <typename T, int NOISE_BITS, bool VEC>
 static int launch_quantize_variant(const T* x, StreamGeometry geo, hipStream_t s, const uint8_t* bits,
                                    const uint64_t* offsets, uint64_t seed, uint64_t tag, uint8_t* packed,
                                    uint64_t capacity, float* header)
 {
+    const uint32_t k0 = static_cast<uint32_t>(seed), k1 = static_cast<uint32_t>(seed >> 32);
+    const uint32_t t0 = static_cast<uint32_t>(tag), t1 = static_cast<uint32_t>(tag >> 32);
+    if (!persistent_shape(NOISE_BITS)) {
+        const uint32_t gx = (geo.tiles_per_sample + kWavesPerBlock - 1) / kWavesPerBlock;
+        const uint32_t gy = geo.N < 65535u ? geo.N : 65535u;
+        const uint32_t gz = (geo.N + gy - 1) / gy;
+        if (gz > 65535u) return fail(ACTQ_EINVAL, "actq_quantize_pack: too many samples for one launch");
+        quantize_pack_tile_kernel<T, NOISE_BITS, VEC><<<dim3(gx, gy, gz), kBlock, 0, s>>>(x, geo, gy, bits, offsets, k0, k1, t0, t1, packed, capacity, header);
+        return ACTQ_OK;
+    }
     static int blocks_cache[16] = {0};  // per device; a pure function of the device and the kernel
     int device = 0;
     if (hipGetDevice(&device) != hipSuccess) return fail(ACTQ_EHIP, "actq_quantize_pack: no current device");
@@ -707,8 +759,6 @@ static int launch_quantize_variant(const T* x, StreamGeometry geo, hipStream_t s
     const uint32_t waves = blocks * kWavesPerBlock;
     geo.step_n = waves / geo.tiles_per_sample;
     geo.step_t = waves % geo.tiles_per_sample;
-    const uint32_t k0 = static_cast<uint32_t>(seed), k1 = static_cast<uint32_t>(seed >> 32);
-    const uint32_t t0 = static_cast<uint32_t>(tag), t1 = static_cast<uint32_t>(tag >> 32);
     quantize_pack_kernel<T, NOISE_BITS, VEC><<<dim3(blocks), kBlock, 0, s>>>(x, geo, bits, offsets, k0, k1, t0, t1, packed, capacity, header);
     return ACTQ_OK;
 }
