@@ -93,16 +93,19 @@ int actq_group_stats(const void* x, actq_dtype dt, int64_t N, int64_t D, int32_t
  * B = 2^b - 1:  inv = B / R,  scale = R / B  (binary32, round to nearest);
  * a group whose R is zero, or whose B / R overflows, has inv = scale = 0.
  * For every element: u = min((x - Z) * inv, B), two separately rounded
- * binary32 operations; code = floor(u) + [noise < u - floor(u)].
- *
- * noise is uniform on a grid of 2^noise_bits points in [0,1), taken from
- * Philox4x32-10 (Salmon et al., SC'11) keyed by `seed`, so a call is exactly
- * reproducible.  With d the feature index inside sample n:
+ * binary32 operations, then stochastic rounding (ceil(u) with probability
+ * u - floor(u), floor(u) otherwise) driven by uniform noise from Philox4x32-10
+ * (Salmon et al., SC'11) keyed by `seed`, so a call is exactly reproducible.
+ * With d the feature index inside sample n:
  *   noise_bits = 24: counter (d>>2, n, lo32(tag), hi32(tag)), element d takes
- *                    output word d&3 and noise = (word >> 8) * 2^-24;
+ *                    output word d&3, noise = (word >> 8) * 2^-24, and
+ *                    code = floor(u) + [noise < u - floor(u)];
  *   noise_bits = 16: counter (d>>3, n, lo32(tag), hi32(tag)), element d takes
  *                    word (d>>1)&3, low half if d is even, high half if odd,
- *                    and noise = half * 2^-16.
+ *                    noise = half * 2^-16, and code = floor(u + noise), the sum
+ *                    being one binary32 addition (it rounds up exactly when
+ *                    noise >= 1 - frac(u)).  This is the fast mode: one
+ *                    generator call serves eight elements.
  * key = (lo32(seed), hi32(seed)).  `tag` separates tensors (layers) that share
  * a seed.  Requires N < 2^32 and D < 2^34.
  *
