@@ -622,6 +622,72 @@ __device__ __forceinline__ void dequantize_tile(const uint8_t* __restrict__ src_
     }
 }
 
+// binary16 output: a lane that owned four elements would store only 8 bytes, so here a lane
+// takes eight consecutive elements (16 bytes) and the wavefront covers two groups per step
+// (lanes 0..31 the even group, lanes 32..63 the odd one).  Unpacking is free to choose its
+// lane-to-element map: nothing is reduced across lanes.
+template <bool VEC, int B>
+__device__ __forceinline__ void dequantize_tile_f16(const uint8_t* __restrict__ src_sample,
+                                                    const float* __restrict__ header, _Float16* os,
+                                                    int64_t D, uint32_t n, uint32_t g0, int groups,
+                                                    uint32_t ng, int lane)
+{
+    typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+    constexpr uint32_t code_mask = (1u << B) - 1u;
+    const int half = lane >> 5;   // which group of the pair
+    const int li = lane & 31;     // position inside the group: elements 8*li .. 8*li+7
+    uint32_t code_lo[2] = {0, 0}, code_hi[2] = {0, 0};  // 8*B bits per lane; the high word only for B = 8
+    f32x2 hd[2];
+    bool live[2];
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const int u = 2 * p + half;
+        live[p] = u < groups;
+        const uint32_t g = g0 + (live[p] ? u : 0);  // a dead lane re-reads the tile's first group
+        const uint8_t* src = src_sample + static_cast<uint64_t>(g) * (32 * B) + li * B;  // 8*B bits per lane
+        if (B == 1) code_lo[p] = __builtin_nontemporal_load(src);
+        if (B == 2) code_lo[p] = __builtin_nontemporal_load(reinterpret_cast<const uint16_t*>(src));
+        if (B == 4) code_lo[p] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(src));
+        if (B == 8) {
+            const u32x2 w = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(src));
+            code_lo[p] = w.x;
+            code_hi[p] = w.y;
+        }
+        hd[p] = *reinterpret_cast<const f32x2*>(header + 2 * (static_cast<int64_t>(n) * ng + g));
+    }
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const uint32_t g = g0 + 2 * p + half;
+        f16x8 o;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const uint32_t word = (k * B < 32) ? code_lo[p] : code_hi[p];
+            const uint32_t q = (word >> ((k * B) & 31)) & code_mask;
+            o[k] = Io<_Float16>::narrow(__builtin_fmaf(static_cast<float>(q), hd[p].y, hd[p].x));
+        }
+        const int64_t d0 = (static_cast<int64_t>(g) << 8) + li * 8;
+        if (!live[p]) continue;
+        if (VEC) {
+            __builtin_nontemporal_store(o, reinterpret_cast<f16x8*>(os + d0));
+        } else {
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                if (d0 + k < D) os[d0 + k] = o[k];
+        }
+    }
+}
+
+template <typename T, bool VEC, int B>
+__device__ __forceinline__ void dequantize_any(const uint8_t* __restrict__ src_sample,
+                                               const float* __restrict__ header, T* os, int64_t D,
+                                               uint32_t n, uint32_t g0, int groups, uint32_t ng, int lane)
+{
+    if constexpr (sizeof(T) == 2)
+        dequantize_tile_f16<VEC, B>(src_sample, header, os, D, n, g0, groups, ng, lane);
+    else
+        dequantize_tile<T, VEC, B>(src_sample, header, os, D, n, g0, groups, ng, lane);
+}
+
 template <typename T, bool VEC>
 __global__ __launch_bounds__(kBlock) void unpack_dequantize_kernel(
     const uint8_t* __restrict__ packed, uint64_t capacity, const float* __restrict__ header,
@@ -641,10 +707,10 @@ __global__ __launch_bounds__(kBlock) void unpack_dequantize_kernel(
         const uint32_t g0 = tile * kTileGroups;
         const int groups = static_cast<int>(min(static_cast<uint32_t>(kTileGroups), geo.ng - g0));
         switch (b) {
-            case 1: dequantize_tile<T, VEC, 1>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
-            case 2: dequantize_tile<T, VEC, 2>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
-            case 4: dequantize_tile<T, VEC, 4>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
-            case 8: dequantize_tile<T, VEC, 8>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
+            case 1: dequantize_any<T, VEC, 1>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
+            case 2: dequantize_any<T, VEC, 2>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
+            case 4: dequantize_any<T, VEC, 4>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
+            case 8: dequantize_any<T, VEC, 8>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
             default: return;
         }
     }
