@@ -26,6 +26,7 @@
 // and a multiplication that are rounded separately.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdint>
 
 #include "actq_internal.h"
@@ -810,15 +811,14 @@ static int launch_quantize_variant(const T* x, StreamGeometry geo, hipStream_t s
         quantize_pack_tile_kernel<T, NOISE_BITS, VEC><<<dim3(gx, gy, gz), kBlock, 0, s>>>(x, geo, gy, bits, offsets, k0, k1, t0, t1, packed, capacity, header);
         return ACTQ_OK;
     }
-    static int blocks_cache[16] = {0};  // per device; a pure function of the device and the kernel
+    // memo per device of a pure function of (device, kernel); racing threads store the same value
+    static std::atomic<int> blocks_cache[16];
     int device = 0;
     if (hipGetDevice(&device) != hipSuccess) return fail(ACTQ_EHIP, "actq_quantize_pack: no current device");
-    int resident = 0;
-    if (device >= 0 && device < 16 && blocks_cache[device] > 0) {
-        resident = blocks_cache[device];
-    } else {
+    int resident = (device >= 0 && device < 16) ? blocks_cache[device].load(std::memory_order_relaxed) : 0;
+    if (resident <= 0) {
         if (int rc = resident_blocks(quantize_pack_kernel<T, NOISE_BITS, VEC>, &resident)) return rc;
-        if (device >= 0 && device < 16) blocks_cache[device] = resident;
+        if (device >= 0 && device < 16) blocks_cache[device].store(resident, std::memory_order_relaxed);
     }
     const uint32_t want = (geo.total_tiles + kWavesPerBlock - 1) / kWavesPerBlock;
     const uint32_t blocks = want < static_cast<uint32_t>(resident) ? want : static_cast<uint32_t>(resident);

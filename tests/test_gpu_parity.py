@@ -173,6 +173,29 @@ def test_non_default_stream():
     assert np.array_equal(out.cpu().numpy(), want)
 
 
+def test_more_samples_than_one_grid_dimension_holds():
+    """N > 65535 exercises the split of the sample index over two grid dimensions."""
+    N, D = 70001, 256
+    rng = np.random.default_rng(9)
+    x = rng.standard_normal((N, D)).astype(np.float32)
+    bits = rng.choice([1, 2, 4, 8], N).astype(np.uint8)
+    _round_trip(x, bits, seed=3, tag=1, noise_bits=16)
+    _round_trip(x[:66000], bits[:66000], seed=3, tag=1, noise_bits=24)
+
+
+def test_unaligned_device_arrays_are_rejected():
+    x = torch.zeros((8, 256), device="cuda:0")
+    bits = torch.full((12,), 2, dtype=torch.uint8, device="cuda:0")
+    offs = torch.arange(8, dtype=torch.int64, device="cuda:0") * 64
+    packed = torch.zeros(8 * 64, dtype=torch.uint8, device="cuda:0")
+    header = torch.zeros(8 * 2, device="cuda:0")
+    with pytest.raises(B.ActqError) as e:
+        B.quantize_pack(x, bits[1:9], offs, packed, header, 1)
+    assert e.value.code == B.ACTQ_EINVAL and "bits" in str(e.value)
+    with pytest.raises(B.ActqError):
+        B.quantize_pack(x.view(-1)[1:257 + 256 * 6].view(7, 256), bits[:7], offs[:7], packed, header[:14], 1)
+
+
 # ----------------------------------------------------------------------------- full sizes
 
 def _full_size(wl, noise_bits, out_dtype):
