@@ -64,6 +64,18 @@ def lib() -> ctypes.CDLL:
         L.orc_quantize_group.argtypes = [vp, c.c_int, i64, i64, i32, c.c_int, u64, u64, c.c_uint32, u64, i32, vp, vp]
         L.orc_dequantize_group.restype = c.c_int
         L.orc_dequantize_group.argtypes = [vp, vp, c.c_int, i64, vp, c.c_int, i64]
+        L.orc_bf16_to_float.restype = c.c_float
+        L.orc_bf16_to_float.argtypes = [c.c_uint16]
+        L.orc_bf16_floor.restype = c.c_uint16
+        L.orc_bf16_floor.argtypes = [c.c_float]
+        L.orc_bf16_ceil.restype = c.c_uint16
+        L.orc_bf16_ceil.argtypes = [c.c_float]
+        L.orc_quantize_pack_bf16.restype = c.c_int
+        L.orc_quantize_pack_bf16.argtypes = [vp, c.c_int, i64, i64, i32, vp, vp, u64, u64, i32, vp, vp]
+        L.orc_unpack_dequantize_bf16.restype = c.c_int
+        L.orc_unpack_dequantize_bf16.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp, c.c_int]
+        L.orc_sample_sensitivity.restype = c.c_int
+        L.orc_sample_sensitivity.argtypes = [vp, i64, i64, i32, vp, vp]
         L.orc_quantize_codes.restype = c.c_int
         L.orc_quantize_codes.argtypes = [vp, c.c_int, i64, i64, i32, vp, u64, u64, i32, vp]
         L.orc_unpack_dequantize.restype = c.c_int
@@ -172,6 +184,63 @@ def quantize_pack(x: np.ndarray, bits, seed: int, tag: int = 0, G: int = 256,
     if rc != OK:
         raise OracleError(rc, "quantize_pack")
     return packed, header, offsets
+
+
+HDR_F32, HDR_BF16 = 0, 1
+
+
+def bf16_floor(f: float) -> int:
+    return int(lib().orc_bf16_floor(f))
+
+
+def bf16_ceil(f: float) -> int:
+    return int(lib().orc_bf16_ceil(f))
+
+
+def bf16_to_float(h: int) -> float:
+    return float(lib().orc_bf16_to_float(h))
+
+
+def quantize_pack_bf16(x: np.ndarray, bits, seed: int, tag: int = 0, G: int = 256, noise_bits: int = 24):
+    """As quantize_pack, with the header stored as bfloat16 (Z rounded down, R rounded up):
+    returns (packed uint8[total], header uint16[N, ng, 2] = (Z, R) bit patterns, offsets)."""
+    x2 = _as2d(x)
+    N, D = x2.shape
+    ng = (D + G - 1) // G
+    bits = np.ascontiguousarray(bits, dtype=np.uint8)
+    offsets, total = packed_bytes(N, D, G, bits)
+    packed = np.zeros(total, dtype=np.uint8)
+    header = np.empty((N, ng, 2), dtype=np.uint16)
+    rc = lib().orc_quantize_pack_bf16(_p(x2), _dtype_code(x2), N, D, G, _p(bits), _p(offsets),
+                                      seed, tag, noise_bits, _p(packed), _p(header))
+    if rc != OK:
+        raise OracleError(rc, "quantize_pack_bf16")
+    return packed, header, offsets
+
+
+def unpack_dequantize_bf16(packed, header, bits, offsets, N: int, D: int, G: int = 256, out_dtype=np.float32):
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    header = np.ascontiguousarray(header, dtype=np.uint16)
+    bits = np.ascontiguousarray(bits, dtype=np.uint8)
+    offsets = np.ascontiguousarray(offsets, dtype=np.uint64)
+    out = np.empty((N, D), dtype=out_dtype)
+    rc = lib().orc_unpack_dequantize_bf16(_p(packed), _p(header), _p(bits), _p(offsets), N, D, G,
+                                          _p(out), _dtype_code(out))
+    if rc != OK:
+        raise OracleError(rc, "unpack_dequantize_bf16")
+    return out
+
+
+def sample_sensitivity(grange: np.ndarray, G: int = 256, grad2=None) -> np.ndarray:
+    """w_n = (G/6) * grad2_n * sum_g R_ng^2 (grad2 = None means 1), float32 [N]."""
+    grange = np.ascontiguousarray(grange, dtype=np.float32)
+    N, ng = grange.shape
+    w = np.empty(N, dtype=np.float32)
+    g2 = None if grad2 is None else np.ascontiguousarray(grad2, dtype=np.float32)
+    rc = lib().orc_sample_sensitivity(_p(grange), N, ng, G, None if g2 is None else _p(g2), _p(w))
+    if rc != OK:
+        raise OracleError(rc, "sample_sensitivity")
+    return w
 
 
 def quantize_group(xg: np.ndarray, b: int, seed: int, tag: int, n: int, d_start: int,

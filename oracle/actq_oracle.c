@@ -305,6 +305,151 @@ int orc_unpack_dequantize(const uint8_t* packed, const float* header,
     return ORC_OK;
 }
 
+/* ------------------------------------------------------------------------- */
+/* Sec. 4.1, last paragraph: the per-group range and zero point stored in       */
+/* bfloat16, 32 bits per group.  So that every element still scales into [0, B] */
+/* the zero point is rounded DOWN to bfloat16 and the range, taken from that     */
+/* rounded zero point, is rounded UP; the quantizer stays unbiased because it is */
+/* unbiased for any (Z, R) that cover the group.                                 */
+
+float orc_bf16_to_float(uint16_t h)
+{
+    uint32_t u = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+/* largest bfloat16 value <= f (f finite) */
+uint16_t orc_bf16_floor(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    uint32_t top = u >> 16;
+    if ((u & 0xffffu) != 0 && (u >> 31)) top += 1; /* negative: truncation moved it up, step down */
+    return (uint16_t)top;
+}
+
+/* smallest bfloat16 value >= f (f finite) */
+uint16_t orc_bf16_ceil(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    uint32_t top = u >> 16;
+    if ((u & 0xffffu) != 0 && !(u >> 31)) top += 1; /* positive: truncation moved it down, step up */
+    return (uint16_t)top;
+}
+
+static void group_min_max(const void* x, int dtype, int64_t base, int64_t len, float* mn_out, float* mx_out)
+{
+    float mn = load_elem(x, dtype, base), mx = mn;
+    for (int64_t j = 1; j < len; ++j) {
+        float v = load_elem(x, dtype, base + j);
+        if (v < mn) mn = v;
+        if (v > mx) mx = v;
+    }
+    *mn_out = mn + 0.0f;
+    *mx_out = mx;
+}
+
+int orc_quantize_group_bf16(const void* x, int dtype, int64_t first, int64_t len, int32_t G, int b,
+                            uint64_t seed, uint64_t tag, uint32_t n, uint64_t d_start,
+                            int32_t noise_bits, uint8_t* dst, uint16_t* header2)
+{
+    if (!x || !dst || !header2 || len <= 0 || len > G || !width_ok(b)) return ORC_EINVAL;
+    if (noise_bits != 24 && noise_bits != 16) return ORC_EINVAL;
+    float B = (float)((1 << b) - 1);
+    float mn, mx;
+    group_min_max(x, dtype, first, len, &mn, &mx);
+    uint16_t zb = orc_bf16_floor(mn);
+    float z = orc_bf16_to_float(zb);
+    float span = mx - z;                       /* from the stored zero point */
+    uint16_t rb = orc_bf16_ceil(span);
+    float r = orc_bf16_to_float(rb);
+    float inv, scale;
+    if (!isfinite(r)) r = 0.0f;                /* rounding up overflowed: treat as degenerate */
+    group_scale(B, r, &inv, &scale);
+    if (inv == 0.0f) rb = 0;                   /* degenerate groups store R = 0 */
+    header2[0] = zb;
+    header2[1] = rb;
+    memset(dst, 0, (size_t)G * b / 8);
+    for (int64_t j = 0; j < len; ++j) {
+        float h = load_elem(x, dtype, first + j);
+        float noise = orc_noise(seed, tag, n, d_start + (uint64_t)j, noise_bits);
+        unsigned code = stochastic_code(h, z, inv, B, noise, noise_bits);
+        int64_t bitpos = j * b;
+        dst[bitpos / 8] |= (uint8_t)(code << (bitpos % 8));
+    }
+    return ORC_OK;
+}
+
+int orc_quantize_pack_bf16(const void* x, int dtype, int64_t N, int64_t D, int32_t G,
+                           const uint8_t* bits, const uint64_t* offsets,
+                           uint64_t seed, uint64_t tag, int32_t noise_bits,
+                           uint8_t* packed, uint16_t* header)
+{
+    if (!x || !bits || !offsets || !packed || !header) return ORC_EINVAL;
+    if (N <= 0 || D <= 0 || G <= 0 || (G % 8) != 0) return ORC_EINVAL;
+    if (noise_bits != 24 && noise_bits != 16) return ORC_EINVAL;
+    for (int64_t n = 0; n < N; ++n)
+        if (!width_ok(bits[n])) return ORC_EINVAL;
+    int64_t ng = (D + G - 1) / G;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < N * ng; ++t) {
+        int64_t n = t / ng, g = t % ng;
+        int b = bits[n];
+        int64_t len = (g * G + G <= D) ? G : D - g * G;
+        uint8_t* dst = packed + offsets[n] + (uint64_t)g * G * b / 8;
+        orc_quantize_group_bf16(x, dtype, n * D + g * G, len, G, b, seed, tag, (uint32_t)n,
+                                (uint64_t)(g * G), noise_bits, dst, &header[2 * t]);
+    }
+    return ORC_OK;
+}
+
+/* Sec. 4.1: h^ = code * R / B + Z from the bfloat16 header: the step R / B is one binary32
+ * division, then one fused multiply-add. */
+int orc_unpack_dequantize_bf16(const uint8_t* packed, const uint16_t* header,
+                               const uint8_t* bits, const uint64_t* offsets,
+                               int64_t N, int64_t D, int32_t G, void* out, int out_dtype)
+{
+    if (!packed || !header || !bits || !offsets || !out) return ORC_EINVAL;
+    if (N <= 0 || D <= 0 || G <= 0 || (G % 8) != 0) return ORC_EINVAL;
+    for (int64_t n = 0; n < N; ++n)
+        if (!width_ok(bits[n])) return ORC_EINVAL;
+    int64_t ng = (D + G - 1) / G;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < N * ng; ++t) {
+        int64_t n = t / ng, g = t % ng;
+        int b = bits[n];
+        int64_t len = (g * G + G <= D) ? G : D - g * G;
+        const uint8_t* src = packed + offsets[n] + (uint64_t)g * G * b / 8;
+        float hd[2];
+        hd[0] = orc_bf16_to_float(header[2 * t + 0]);
+        hd[1] = orc_bf16_to_float(header[2 * t + 1]) / (float)((1 << b) - 1);
+        orc_dequantize_group(src, hd, b, len, out, out_dtype, n * D + g * G);
+    }
+    return ORC_OK;
+}
+
+/* Sec. 4.2, Eq. (8) and the sentence after Prob. (9): the sensitivity of sample n of a linear
+ * layer is w_n = (G / 6) * ||grad_n||^2 * ||R_n||^2, with R_n the vector of its group ranges.
+ * grad2 may be NULL (then ||grad_n||^2 = 1).  Accumulated in double. */
+int orc_sample_sensitivity(const float* grange, int64_t N, int64_t ng, int32_t G,
+                           const float* grad2, float* w_out)
+{
+    if (!grange || !w_out || N <= 0 || ng <= 0 || G <= 0) return ORC_EINVAL;
+    for (int64_t n = 0; n < N; ++n) {
+        double acc = 0.0;
+        for (int64_t g = 0; g < ng; ++g) {
+            double r = grange[n * ng + g];
+            acc += r * r;
+        }
+        double w = (double)G / 6.0 * acc * (grad2 ? (double)grad2[n] : 1.0);
+        w_out[n] = (float)w;
+    }
+    return ORC_OK;
+}
+
 /* Codes alone (no packing), for tests that look at the rounding itself. */
 int orc_quantize_codes(const void* x, int dtype, int64_t N, int64_t D, int32_t G,
                        const uint8_t* bits, uint64_t seed, uint64_t tag,
