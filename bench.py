@@ -34,6 +34,8 @@ def parse():
     p.add_argument("--warmup", type=int, default=5)
     p.add_argument("--workload", default="r50_stage1", choices=["r50_stage1", "tiny", "r50_stem_f16", "fpn", "r50_sweep"])
     p.add_argument("--noise-bits", type=int, default=16, choices=[24, 16])
+    p.add_argument("--header", default="f32", choices=["f32", "bf16"],
+                   help="group header format: (Z, R/B) binary32, 8 B/group, or (Z, R) bfloat16, 4 B/group")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--profile-pass", action="store_true",
                    help="for rocprofv3 counter runs: a few launches of each kernel plus a plain device copy "
@@ -41,12 +43,13 @@ def parse():
     return p.parse_args()
 
 
-def algorithmic_bytes(N, D, ng, elem_bytes, code_bytes):
-    """Bytes each kernel must move per launch: input or output tensor, bit stream, 8-byte headers."""
+def algorithmic_bytes(N, D, ng, elem_bytes, code_bytes, header_group_bytes=8):
+    """Bytes each kernel must move per launch: input or output tensor, bit stream, group headers
+    (group_stats always writes 4 + 4 bytes per group)."""
     tensor = N * D * elem_bytes
-    hdr = N * ng * 8
+    hdr = N * ng * header_group_bytes
     return {
-        "group_stats": tensor + hdr,
+        "group_stats": tensor + N * ng * 8,
         "quantize_pack": tensor + code_bytes + hdr,
         "unpack_dequantize": code_bytes + hdr + tensor,
     }
@@ -125,11 +128,11 @@ def sweep(args, torch, B, synth, dev):
             if ev is not None:
                 ev[3 * l][1].record(stream)
                 ev[3 * l + 1][0].record(stream)
-            rc |= lib.actq_quantize_pack(xp, B.ACTQ_F32, N, D, G, bp, op, 15, l, args.noise_bits, pk, packed_capacity, hd, sp)
+            rc |= lib.actq_quantize_pack(xp, B.ACTQ_F32, N, D, G, bp, op, 15, l, args.noise_bits, pk, packed_capacity, hd, B.ACTQ_HDR_F32, sp)
             if ev is not None:
                 ev[3 * l + 1][1].record(stream)
                 ev[3 * l + 2][0].record(stream)
-            rc |= lib.actq_unpack_dequantize(pk, packed_capacity, hd, bp, op, N, D, G, o, B.ACTQ_F32, sp)
+            rc |= lib.actq_unpack_dequantize(pk, packed_capacity, hd, B.ACTQ_HDR_F32, bp, op, N, D, G, o, B.ACTQ_F32, sp)
             if ev is not None:
                 ev[3 * l + 2][1].record(stream)
             if rc:
@@ -210,7 +213,8 @@ def main():
     grange = torch.empty((N, ng), dtype=torch.float32, device=dev)
     _, worst_total = B.packed_bytes(N, D, np.full(N, 8, dtype=np.uint8), G)
     packed_buf = torch.empty(worst_total, dtype=torch.uint8, device=dev)
-    header = torch.empty((N, ng, 2), dtype=torch.float32, device=dev)
+    hf = B.ACTQ_HDR_BF16 if args.header == "bf16" else B.ACTQ_HDR_F32
+    header = torch.empty((N, ng, 2), dtype=torch.int16 if hf == B.ACTQ_HDR_BF16 else torch.float32, device=dev)
     out = torch.empty((N, D), dtype=x.dtype, device=dev)
     bits_pin = torch.empty(N, dtype=torch.uint8, pin_memory=True)
     offs_pin = torch.empty(N, dtype=torch.int64, pin_memory=True)
@@ -238,10 +242,10 @@ def main():
         offs_dev.copy_(offs_pin, non_blocking=True)
         packed = packed_buf[:total]
         mark("quantize_pack", 0)
-        B.quantize_pack(x, bits_dev, offs_dev, packed, header, wl.philox_seed, wl.tag, args.noise_bits, G, stream=stream)
+        B.quantize_pack(x, bits_dev, offs_dev, packed, header, wl.philox_seed, wl.tag, args.noise_bits, G, stream=stream, hf=hf)
         mark("quantize_pack", 1)
         mark("unpack_dequantize", 0)
-        B.unpack_dequantize(packed, header, bits_dev, offs_dev, out, G, stream=stream)
+        B.unpack_dequantize(packed, header, bits_dev, offs_dev, out, G, stream=stream, hf=hf)
         mark("unpack_dequantize", 1)
         state["bits"], state["total"] = bits, total
 
@@ -275,7 +279,7 @@ def main():
         kernel_ms[name] = float(np.mean([a.elapsed_time(b) for a, b in zip(starts, stops)]))
 
     in_bytes = N * D * wl.elem_bytes
-    alg = algorithmic_bytes(N, D, ng, wl.elem_bytes, state["total"])
+    alg = algorithmic_bytes(N, D, ng, wl.elem_bytes, state["total"], 4 if hf == B.ACTQ_HDR_BF16 else 8)
     per_kernel = {k: {"ms": kernel_ms[k], "input_GBps": in_bytes / kernel_ms[k] / 1e6,
                       "algorithmic_GBps": alg[k] / kernel_ms[k] / 1e6,
                       "frac_of_hbm_peak": alg[k] / kernel_ms[k] / 1e6 / HBM_PEAK_GBS} for k in kernel_ms}
@@ -291,8 +295,12 @@ def main():
         import oracle
         t = time.perf_counter()
         oracle.group_stats(x_np, G)
-        opacked, oheader, ooff = oracle.quantize_pack(x_np, wl.bits, wl.philox_seed, wl.tag, G, args.noise_bits)
-        oracle.unpack_dequantize(opacked, oheader, wl.bits, ooff, N, D, G, out_dtype=x_np.dtype)
+        if hf == B.ACTQ_HDR_BF16:
+            opacked, oheader, ooff = oracle.quantize_pack_bf16(x_np, wl.bits, wl.philox_seed, wl.tag, G, args.noise_bits)
+            oracle.unpack_dequantize_bf16(opacked, oheader, wl.bits, ooff, N, D, G, out_dtype=x_np.dtype)
+        else:
+            opacked, oheader, ooff = oracle.quantize_pack(x_np, wl.bits, wl.philox_seed, wl.tag, G, args.noise_bits)
+            oracle.unpack_dequantize(opacked, oheader, wl.bits, ooff, N, D, G, out_dtype=x_np.dtype)
         cpu_s = time.perf_counter() - t
         cpu_baseline = {"value": in_bytes / cpu_s / 1e9, "unit": "GB/s", "cores": oracle.threads(),
                         "kind": "oracle",
@@ -313,7 +321,7 @@ def main():
         "dtype": wl.dtype,
         "data": "synthetic",
         "config": {"workload": wl.name, "G": G, "mean_bits": float(wl.bits.astype(np.float64).mean()),
-                   "noise_bits": args.noise_bits,
+                   "noise_bits": args.noise_bits, "header": args.header,
                    "step": "group_stats + allocate_bits(host) + quantize_pack + unpack_dequantize"},
         "kernels": per_kernel,
         "roofline": roofline,

@@ -47,6 +47,14 @@ typedef enum actq_dtype {
     ACTQ_F16 = 1  /* IEEE binary16; widened exactly to binary32 before any arithmetic */
 } actq_dtype;
 
+/* Per-group header kept beside the codes. */
+typedef enum actq_header_format {
+    ACTQ_HDR_F32 = 0, /* (Z, R/B) in binary32: 8 bytes per group, 0.25 bit per element at G = 256 */
+    ACTQ_HDR_BF16 = 1 /* (Z, R) in bfloat16 as in Sec. 4.1: 4 bytes per group, 0.125 bit per
+                         element.  Z is rounded down to bfloat16 and R = max - Z is rounded up, so
+                         every element still scales into [0, B]; a degenerate group stores R = 0 */
+} actq_header_format;
+
 /* Library version, major*10000 + minor*100 + patch. */
 int actq_version(void);
 
@@ -73,6 +81,9 @@ const char* actq_last_error(void);
  */
 int actq_packed_bytes(int64_t N, int64_t D, int32_t G, const uint8_t* bits_host,
                       uint64_t* offsets_host, uint64_t* total_host);
+
+/* Bytes of the header array for N*ng groups in format hf (host arithmetic only). */
+int actq_header_bytes(int64_t N, int64_t D, int32_t G, actq_header_format hf, uint64_t* bytes_host);
 
 /*
  * Per-group zero point Z = min and range R = max - min (Sec. 4.1).
@@ -113,7 +124,8 @@ int actq_group_stats(const void* x, actq_dtype dt, int64_t N, int64_t D, int32_t
  * bits     device, in  : [N] widths b_n in {1,2,4,8}
  * offsets  device, in  : [N] byte offsets as produced by actq_packed_bytes
  * packed   device, out : the bit stream; `packed_capacity` bytes are writable
- * header   device, out : [N*ng][2] float, (Z, scale) of every group
+ * header   device, out : [N*ng] groups in format hf: {float Z, float scale} or
+ *                        {uint16 Z, uint16 R} (bfloat16 bit patterns), 8-byte aligned
  *
  * bits and offsets live on the device, so the host cannot check them: a sample
  * whose width is not in {1,2,4,8} or whose byte range would leave
@@ -122,24 +134,42 @@ int actq_group_stats(const void* x, actq_dtype dt, int64_t N, int64_t D, int32_t
 int actq_quantize_pack(const void* x, actq_dtype dt, int64_t N, int64_t D, int32_t G,
                        const uint8_t* bits, const uint64_t* offsets,
                        uint64_t seed, uint64_t tag, int32_t noise_bits,
-                       void* packed, uint64_t packed_capacity, float* header,
-                       void* stream);
+                       void* packed, uint64_t packed_capacity, void* header,
+                       actq_header_format hf, void* stream);
 
 /*
  * Backward pass: unpack and dequantize (Sec. 4.1): h^ = code * scale + Z,
  * evaluated as one fused multiply-add in binary32; binary16 output is the
  * round-to-nearest-even conversion of that value.
  *
+ * With the bfloat16 header the step is recomputed as scale = R / B (one
+ * binary32 division) before the multiply-add.
+ *
  * packed  device, in  : bit stream written by actq_quantize_pack
- * header  device, in  : [N*ng][2] float (Z, scale)
+ * header  device, in  : as written by actq_quantize_pack with the same hf
  * bits, offsets       : as for actq_quantize_pack; a sample that fails the same
  *                       checks against `packed_capacity` is skipped
  * out     device, out : N*D elements of dtype `out_dt`
  */
 int actq_unpack_dequantize(const void* packed, uint64_t packed_capacity,
-                           const float* header, const uint8_t* bits,
+                           const void* header, actq_header_format hf, const uint8_t* bits,
                            const uint64_t* offsets, int64_t N, int64_t D, int32_t G,
                            void* out, actq_dtype out_dt, void* stream);
+
+/*
+ * Per-sample sensitivity of a linear layer (Sec. 4.2, Eq. (8) and the sentence
+ * after Prob. (9)): w_n = (G / 6) * ||grad_n||^2 * sum_g R_ng^2, the input of
+ * actq_allocate_bits.  It reads only the group ranges written by
+ * actq_group_stats (1/256 of the tensor), one block per sample, binary32 sums in
+ * a fixed order.
+ *
+ * grange device, in  : [N*ng] float
+ * grad2  device, in  : [N] float, the squared gradient norms (or their running
+ *                      estimate, Sec. 4.3); NULL means 1
+ * w      device, out : [N] float
+ */
+int actq_sample_sensitivity(const float* grange, int64_t N, int64_t ng, int32_t G,
+                            const float* grad2, float* w, void* stream);
 
 /*
  * Greedy solution of the bit-allocation problem (Sec. 4.2, Prob. (9); greedy

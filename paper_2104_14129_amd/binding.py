@@ -19,8 +19,10 @@ ACTQ_OK, ACTQ_EINVAL, ACTQ_EINFEASIBLE, ACTQ_EHIP = 0, -1, -2, -3
 ACTQ_F32, ACTQ_F16 = 0, 1
 G_DEFAULT = 256
 
-EXPORTS = ("actq_version", "actq_last_error", "actq_packed_bytes", "actq_group_stats",
-           "actq_quantize_pack", "actq_unpack_dequantize", "actq_allocate_bits")
+ACTQ_HDR_F32, ACTQ_HDR_BF16 = 0, 1
+
+EXPORTS = ("actq_version", "actq_last_error", "actq_packed_bytes", "actq_header_bytes", "actq_group_stats",
+           "actq_quantize_pack", "actq_unpack_dequantize", "actq_sample_sensitivity", "actq_allocate_bits")
 
 
 class ActqError(RuntimeError):
@@ -52,9 +54,13 @@ def lib() -> ctypes.CDLL:
     L.actq_group_stats.restype = c.c_int
     L.actq_group_stats.argtypes = [vp, c.c_int, i64, i64, i32, vp, vp, vp]
     L.actq_quantize_pack.restype = c.c_int
-    L.actq_quantize_pack.argtypes = [vp, c.c_int, i64, i64, i32, vp, vp, u64, u64, i32, vp, u64, vp, vp]
+    L.actq_quantize_pack.argtypes = [vp, c.c_int, i64, i64, i32, vp, vp, u64, u64, i32, vp, u64, vp, c.c_int, vp]
     L.actq_unpack_dequantize.restype = c.c_int
-    L.actq_unpack_dequantize.argtypes = [vp, u64, vp, vp, vp, i64, i64, i32, vp, c.c_int, vp]
+    L.actq_unpack_dequantize.argtypes = [vp, u64, vp, c.c_int, vp, vp, i64, i64, i32, vp, c.c_int, vp]
+    L.actq_header_bytes.restype = c.c_int
+    L.actq_header_bytes.argtypes = [i64, i64, i32, c.c_int, vp]
+    L.actq_sample_sensitivity.restype = c.c_int
+    L.actq_sample_sensitivity.argtypes = [vp, i64, i64, i32, vp, vp, vp]
     L.actq_allocate_bits.restype = c.c_int
     L.actq_allocate_bits.argtypes = [vp, vp, i64, i64, vp]
     _lib = L
@@ -136,38 +142,68 @@ def group_stats(x, gmin=None, grange=None, G: int = G_DEFAULT, stream=None):
     return gmin, grange
 
 
+def header_bytes(N: int, D: int, hf: int = ACTQ_HDR_F32, G: int = G_DEFAULT) -> int:
+    out = ctypes.c_uint64(0)
+    _check(lib().actq_header_bytes(N, D, G, hf, ctypes.addressof(out)))
+    return int(out.value)
+
+
+def _header_ptr(header, N, ng, hf):
+    torch = _torch()
+    want = torch.float32 if hf == ACTQ_HDR_F32 else torch.int16
+    if header.dtype != want:
+        raise TypeError(f"header must be {want} for this header format, got {header.dtype}")
+    if header.numel() != N * ng * 2:
+        raise ValueError("header must hold N*ng*2 entries")
+    return _dev(header, want, "header")
+
+
 def quantize_pack(x, bits, offsets, packed, header, seed: int, tag: int = 0, noise_bits: int = 24,
-                  G: int = G_DEFAULT, stream=None):
-    """Device: writes the bit stream into `packed` (uint8) and (Z, scale) into `header`."""
+                  G: int = G_DEFAULT, stream=None, hf: int = ACTQ_HDR_F32):
+    """Device: writes the bit stream into `packed` (uint8) and the group headers into `header`
+    (float32 [N*ng*2] for ACTQ_HDR_F32, int16 [N*ng*2] bfloat16 bit patterns for ACTQ_HDR_BF16)."""
     torch = _torch()
     N, D = _view2d(x)
     ng = (D + G - 1) // G
     if bits.numel() != N or offsets.numel() != N:
         raise ValueError("bits and offsets must have N entries")
-    if header.numel() != N * ng * 2:
-        raise ValueError("header must hold N*ng*2 floats")
     _check(lib().actq_quantize_pack(_dev(x, name="x"), _dtype_code(x), N, D, G,
                                     _dev(bits, torch.uint8, "bits"), _dev(offsets, torch.int64, "offsets"),
                                     seed & (2 ** 64 - 1), tag & (2 ** 64 - 1), noise_bits,
                                     _dev(packed, torch.uint8, "packed"), packed.numel(),
-                                    _dev(header, torch.float32, "header"), _stream(stream)))
+                                    _header_ptr(header, N, ng, hf), hf, _stream(stream)))
     return packed, header
 
 
-def unpack_dequantize(packed, header, bits, offsets, out, G: int = G_DEFAULT, stream=None):
+def unpack_dequantize(packed, header, bits, offsets, out, G: int = G_DEFAULT, stream=None,
+                      hf: int = ACTQ_HDR_F32):
     """Device: reconstructs `out` ([N, ...] float32 or float16) from the bit stream."""
     torch = _torch()
     N, D = _view2d(out)
     ng = (D + G - 1) // G
     if bits.numel() != N or offsets.numel() != N:
         raise ValueError("bits and offsets must have N entries")
-    if header.numel() != N * ng * 2:
-        raise ValueError("header must hold N*ng*2 floats")
     _check(lib().actq_unpack_dequantize(_dev(packed, torch.uint8, "packed"), packed.numel(),
-                                        _dev(header, torch.float32, "header"),
+                                        _header_ptr(header, N, ng, hf), hf,
                                         _dev(bits, torch.uint8, "bits"), _dev(offsets, torch.int64, "offsets"),
                                         N, D, G, _dev(out, name="out"), _dtype_code(out), _stream(stream)))
     return out
+
+
+def sample_sensitivity(grange, grad2=None, w=None, G: int = G_DEFAULT, stream=None):
+    """Device: w[n] = (G/6) * grad2[n] * sum_g grange[n, g]^2 (grad2 = None means 1)."""
+    torch = _torch()
+    if grange.dim() != 2:
+        raise ValueError("grange must be [N, ng]")
+    N, ng = int(grange.shape[0]), int(grange.shape[1])
+    if w is None:
+        w = torch.empty(N, dtype=torch.float32, device=grange.device)
+    if w.numel() != N or (grad2 is not None and grad2.numel() != N):
+        raise ValueError("w and grad2 must have N entries")
+    g2 = None if grad2 is None else _dev(grad2, torch.float32, "grad2")
+    _check(lib().actq_sample_sensitivity(_dev(grange, torch.float32, "grange"), N, ng, G, g2,
+                                         _dev(w, torch.float32, "w"), _stream(stream)))
+    return w
 
 
 def allocate_bits(w_host, D_host, budget_bits: int) -> np.ndarray:

@@ -41,6 +41,12 @@ static int check_view(const char* who, int64_t N, int64_t D, int32_t G)
     return ACTQ_OK;
 }
 
+static int check_header(const char* who, int hf)
+{
+    if (hf != ACTQ_HDR_F32 && hf != ACTQ_HDR_BF16) return fail(ACTQ_EINVAL, "%s: unknown header format %d", who, hf);
+    return ACTQ_OK;
+}
+
 static int check_dtype(const char* who, int dt)
 {
     if (dt != ACTQ_F32 && dt != ACTQ_F16) return fail(ACTQ_EINVAL, "%s: unknown dtype %d", who, dt);
@@ -53,7 +59,17 @@ using namespace actq;
 
 extern "C" {
 
-int actq_version(void) { return 100; }
+int actq_version(void) { return 200; }
+
+int actq_header_bytes(int64_t N, int64_t D, int32_t G, actq_header_format hf, uint64_t* bytes_host)
+{
+    if (int rc = check_view("actq_header_bytes", N, D, G)) return rc;
+    if (int rc = check_header("actq_header_bytes", hf)) return rc;
+    if (!bytes_host) return fail(ACTQ_EINVAL, "actq_header_bytes: null output");
+    const uint64_t ng = static_cast<uint64_t>((D + G - 1) / G);
+    *bytes_host = static_cast<uint64_t>(N) * ng * (hf == ACTQ_HDR_BF16 ? 4u : 8u);
+    return ACTQ_OK;
+}
 
 const char* actq_last_error(void) { return g_error; }
 
@@ -91,9 +107,10 @@ int actq_group_stats(const void* x, actq_dtype dt, int64_t N, int64_t D, int32_t
 int actq_quantize_pack(const void* x, actq_dtype dt, int64_t N, int64_t D, int32_t G,
                        const uint8_t* bits, const uint64_t* offsets, uint64_t seed,
                        uint64_t tag, int32_t noise_bits, void* packed,
-                       uint64_t packed_capacity, float* header, void* stream)
+                       uint64_t packed_capacity, void* header, actq_header_format hf, void* stream)
 {
     if (int rc = check_view("actq_quantize_pack", N, D, G)) return rc;
+    if (int rc = check_header("actq_quantize_pack", hf)) return rc;
     if (int rc = check_dtype("actq_quantize_pack", dt)) return rc;
     if (!x || !bits || !offsets || !packed || !header) return fail(ACTQ_EINVAL, "actq_quantize_pack: null pointer");
     if (noise_bits != 24 && noise_bits != 16) return fail(ACTQ_EINVAL, "actq_quantize_pack: noise_bits must be 24 or 16, got %d", noise_bits);
@@ -106,14 +123,15 @@ int actq_quantize_pack(const void* x, actq_dtype dt, int64_t N, int64_t D, int32
     if (packed_capacity < static_cast<uint64_t>(N) * ng * (G / 8))
         return fail(ACTQ_EINVAL, "actq_quantize_pack: packed_capacity %llu is below one bit per element", (unsigned long long)packed_capacity);
     return launch_quantize_pack(x, dt, N, D, bits, offsets, seed, tag, noise_bits, packed,
-                                packed_capacity, header, stream);
+                                packed_capacity, header, hf, stream);
 }
 
-int actq_unpack_dequantize(const void* packed, uint64_t packed_capacity, const float* header,
-                           const uint8_t* bits, const uint64_t* offsets, int64_t N, int64_t D,
-                           int32_t G, void* out, actq_dtype out_dt, void* stream)
+int actq_unpack_dequantize(const void* packed, uint64_t packed_capacity, const void* header,
+                           actq_header_format hf, const uint8_t* bits, const uint64_t* offsets,
+                           int64_t N, int64_t D, int32_t G, void* out, actq_dtype out_dt, void* stream)
 {
     if (int rc = check_view("actq_unpack_dequantize", N, D, G)) return rc;
+    if (int rc = check_header("actq_unpack_dequantize", hf)) return rc;
     if (int rc = check_dtype("actq_unpack_dequantize", out_dt)) return rc;
     if (!packed || !header || !bits || !offsets || !out) return fail(ACTQ_EINVAL, "actq_unpack_dequantize: null pointer");
     if (!aligned(out, 16)) return fail(ACTQ_EINVAL, "actq_unpack_dequantize: out must be 16-byte aligned");
@@ -121,8 +139,20 @@ int actq_unpack_dequantize(const void* packed, uint64_t packed_capacity, const f
     if (!aligned(header, 8)) return fail(ACTQ_EINVAL, "actq_unpack_dequantize: header must be 8-byte aligned");
     if (!aligned(offsets, 8)) return fail(ACTQ_EINVAL, "actq_unpack_dequantize: offsets must be 8-byte aligned");
     if (!aligned(bits, 4)) return fail(ACTQ_EINVAL, "actq_unpack_dequantize: bits must be 4-byte aligned");
-    return launch_unpack_dequantize(packed, packed_capacity, header, bits, offsets, N, D, out,
+    return launch_unpack_dequantize(packed, packed_capacity, header, hf, bits, offsets, N, D, out,
                                     out_dt, stream);
+}
+
+int actq_sample_sensitivity(const float* grange, int64_t N, int64_t ng, int32_t G,
+                            const float* grad2, float* w, void* stream)
+{
+    if (!grange || !w) return fail(ACTQ_EINVAL, "actq_sample_sensitivity: null pointer");
+    if (N <= 0 || ng <= 0 || N >= (int64_t(1) << 32) || ng >= (int64_t(1) << 32))
+        return fail(ACTQ_EINVAL, "actq_sample_sensitivity: N and ng must be positive and below 2^32");
+    if (G <= 0) return fail(ACTQ_EINVAL, "actq_sample_sensitivity: G must be positive");
+    if (!aligned(grange, 4) || !aligned(w, 4) || !aligned(grad2, 4))
+        return fail(ACTQ_EINVAL, "actq_sample_sensitivity: arrays must be 4-byte aligned");
+    return launch_sample_sensitivity(grange, N, ng, G, grad2, w, stream);
 }
 
 // Greedy allocator of Sec. 4.3 on the ladder 8 -> 4 -> 2 -> 1.  The heap holds, for

@@ -19,10 +19,12 @@ int launch_group_stats(const void* x, int dtype, int64_t N, int64_t D, float* gm
                        float* grange, void* stream);
 int launch_quantize_pack(const void* x, int dtype, int64_t N, int64_t D, const uint8_t* bits,
                          const uint64_t* offsets, uint64_t seed, uint64_t tag, int noise_bits,
-                         void* packed, uint64_t capacity, float* header, void* stream);
-int launch_unpack_dequantize(const void* packed, uint64_t capacity, const float* header,
+                         void* packed, uint64_t capacity, void* header, int hdr, void* stream);
+int launch_unpack_dequantize(const void* packed, uint64_t capacity, const void* header, int hdr,
                              const uint8_t* bits, const uint64_t* offsets, int64_t N,
                              int64_t D, void* out, int out_dtype, void* stream);
+int launch_sample_sensitivity(const float* grange, int64_t N, int64_t ng, int32_t G,
+                              const float* grad2, float* w, void* stream);
 
 }  // namespace actq
 

@@ -190,6 +190,7 @@ struct Geometry {
     uint32_t tiles_per_sample;  // ceil(ng / 4)
     uint32_t tiles_per_wave;    // consecutive tiles handled by one wavefront
     uint32_t grid_y;            // samples per grid.z slice
+    uint32_t hdr_bf16;          // header format: 0 = (Z, R/B) binary32, 1 = (Z, R) bfloat16
 };
 
 // First tile (inside its sample) and sample of this wavefront; false if it has no work.
@@ -260,6 +261,35 @@ __device__ __forceinline__ uint32_t load_width(const uint8_t* __restrict__ bits,
 {
     const uint32_t word = reinterpret_cast<const uint32_t*>(bits)[n >> 2];
     return (word >> ((n & 3u) * 8u)) & 0xffu;
+}
+
+// bfloat16 header (Sec. 4.1, last paragraph): the zero point is rounded down and the range,
+// taken from the rounded zero point, is rounded up, so every element still scales into [0, B].
+// Both return the 16 bits of the bfloat16 value.
+__device__ __forceinline__ uint32_t bf16_floor_bits(float f)
+{
+    const uint32_t u = __float_as_uint(f);
+    return (u >> 16) + (((u & 0xffffu) != 0 && (u >> 31) != 0) ? 1u : 0u);
+}
+
+__device__ __forceinline__ uint32_t bf16_ceil_bits(float f)
+{
+    const uint32_t u = __float_as_uint(f);
+    return (u >> 16) + (((u & 0xffffu) != 0 && (u >> 31) == 0) ? 1u : 0u);
+}
+
+// (Z, scale = R / B) of group `index` from either header format.
+template <bool BF16>
+__device__ __forceinline__ f32x2 load_header(const void* __restrict__ header, int64_t index, float kB)
+{
+    if (BF16) {
+        const uint32_t w = static_cast<const uint32_t*>(header)[index];
+        f32x2 h;
+        h.x = __uint_as_float(w << 16);
+        h.y = __uint_as_float(w & 0xffff0000u) / kB;  // IEEE division, as the step R / B is defined
+        return h;
+    }
+    return static_cast<const f32x2*>(header)[index];
 }
 
 // ------------------------------------------------------------------------------------
@@ -356,24 +386,40 @@ __device__ __forceinline__ void encode_tile(const TileRegs& td, const uint32_t (
                                             float row_min, float row_max, uint32_t n, uint32_t g0,
                                             int groups, uint32_t ng, int lane,
                                             uint8_t* __restrict__ dst_sample,
-                                            float* __restrict__ header, uint32_t* stage)
+                                            void* __restrict__ header, bool hdr_bf16, uint32_t* stage)
 {
     constexpr float kB = static_cast<float>((1 << B) - 1);
     constexpr float kNoiseGrid = 16777216.0f;  // 24-bit noise is compared as an integer with frac * 2^24
-    const float mn = row_min;
-    const float range = row_max - mn;
+    float mn = row_min;
+    float range;
+    uint32_t zb = 0, rb = 0;
+    if (hdr_bf16) {
+        zb = bf16_floor_bits(mn);
+        mn = __uint_as_float(zb << 16);
+        rb = bf16_ceil_bits(row_max - mn);
+        range = __uint_as_float(rb << 16);
+        if (!__builtin_isfinite(range)) range = 0.0f;  // rounding up overflowed: degenerate
+    } else {
+        range = row_max - mn;
+    }
     float inv = kB / range;
     float scale = range / kB;
     if (!(range != 0.0f) || !__builtin_isfinite(inv)) {  // constant group, or B / R overflows
         inv = 0.0f;
         scale = 0.0f;
+        rb = 0;
     }
     const int row = lane >> 4;
     if ((lane & 15) == 0 && row < groups) {
-        f32x2 h;
-        h.x = mn;
-        h.y = scale;
-        __builtin_nontemporal_store(h, reinterpret_cast<f32x2*>(header + 2 * (static_cast<int64_t>(n) * ng + g0 + row)));
+        const int64_t gi = static_cast<int64_t>(n) * ng + g0 + row;
+        if (hdr_bf16) {
+            __builtin_nontemporal_store(zb | (rb << 16), static_cast<uint32_t*>(header) + gi);
+        } else {
+            f32x2 h;
+            h.x = mn;
+            h.y = scale;
+            __builtin_nontemporal_store(h, static_cast<f32x2*>(header) + gi);
+        }
     }
 
     uint32_t piece[kTileGroups];
@@ -453,6 +499,7 @@ struct StreamGeometry {
     uint32_t tiles_per_sample;
     uint32_t total_tiles;
     uint32_t step_n, step_t;  // waves = step_n * tiles_per_sample + step_t
+    uint32_t hdr_bf16;        // header format: 0 = (Z, R/B) binary32, 1 = (Z, R) bfloat16
 };
 
 // Position of a wavefront in its sequence of tiles, with the scalar facts of the sample.
@@ -488,7 +535,7 @@ template <int NOISE_BITS, bool VEC>
 __device__ __forceinline__ void quantize_one(const TileRegs& r, const Cursor& c, const StreamGeometry& geo,
                                              int lane, uint32_t k0, uint32_t k1, uint32_t tag0, uint32_t tag1,
                                              uint8_t* __restrict__ packed, uint64_t capacity,
-                                             float* __restrict__ header, uint32_t* stage)
+                                             void* __restrict__ header, uint32_t* stage)
 {
     const uint32_t g0 = c.t * kTileGroups;
     const int groups = static_cast<int>(min(static_cast<uint32_t>(kTileGroups), geo.ng - g0));
@@ -512,10 +559,10 @@ __device__ __forceinline__ void quantize_one(const TileRegs& r, const Cursor& c,
     if ((off & 31u) != 0 || off > capacity || bytes > capacity - off) return;
     uint8_t* dst = packed + off;
     switch (b) {
-        case 1: encode_tile<NOISE_BITS, VEC, 1>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, stage); break;
-        case 2: encode_tile<NOISE_BITS, VEC, 2>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, stage); break;
-        case 4: encode_tile<NOISE_BITS, VEC, 4>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, stage); break;
-        case 8: encode_tile<NOISE_BITS, VEC, 8>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, stage); break;
+        case 1: encode_tile<NOISE_BITS, VEC, 1>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, geo.hdr_bf16 != 0, stage); break;
+        case 2: encode_tile<NOISE_BITS, VEC, 2>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, geo.hdr_bf16 != 0, stage); break;
+        case 4: encode_tile<NOISE_BITS, VEC, 4>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, geo.hdr_bf16 != 0, stage); break;
+        case 8: encode_tile<NOISE_BITS, VEC, 8>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, geo.hdr_bf16 != 0, stage); break;
         default: break;
     }
 }
@@ -530,7 +577,7 @@ template <typename T, int NOISE_BITS, bool VEC>
 __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(
     const T* __restrict__ x, StreamGeometry geo, const uint8_t* __restrict__ bits,
     const uint64_t* __restrict__ offsets, uint32_t k0, uint32_t k1, uint32_t tag0, uint32_t tag1,
-    uint8_t* __restrict__ packed, uint64_t capacity, float* __restrict__ header)
+    uint8_t* __restrict__ packed, uint64_t capacity, void* __restrict__ header)
 {
     __shared__ uint32_t stage_all[kWavesPerBlock][256];  // 1 KiB per wavefront, private to it
     const int lane = threadIdx.x & (kWave - 1);
@@ -566,7 +613,7 @@ template <typename T, int NOISE_BITS, bool VEC>
 __global__ __launch_bounds__(kBlock) void quantize_pack_tile_kernel(
     const T* __restrict__ x, StreamGeometry geo, uint32_t grid_y, const uint8_t* __restrict__ bits,
     const uint64_t* __restrict__ offsets, uint32_t k0, uint32_t k1, uint32_t tag0, uint32_t tag1,
-    uint8_t* __restrict__ packed, uint64_t capacity, float* __restrict__ header)
+    uint8_t* __restrict__ packed, uint64_t capacity, void* __restrict__ header)
 {
     __shared__ uint32_t stage_all[kWavesPerBlock][256];
     const int lane = threadIdx.x & (kWave - 1);
@@ -583,10 +630,10 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_tile_kernel(
 // ------------------------------------------------------------------------------------
 // Sec. 4.1: h^ = code * scale + Z.
 
-template <typename T, bool VEC, int B>
+template <typename T, bool VEC, int B, bool BF16>
 __device__ __forceinline__ void dequantize_tile(const uint8_t* __restrict__ src_sample,
-                                                const float* __restrict__ header, T* os, int64_t D,
-                                                uint32_t n, uint32_t g0, int groups, uint32_t ng,
+                                                const void* __restrict__ header, T* os,
+                                                int64_t D, uint32_t n, uint32_t g0, int groups, uint32_t ng,
                                                 int lane)
 {
     constexpr int lanes_per_word = 8 / B;  // a lane's four codes are 4*B bits of a 32-bit word
@@ -599,7 +646,7 @@ __device__ __forceinline__ void dequantize_tile(const uint8_t* __restrict__ src_
         const uint32_t g = g0 + u;
         const uint32_t* src = reinterpret_cast<const uint32_t*>(src_sample + static_cast<uint64_t>(g) * (32 * B));
         word[u] = __builtin_nontemporal_load(src + lane / lanes_per_word);
-        hd[u] = *reinterpret_cast<const f32x2*>(header + 2 * (static_cast<int64_t>(n) * ng + g));
+        hd[u] = load_header<BF16>(header, static_cast<int64_t>(n) * ng + g, static_cast<float>(code_mask));
     }
 #pragma unroll
     for (int u = 0; u < kTileGroups; ++u) {
@@ -627,11 +674,11 @@ __device__ __forceinline__ void dequantize_tile(const uint8_t* __restrict__ src_
 // takes eight consecutive elements (16 bytes) and the wavefront covers two groups per step
 // (lanes 0..31 the even group, lanes 32..63 the odd one).  Unpacking is free to choose its
 // lane-to-element map: nothing is reduced across lanes.
-template <bool VEC, int B>
+template <bool VEC, int B, bool BF16>
 __device__ __forceinline__ void dequantize_tile_f16(const uint8_t* __restrict__ src_sample,
-                                                    const float* __restrict__ header, _Float16* os,
-                                                    int64_t D, uint32_t n, uint32_t g0, int groups,
-                                                    uint32_t ng, int lane)
+                                                    const void* __restrict__ header,
+                                                    _Float16* os, int64_t D, uint32_t n, uint32_t g0,
+                                                    int groups, uint32_t ng, int lane)
 {
     typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
     constexpr uint32_t code_mask = (1u << B) - 1u;
@@ -654,7 +701,7 @@ __device__ __forceinline__ void dequantize_tile_f16(const uint8_t* __restrict__ 
             code_lo[p] = w.x;
             code_hi[p] = w.y;
         }
-        hd[p] = *reinterpret_cast<const f32x2*>(header + 2 * (static_cast<int64_t>(n) * ng + g));
+        hd[p] = load_header<BF16>(header, static_cast<int64_t>(n) * ng + g, static_cast<float>(code_mask));
     }
 #pragma unroll
     for (int p = 0; p < 2; ++p) {
@@ -678,20 +725,20 @@ __device__ __forceinline__ void dequantize_tile_f16(const uint8_t* __restrict__ 
     }
 }
 
-template <typename T, bool VEC, int B>
+template <typename T, bool VEC, int B, bool BF16>
 __device__ __forceinline__ void dequantize_any(const uint8_t* __restrict__ src_sample,
-                                               const float* __restrict__ header, T* os, int64_t D,
-                                               uint32_t n, uint32_t g0, int groups, uint32_t ng, int lane)
+                                               const void* __restrict__ header, T* os,
+                                               int64_t D, uint32_t n, uint32_t g0, int groups, uint32_t ng, int lane)
 {
     if constexpr (sizeof(T) == 2)
-        dequantize_tile_f16<VEC, B>(src_sample, header, os, D, n, g0, groups, ng, lane);
+        dequantize_tile_f16<VEC, B, BF16>(src_sample, header, os, D, n, g0, groups, ng, lane);
     else
-        dequantize_tile<T, VEC, B>(src_sample, header, os, D, n, g0, groups, ng, lane);
+        dequantize_tile<T, VEC, B, BF16>(src_sample, header, os, D, n, g0, groups, ng, lane);
 }
 
-template <typename T, bool VEC>
+template <typename T, bool VEC, bool BF16>
 __global__ __launch_bounds__(kBlock) void unpack_dequantize_kernel(
-    const uint8_t* __restrict__ packed, uint64_t capacity, const float* __restrict__ header,
+    const uint8_t* __restrict__ packed, uint64_t capacity, const void* __restrict__ header,
     const uint8_t* __restrict__ bits, const uint64_t* __restrict__ offsets, Geometry geo,
     T* __restrict__ out)
 {
@@ -708,12 +755,41 @@ __global__ __launch_bounds__(kBlock) void unpack_dequantize_kernel(
         const uint32_t g0 = tile * kTileGroups;
         const int groups = static_cast<int>(min(static_cast<uint32_t>(kTileGroups), geo.ng - g0));
         switch (b) {
-            case 1: dequantize_any<T, VEC, 1>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
-            case 2: dequantize_any<T, VEC, 2>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
-            case 4: dequantize_any<T, VEC, 4>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
-            case 8: dequantize_any<T, VEC, 8>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
+            case 1: dequantize_any<T, VEC, 1, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
+            case 2: dequantize_any<T, VEC, 2, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
+            case 4: dequantize_any<T, VEC, 4, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
+            case 8: dequantize_any<T, VEC, 8, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
             default: return;
         }
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// Sec. 4.2, Eq. (8): w_n = (G / 6) * ||grad_n||^2 * sum_g R_ng^2.  One block per sample over the
+// group ranges (1/256 of the tensor's size); fixed summation order, so results are reproducible.
+__global__ __launch_bounds__(kBlock) void sample_sensitivity_kernel(const float* __restrict__ grange,
+                                                                    uint32_t N, uint32_t ng, uint32_t grid_x,
+                                                                    float coeff, const float* __restrict__ grad2,
+                                                                    float* __restrict__ w)
+{
+    __shared__ float partial[kWavesPerBlock];
+    const uint32_t n = blockIdx.y * grid_x + blockIdx.x;
+    if (n >= N) return;
+    const float* r = grange + static_cast<int64_t>(n) * ng;
+    float acc = 0.0f;
+    for (uint32_t g = threadIdx.x; g < ng; g += kBlock) acc = __builtin_fmaf(r[g], r[g], acc);
+    // lanes, then wavefronts, in a fixed order
+    acc += dpp_f32<kDppXor1>(acc);
+    acc += dpp_f32<kDppXor2>(acc);
+    acc += dpp_f32<kDppHalfMirror>(acc);
+    acc += dpp_f32<kDppXor8>(acc);
+    acc += __shfl_xor(acc, 16);
+    acc += __shfl_xor(acc, 32);
+    if ((threadIdx.x & (kWave - 1)) == 0) partial[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const float total = (partial[0] + partial[1]) + (partial[2] + partial[3]);
+        w[n] = coeff * total * (grad2 ? grad2[n] : 1.0f);
     }
 }
 
@@ -729,6 +805,7 @@ int make_geometry(const char* who, int64_t N, int64_t D, uint32_t tiles_per_wave
     geo->ng = static_cast<uint32_t>(ng);
     geo->tiles_per_sample = static_cast<uint32_t>(tps);
     geo->tiles_per_wave = tiles_per_wave;
+    geo->hdr_bf16 = 0;
     const int64_t waves = (tps + tiles_per_wave - 1) / tiles_per_wave;
     const int64_t gx = (waves + kWavesPerBlock - 1) / kWavesPerBlock;
     const int64_t gy = N < 65535 ? N : 65535;
@@ -799,7 +876,7 @@ constexpr bool persistent_shape(int noise_bits) { return noise_bits == 24; }
 template <typename T, int NOISE_BITS, bool VEC>
 static int launch_quantize_variant(const T* x, StreamGeometry geo, hipStream_t s, const uint8_t* bits,
                                    const uint64_t* offsets, uint64_t seed, uint64_t tag, uint8_t* packed,
-                                   uint64_t capacity, float* header)
+                                   uint64_t capacity, void* header)
 {
     const uint32_t k0 = static_cast<uint32_t>(seed), k1 = static_cast<uint32_t>(seed >> 32);
     const uint32_t t0 = static_cast<uint32_t>(tag), t1 = static_cast<uint32_t>(tag >> 32);
@@ -833,7 +910,7 @@ template <typename T>
 static int launch_quantize_typed(const T* x, const StreamGeometry& geo, hipStream_t s, bool vec,
                                  int noise_bits, const uint8_t* bits, const uint64_t* offsets,
                                  uint64_t seed, uint64_t tag, uint8_t* packed, uint64_t capacity,
-                                 float* header)
+                                 void* header)
 {
     if (noise_bits == 24) {
         if (vec) return launch_quantize_variant<T, 24, true>(x, geo, s, bits, offsets, seed, tag, packed, capacity, header);
@@ -845,7 +922,7 @@ static int launch_quantize_typed(const T* x, const StreamGeometry& geo, hipStrea
 
 int launch_quantize_pack(const void* x, int dtype, int64_t N, int64_t D, const uint8_t* bits,
                          const uint64_t* offsets, uint64_t seed, uint64_t tag, int noise_bits,
-                         void* packed, uint64_t capacity, float* header, void* stream)
+                         void* packed, uint64_t capacity, void* header, int hdr, void* stream)
 {
     const int64_t ng = (D + kGroup - 1) / kGroup;
     const int64_t tps = (ng + kTileGroups - 1) / kTileGroups;
@@ -858,6 +935,7 @@ int launch_quantize_pack(const void* x, int dtype, int64_t N, int64_t D, const u
     geo.tiles_per_sample = static_cast<uint32_t>(tps);
     geo.total_tiles = static_cast<uint32_t>(N * tps);
     geo.step_n = geo.step_t = 0;
+    geo.hdr_bf16 = hdr == ACTQ_HDR_BF16 ? 1u : 0u;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool vec = vector_ok(D);
     int rc;
@@ -869,26 +947,39 @@ int launch_quantize_pack(const void* x, int dtype, int64_t N, int64_t D, const u
     return check_launch("actq_quantize_pack");
 }
 
-int launch_unpack_dequantize(const void* packed, uint64_t capacity, const float* header,
+int launch_unpack_dequantize(const void* packed, uint64_t capacity, const void* header, int hdr,
                              const uint8_t* bits, const uint64_t* offsets, int64_t N, int64_t D,
                              void* out, int out_dtype, void* stream)
 {
     Geometry geo;
     dim3 grid;
     if (int rc = make_geometry("actq_unpack_dequantize", N, D, kTilesPerWaveWrite, &geo, &grid)) return rc;
+    geo.hdr_bf16 = hdr == ACTQ_HDR_BF16 ? 1u : 0u;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool vec = vector_ok(D);
     auto* pk = static_cast<const uint8_t*>(packed);
+    const bool bf = hdr == ACTQ_HDR_BF16;
+#define ACTQ_DEQ(T, V, H) unpack_dequantize_kernel<T, V, H><<<grid, kBlock, 0, s>>>(pk, capacity, header, bits, offsets, geo, static_cast<T*>(out))
     if (out_dtype == ACTQ_F32) {
-        auto* o = static_cast<float*>(out);
-        if (vec) unpack_dequantize_kernel<float, true><<<grid, kBlock, 0, s>>>(pk, capacity, header, bits, offsets, geo, o);
-        else unpack_dequantize_kernel<float, false><<<grid, kBlock, 0, s>>>(pk, capacity, header, bits, offsets, geo, o);
+        if (vec) { if (bf) ACTQ_DEQ(float, true, true); else ACTQ_DEQ(float, true, false); }
+        else { if (bf) ACTQ_DEQ(float, false, true); else ACTQ_DEQ(float, false, false); }
     } else {
-        auto* o = static_cast<_Float16*>(out);
-        if (vec) unpack_dequantize_kernel<_Float16, true><<<grid, kBlock, 0, s>>>(pk, capacity, header, bits, offsets, geo, o);
-        else unpack_dequantize_kernel<_Float16, false><<<grid, kBlock, 0, s>>>(pk, capacity, header, bits, offsets, geo, o);
+        if (vec) { if (bf) ACTQ_DEQ(_Float16, true, true); else ACTQ_DEQ(_Float16, true, false); }
+        else { if (bf) ACTQ_DEQ(_Float16, false, true); else ACTQ_DEQ(_Float16, false, false); }
     }
+#undef ACTQ_DEQ
     return check_launch("actq_unpack_dequantize");
+}
+
+int launch_sample_sensitivity(const float* grange, int64_t N, int64_t ng, int32_t G, const float* grad2,
+                              float* w, void* stream)
+{
+    const uint32_t gx = N < 65535 ? static_cast<uint32_t>(N) : 65535u;
+    const uint32_t gy = static_cast<uint32_t>((N + gx - 1) / gx);
+    if (gy > 65535u) return fail(ACTQ_EINVAL, "actq_sample_sensitivity: too many samples for one launch");
+    sample_sensitivity_kernel<<<dim3(gx, gy), kBlock, 0, static_cast<hipStream_t>(stream)>>>(
+        grange, static_cast<uint32_t>(N), static_cast<uint32_t>(ng), gx, static_cast<float>(G) / 6.0f, grad2, w);
+    return check_launch("actq_sample_sensitivity");
 }
 
 }  // namespace actq

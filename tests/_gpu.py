@@ -12,7 +12,8 @@ CANARY = 0xA5
 class GpuRun:
     """Buffers of one quantize -> dequantize round trip, with canary bytes after each output."""
 
-    def __init__(self, x_np: np.ndarray, bits_np: np.ndarray, G: int = 256, pad: int = 256):
+    def __init__(self, x_np: np.ndarray, bits_np: np.ndarray, G: int = 256, pad: int = 256, hf: int = 0):
+        self.hf = hf
         self.N = int(x_np.shape[0])
         self.D = int(x_np.size // self.N)
         self.G = G
@@ -26,7 +27,10 @@ class GpuRun:
         self.offsets = torch.from_numpy(self.offsets_np.view(np.int64)).to(dev)
         self.packed_buf = torch.full((self.total + pad,), CANARY, dtype=torch.uint8, device=dev)
         self.packed = self.packed_buf[: self.total]
-        self.header_buf = torch.full((self.N * self.ng * 2 + pad,), float("nan"), dtype=torch.float32, device=dev)
+        if hf == B.ACTQ_HDR_F32:
+            self.header_buf = torch.full((self.N * self.ng * 2 + pad,), float("nan"), dtype=torch.float32, device=dev)
+        else:
+            self.header_buf = torch.full((self.N * self.ng * 2 + pad,), 0x7A5A, dtype=torch.int16, device=dev)
         self.header = self.header_buf[: self.N * self.ng * 2]
 
     def stats(self):
@@ -39,17 +43,20 @@ class GpuRun:
         return buf_a[:n].cpu().numpy().reshape(self.N, self.ng), buf_b[:n].cpu().numpy().reshape(self.N, self.ng)
 
     def quantize(self, seed: int, tag: int = 0, noise_bits: int = 24):
-        B.quantize_pack(self.x, self.bits, self.offsets, self.packed, self.header, seed, tag, noise_bits, self.G)
+        B.quantize_pack(self.x, self.bits, self.offsets, self.packed, self.header, seed, tag, noise_bits, self.G, hf=self.hf)
         torch.cuda.synchronize()
         assert (self.packed_buf[self.total:] == CANARY).all(), "quantize_pack wrote past the bit stream"
-        assert torch.isnan(self.header_buf[self.N * self.ng * 2:]).all(), "quantize_pack wrote past the header"
-        return (self.packed.cpu().numpy(), self.header.cpu().numpy().reshape(self.N, self.ng, 2))
+        tail = self.header_buf[self.N * self.ng * 2:]
+        intact = torch.isnan(tail).all() if self.hf == B.ACTQ_HDR_F32 else (tail == 0x7A5A).all()
+        assert intact, "quantize_pack wrote past the header"
+        hd = self.header.cpu().numpy().reshape(self.N, self.ng, 2)
+        return (self.packed.cpu().numpy(), hd if self.hf == B.ACTQ_HDR_F32 else hd.view(np.uint16))
 
     def dequantize(self, out_dtype=torch.float32):
         n = self.N * self.D
         buf = torch.full((n + self.pad,), float("nan"), dtype=out_dtype, device=self.x.device)
         out = buf[:n].view(self.N, self.D)
-        B.unpack_dequantize(self.packed, self.header, self.bits, self.offsets, out, self.G)
+        B.unpack_dequantize(self.packed, self.header, self.bits, self.offsets, out, self.G, hf=self.hf)
         torch.cuda.synchronize()
         assert torch.isnan(buf[n:]).all(), "unpack_dequantize wrote past its output"
         return out.cpu().numpy()

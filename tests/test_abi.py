@@ -21,7 +21,7 @@ def test_every_declared_symbol_is_exported():
     L = B.lib()
     for name in declared:
         assert hasattr(L, name), name
-    assert B.version() >= 100
+    assert B.version() >= 200
 
 
 def test_packed_bytes_and_its_errors():
@@ -50,22 +50,35 @@ def test_device_calls_validate_before_launching():
     assert L.actq_group_stats(FAKE, 7, 1, 256, 256, FAKE, FAKE, None) == E
     assert L.actq_group_stats(FAKE + 4, 0, 1, 256, 256, FAKE, FAKE, None) == E
     assert "aligned" in B.last_error()
-    # quantize_pack: order is x, dt, N, D, G, bits, offsets, seed, tag, noise_bits, packed, capacity, header, stream
-    ok = [FAKE, 0, 2, 512, 256, FAKE, FAKE, 1, 0, 24, FAKE, 1 << 20, FAKE, None]
+    # quantize_pack: x, dt, N, D, G, bits, offsets, seed, tag, noise_bits, packed, capacity, header, hf, stream
+    ok = [FAKE, 0, 2, 512, 256, FAKE, FAKE, 1, 0, 24, FAKE, 1 << 20, FAKE, 0, None]
+    assert L.actq_quantize_pack(*(ok[:2] + [2, 512, 128] + ok[5:])) == E      # sanity: list is well-formed
     for idx, bad in [(0, None), (5, None), (6, None), (10, None), (12, None), (2, -1), (3, 0), (4, 512),
                      (1, 3), (9, 12), (0, FAKE + 2), (10, FAKE + 8), (12, FAKE + 4), (11, 10), (2, 1 << 32),
-                     (3, 1 << 34)]:
+                     (3, 1 << 34), (13, 2), (5, FAKE + 1)]:
         args = list(ok)
         args[idx] = bad
         assert L.actq_quantize_pack(*args) == E, (idx, bad)
         assert B.last_error()
-    # unpack_dequantize: packed, capacity, header, bits, offsets, N, D, G, out, out_dt, stream
-    ok = [FAKE, 1 << 20, FAKE, FAKE, FAKE, 2, 512, 256, FAKE, 0, None]
-    for idx, bad in [(0, None), (2, None), (3, None), (4, None), (8, None), (5, 0), (6, -5), (7, 8), (9, 2),
-                     (8, FAKE + 4), (0, FAKE + 1)]:
+    # unpack_dequantize: packed, capacity, header, hf, bits, offsets, N, D, G, out, out_dt, stream
+    ok = [FAKE, 1 << 20, FAKE, 1, FAKE, FAKE, 2, 512, 256, FAKE, 0, None]
+    for idx, bad in [(0, None), (2, None), (4, None), (5, None), (9, None), (6, 0), (7, -5), (8, 8), (10, 2),
+                     (9, FAKE + 4), (0, FAKE + 1), (3, 7), (4, FAKE + 2)]:
         args = list(ok)
         args[idx] = bad
         assert L.actq_unpack_dequantize(*args) == E, (idx, bad)
+    # sample_sensitivity: grange, N, ng, G, grad2, w, stream
+    ok = [FAKE, 4, 16, 256, None, FAKE, None]
+    for idx, bad in [(0, None), (5, None), (1, 0), (2, 0), (3, 0), (0, FAKE + 2), (4, FAKE + 1)]:
+        args = list(ok)
+        args[idx] = bad
+        assert L.actq_sample_sensitivity(*args) == E, (idx, bad)
+    # header_bytes
+    out = ctypes.c_uint64()
+    assert L.actq_header_bytes(3, 1000, 256, 0, ctypes.addressof(out)) == 0 and out.value == 3 * 4 * 8
+    assert L.actq_header_bytes(3, 1000, 256, 1, ctypes.addressof(out)) == 0 and out.value == 3 * 4 * 4
+    assert L.actq_header_bytes(3, 1000, 256, 5, ctypes.addressof(out)) == E
+    assert L.actq_header_bytes(3, 1000, 256, 0, None) == E
 
 
 def test_allocate_bits_errors():
