@@ -82,6 +82,8 @@ def lib() -> ctypes.CDLL:
         L.orc_unpack_dequantize.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp, c.c_int]
         L.orc_allocate_bits.restype = c.c_int
         L.orc_allocate_bits.argtypes = [vp, vp, i64, i64, vp]
+        L.orc_allocate_bits_ladder.restype = c.c_int
+        L.orc_allocate_bits_ladder.argtypes = [vp, vp, i64, i64, c.c_uint32, vp]
         L.orc_objective.restype = c.c_double
         L.orc_objective.argtypes = [vp, vp, i64]
         _lib = L
@@ -295,11 +297,16 @@ def unpack_dequantize(packed: np.ndarray, header: np.ndarray, bits, offsets,
     return out
 
 
-def allocate_bits(w, D, budget_bits: int) -> np.ndarray:
+WIDTHS_POW2 = 0x116  # {1, 2, 4, 8}
+WIDTHS_ALL = 0x1FE   # {1, ..., 8}
+
+
+def allocate_bits(w, D, budget_bits: int, widths: int = WIDTHS_POW2) -> np.ndarray:
+    """Greedy allocation over the widths whose bit is set in `widths` (bit b: b bits)."""
     w = np.ascontiguousarray(w, dtype=np.float32)
     D = np.ascontiguousarray(D, dtype=np.int64)
     bits = np.zeros(w.shape[0], dtype=np.uint8)
-    rc = lib().orc_allocate_bits(_p(w), _p(D), w.shape[0], int(budget_bits), _p(bits))
+    rc = lib().orc_allocate_bits_ladder(_p(w), _p(D), w.shape[0], int(budget_bits), int(widths), _p(bits))
     if rc != OK:
         err = OracleError(rc, "allocate_bits")
         err.bits = bits

@@ -127,7 +127,29 @@ float orc_noise(uint64_t seed, uint64_t tag, uint32_t n, uint64_t d, int noise_b
 
 /* ------------------------------------------------------------------------- */
 
-static int width_ok(int b) { return b == 1 || b == 2 || b == 4 || b == 8; }
+/* Any whole number of bits from 1 to 8 (Sec. 4.3 lowers a width one bit at a time). */
+static int width_ok(int b) { return b >= 1 && b <= 8; }
+
+/* The bit stream is linear and LSB-first: bit k of the stream is bit (k mod 8) of byte
+ * floor(k / 8), and the code of element j of a group occupies stream bits [j*b, j*b + b).
+ * A code whose width does not divide 8 may straddle two bytes. */
+static void put_code(uint8_t* dst, int64_t j, int b, unsigned code)
+{
+    for (int k = 0; k < b; ++k) {
+        int64_t bit = j * b + k;
+        if ((code >> k) & 1u) dst[bit / 8] |= (uint8_t)(1u << (bit % 8));
+    }
+}
+
+static unsigned get_code(const uint8_t* src, int64_t j, int b)
+{
+    unsigned code = 0;
+    for (int k = 0; k < b; ++k) {
+        int64_t bit = j * b + k;
+        code |= (unsigned)((src[bit / 8] >> (bit % 8)) & 1u) << k;
+    }
+    return code;
+}
 
 int orc_packed_bytes(int64_t N, int64_t D, int32_t G, const uint8_t* bits,
                      uint64_t* offsets, uint64_t* total)
@@ -237,8 +259,7 @@ int orc_quantize_group(const void* x, int dtype, int64_t first, int64_t len, int
         float h = load_elem(x, dtype, first + j);
         float noise = orc_noise(seed, tag, n, d_start + (uint64_t)j, noise_bits);
         unsigned code = stochastic_code(h, mn, inv, B, noise, noise_bits);
-        int64_t bitpos = j * b;
-        dst[bitpos / 8] |= (uint8_t)(code << (bitpos % 8));
+        put_code(dst, j, b, code);
     }
     return ORC_OK;
 }
@@ -273,8 +294,7 @@ int orc_dequantize_group(const uint8_t* src, const float* header2, int b, int64_
     if (!src || !header2 || !out || len <= 0 || !width_ok(b)) return ORC_EINVAL;
     float mn = header2[0], scale = header2[1];
     for (int64_t j = 0; j < len; ++j) {
-        int64_t bitpos = j * b;
-        unsigned code = (src[bitpos / 8] >> (bitpos % 8)) & ((1u << b) - 1u);
+        unsigned code = get_code(src, j, b);
         float v = fmaf((float)code, scale, mn);
         if (out_dtype == 0)
             ((float*)out)[first + j] = v;
@@ -377,8 +397,7 @@ int orc_quantize_group_bf16(const void* x, int dtype, int64_t first, int64_t len
         float h = load_elem(x, dtype, first + j);
         float noise = orc_noise(seed, tag, n, d_start + (uint64_t)j, noise_bits);
         unsigned code = stochastic_code(h, z, inv, B, noise, noise_bits);
-        int64_t bitpos = j * b;
-        dst[bitpos / 8] |= (uint8_t)(code << (bitpos % 8));
+        put_code(dst, j, b, code);
     }
     return ORC_OK;
 }
@@ -478,49 +497,67 @@ int orc_quantize_codes(const void* x, int dtype, int64_t N, int64_t D, int32_t G
 }
 
 /* ------------------------------------------------------------------------- */
-/* Sec. 4.3: start every item at 8 bits and keep applying the cheapest move    */
-/* until the budget of Prob. (9) holds.  A move is one rung of 8->4->2->1; its  */
-/* price is the variance added, w (1/B_new^2 - 1/B_old^2), per bit freed,       */
-/* D (b_old - b_new).  Plain repeated linear scan: no heap, no sort.           */
+/* Sec. 4.3: start every item at the widest allowed width and keep applying the  */
+/* cheapest move until the budget of Prob. (9) holds.  The allowed widths are a    */
+/* set given as a mask (bit b set: b bits allowed); a move takes one item to the   */
+/* next narrower allowed width.  With every width allowed this is the paper's      */
+/* one-bit-at-a-time greedy.  The price of a move is the variance it adds,         */
+/* w (1/B_new^2 - 1/B_old^2), per bit it frees, D (b_old - b_new).                 */
+/* Plain repeated linear scan: no heap, no sort.                                  */
 
-static double move_price(float w, int64_t D, int b_now)
+static int next_narrower(uint32_t widths, int b)
 {
-    double c;
-    if (b_now == 8) c = (1.0 / 225.0 - 1.0 / 65025.0) / 4.0;
-    else if (b_now == 4) c = (1.0 / 9.0 - 1.0 / 225.0) / 2.0;
-    else c = 1.0 - 1.0 / 9.0;
+    for (int c = b - 1; c >= 1; --c)
+        if ((widths >> c) & 1u) return c;
+    return 0;
+}
+
+static double move_price(float w, int64_t D, int b_now, int b_next)
+{
+    double B_now = (double)((1 << b_now) - 1), B_next = (double)((1 << b_next) - 1);
+    double c = (1.0 / (B_next * B_next) - 1.0 / (B_now * B_now)) / (double)(b_now - b_next);
     return ((double)w * c) / (double)D;
 }
 
-int orc_allocate_bits(const float* w, const int64_t* D, int64_t M,
-                      int64_t budget_bits, uint8_t* bits_out)
+int orc_allocate_bits_ladder(const float* w, const int64_t* D, int64_t M,
+                             int64_t budget_bits, uint32_t widths, uint8_t* bits_out)
 {
     if (!w || !D || !bits_out || M <= 0 || budget_bits < 0) return ORC_EINVAL;
+    if ((widths & ~0x1feu) != 0 || (widths & 0x1feu) == 0) return ORC_EINVAL;
     for (int64_t i = 0; i < M; ++i)
         if (!(w[i] >= 0.0f) || !isfinite(w[i]) || D[i] <= 0) return ORC_EINVAL;
-    /* 128-bit-safe enough: sum of D*8 stays far below 2^63 for any real tensor */
+    int widest = next_narrower(widths, 9);
+    /* the sum of D * 8 stays far below 2^63 for any real tensor */
     int64_t used = 0;
     for (int64_t i = 0; i < M; ++i) {
-        bits_out[i] = 8;
-        used += 8 * D[i];
+        bits_out[i] = (uint8_t)widest;
+        used += widest * D[i];
     }
     while (used > budget_bits) {
         int64_t best = -1;
         double best_price = 0.0;
         for (int64_t i = 0; i < M; ++i) {
-            if (bits_out[i] == 1) continue;
-            double price = move_price(w[i], D[i], bits_out[i]);
+            int nb = next_narrower(widths, bits_out[i]);
+            if (nb == 0) continue;
+            double price = move_price(w[i], D[i], bits_out[i], nb);
             if (best < 0 || price < best_price) { /* ties: the lowest index wins */
                 best = i;
                 best_price = price;
             }
         }
-        if (best < 0) return ORC_EINFEASIBLE; /* everything already at one bit */
-        int nb = bits_out[best] / 2;
+        if (best < 0) return ORC_EINFEASIBLE; /* everything already at the narrowest width */
+        int nb = next_narrower(widths, bits_out[best]);
         used -= D[best] * (bits_out[best] - nb);
         bits_out[best] = (uint8_t)nb;
     }
     return ORC_OK;
+}
+
+/* The widths {1, 2, 4, 8}: a code never straddles a byte. */
+int orc_allocate_bits(const float* w, const int64_t* D, int64_t M,
+                      int64_t budget_bits, uint8_t* bits_out)
+{
+    return orc_allocate_bits_ladder(w, D, M, budget_bits, 0x116u, bits_out);
 }
 
 /* The objective of Prob. (9), sum_i w_i / B_i^2, in double precision. */

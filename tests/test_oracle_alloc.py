@@ -139,3 +139,97 @@ def test_tiered_sensitivities_give_the_intended_multiset():
     bits = oracle.allocate_bits(w, D, 2 * wl.N * wl.D)
     assert np.array_equal(bits, wl.bits)
     assert bits.astype(np.float64).mean() == 2.0
+
+
+# --------------------------------------------------------------------------- any set of widths
+
+ALL = tuple(range(1, 9))
+
+
+def _mask(widths):
+    return sum(1 << b for b in widths)
+
+
+def test_width_masks_are_validated():
+    w = np.ones(3, dtype=np.float32)
+    D = np.full(3, 16, dtype=np.int64)
+    for bad in (0, 1, 1 << 9, 0x116 | 1, 0x116 | (1 << 9)):
+        with pytest.raises(oracle.OracleError) as e:
+            oracle.allocate_bits(w, D, 100, widths=bad)
+        assert e.value.code == oracle.EINVAL
+    assert oracle.WIDTHS_POW2 == _mask((1, 2, 4, 8)) and oracle.WIDTHS_ALL == _mask(ALL)
+
+
+@pytest.mark.parametrize("widths", [(2, 4), (3,), (1, 3, 8), (5, 6, 7)])
+def test_allocation_stays_inside_the_allowed_widths(widths):
+    rng = np.random.default_rng(sum(widths))
+    M = 50
+    w = rng.lognormal(0, 2, M).astype(np.float32)
+    D = rng.choice([256, 512, 4096], M).astype(np.int64)
+    lo, hi = min(widths), max(widths)
+    # loose budget: everything at the widest width
+    assert set(oracle.allocate_bits(w, D, hi * int(D.sum()), _mask(widths))) == {hi}
+    # exactly the narrowest width everywhere is feasible, one bit less is not
+    assert set(oracle.allocate_bits(w, D, lo * int(D.sum()), _mask(widths))) == {lo}
+    if len(widths) > 1 or True:
+        with pytest.raises(oracle.OracleError) as e:
+            oracle.allocate_bits(w, D, lo * int(D.sum()) - 1, _mask(widths))
+        assert e.value.code == oracle.EINFEASIBLE
+    mid = (lo + hi) * int(D.sum()) // 2
+    bits = oracle.allocate_bits(w, D, mid, _mask(widths))
+    assert set(bits) <= set(widths)
+    assert int((bits.astype(np.int64) * D).sum()) <= mid
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_one_bit_steps_with_equal_sizes_are_exactly_optimal(seed):
+    """Sec. 4.3's greedy lowers one width by one bit at a time.  When all items have the same
+    size every move frees the same number of bits, the cost of an item is convex in its
+    width, and the greedy answer is the exact minimum of Prob. (9): checked against all
+    8^M assignments."""
+    rng = np.random.default_rng(300 + seed)
+    M = 5
+    w = rng.lognormal(0, 1.5, M).astype(np.float32)
+    D = np.full(M, 32, dtype=np.int64)
+    budget = int(rng.uniform(1.0, 7.9) * D.sum())
+    bits = oracle.allocate_bits(w, D, budget, oracle.WIDTHS_ALL)
+    assert int((bits.astype(np.int64) * D).sum()) <= budget
+    best = min(_cost(w, c) for c in itertools.product(ALL, repeat=M)
+               if int((np.array(c) * D).sum()) <= budget)
+    assert _cost(w, bits) <= best * (1 + 1e-12)
+
+
+@pytest.mark.parametrize("widths", [ALL, (1, 2, 4, 8), (2, 3, 5, 8)])
+def test_moves_over_any_width_set_form_a_cheapest_first_prefix(widths):
+    rng = np.random.default_rng(400 + len(widths) + widths[1])
+    M = 40
+    w = rng.lognormal(0, 1.5, M).astype(np.float32)
+    D = rng.choice([256, 1024, 4096, 25088], M).astype(np.int64)
+    budget = int(rng.uniform(min(widths) + 0.3, max(widths) - 0.5) * D.sum())
+    bits = oracle.allocate_bits(w, D, budget, _mask(widths))
+    w64 = w.astype(np.float64)
+    order = sorted(widths, reverse=True)
+    steps = list(zip(order[:-1], order[1:]))           # (from, to), widest first
+
+    def price(i, hi, lo):
+        Bh, Bl = 2.0 ** hi - 1, 2.0 ** lo - 1
+        return w64[i] * (1 / Bl ** 2 - 1 / Bh ** 2) / (D[i] * (hi - lo))
+
+    applied = [(price(i, hi, lo), i, hi, lo) for i in range(M) for hi, lo in steps if bits[i] <= lo]
+    pending = [price(i, hi, lo) for i in range(M) for hi, lo in steps if bits[i] > lo]
+    assert applied and pending
+    assert max(applied)[0] <= min(pending) * (1 + 1e-12)
+    _, i, hi, lo = max(applied)                        # the dearest applied move was needed
+    assert int((bits.astype(np.int64) * D).sum()) + int(D[i]) * (hi - lo) > budget
+
+
+def test_one_bit_steps_use_the_budget_at_least_as_well_as_power_of_two_widths():
+    rng = np.random.default_rng(77)
+    M = 128
+    w = rng.lognormal(0, 2, M).astype(np.float32)
+    D = np.full(M, 4096, dtype=np.int64)
+    for avg in (1.5, 2.0, 3.0, 4.5):
+        budget = int(avg * D.sum())
+        fine = oracle.allocate_bits(w, D, budget, oracle.WIDTHS_ALL)
+        coarse = oracle.allocate_bits(w, D, budget, oracle.WIDTHS_POW2)
+        assert oracle.objective(w, fine) <= oracle.objective(w, coarse) * (1 + 1e-12)

@@ -31,7 +31,7 @@ def test_bf16_floor_and_ceil_against_the_sorted_table_of_all_bfloat16_values():
     assert oracle.bf16_to_float(0x3F80) == 1.0 and oracle.bf16_to_float(0xC000) == -2.0
 
 
-@pytest.mark.parametrize("b", [1, 2, 4, 8])
+@pytest.mark.parametrize("b", [1, 2, 3, 4, 5, 6, 7, 8])
 def test_bf16_header_covers_the_group_and_is_tight(b):
     rng = np.random.default_rng(b)
     x = (rng.standard_normal((4, 6 * 256)) * np.exp(rng.uniform(-6, 6, (4, 1))) + rng.standard_normal((4, 1)) * 10).astype(np.float32)

@@ -14,7 +14,7 @@ import oracle
 from paper_2104_14129_amd import synth
 from _helpers import philox_witness, round_fraction_to_f32, witness_noise_words
 
-WIDTHS = (1, 2, 4, 8)
+WIDTHS = (1, 2, 3, 4, 5, 6, 7, 8)
 
 
 # --------------------------------------------------------------------------- stats
@@ -192,8 +192,12 @@ def test_brute_force_tiny_tensor_with_rational_arithmetic(b, noise_bits):
                     # 16-bit noise is added to u in one binary32 addition (numpy's float32 add) and floored
                     q = int(np.floor(np.float32(min(u32, np.float32(B))) + np.float32(float(noise))))
                 assert codes[n, d] == q, (n, d)
-                bitpos = j * b
-                want_bytes[int(offsets[n]) + g * G * b // 8 + bitpos // 8] |= q << (bitpos % 8)
+                bitpos = j * b               # the code as a b-bit field of a little-endian integer
+                first = int(offsets[n]) + g * G * b // 8 + bitpos // 8
+                field = q << (bitpos % 8)    # at most 15 bits: one or two bytes
+                want_bytes[first] |= field & 0xff
+                if field >> 8:
+                    want_bytes[first + 1] |= field >> 8
     assert np.array_equal(packed, want_bytes)
 
 
@@ -222,8 +226,8 @@ def test_bit_stream_layout_against_numpy_bit_routines(b):
 
 
 def test_mixed_widths_offsets_and_sizes():
-    bits = np.array([1, 8, 2, 4, 1], dtype=np.uint8)
-    N, D = 5, 3 * 256
+    bits = np.array([1, 8, 3, 2, 7, 4, 5, 1, 6], dtype=np.uint8)
+    N, D = 9, 3 * 256
     offsets, total = oracle.packed_bytes(N, D, 256, bits)
     per = 3 * 256 * bits.astype(np.int64) // 8
     assert list(offsets) == list(np.concatenate([[0], np.cumsum(per)[:-1]]))
@@ -273,7 +277,7 @@ def _monte_carlo(x, b, seeds, noise_bits=24):
     return mean, var, header
 
 
-@pytest.mark.parametrize("b,noise_bits", [(2, 24), (2, 16), (1, 24), (4, 24), (8, 16)])
+@pytest.mark.parametrize("b,noise_bits", [(2, 24), (2, 16), (1, 24), (4, 24), (8, 16), (3, 16), (6, 24)])
 def test_unbiased_and_variance_matches_closed_form(b, noise_bits):
     """E[h^] = h (Sec. 4.1 / Thm. 1) and Var[h^] = scale^2 * p(1-p) per element, summed per
     group, where p is the fractional part of the scaled value -- computed here in float64,
