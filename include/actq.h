@@ -22,7 +22,7 @@
  *     launch; a call that fails validation launches nothing.
  *   - Inputs must be finite.  Non-finite inputs are memory-safe but the codes
  *     they produce are unspecified.
- *   - Supported group size: G = 256.  Supported widths: b_n in {1, 2, 4, 8}.
+ *   - Supported group size: G = 256.  Supported widths: every b_n from 1 to 8.
  *   - x / out must be aligned to 16 bytes, packed to 16 bytes, header and offsets to 8,
  *     bits (device) to 4.
  */
@@ -69,15 +69,17 @@ const char* actq_last_error(void);
  * Sample n occupies ng * G * b_n / 8 bytes starting at byte
  * offsets_host[n] = sum_{m<n} ng * G * b_m / 8; *total_host receives the sum
  * over all samples.  Inside a sample, group g starts at g * G * b_n / 8 and the
- * code of in-group element j occupies bits [(j*b_n) mod 8, +b_n) of byte
- * floor(j*b_n / 8): an LSB-first linear bit stream.  The padding codes of a
+ * code of in-group element j occupies bits [j*b_n, j*b_n + b_n) of the group's
+ * stream, where stream bit k is bit (k mod 8) of byte floor(k / 8): an LSB-first
+ * linear bit stream.  A code whose width does not divide 8 may straddle two
+ * bytes; a group always ends on a byte (32*b_n bytes).  The padding codes of a
  * ragged last group are zero.
  *
- * bits_host [N]    host, in   : b_n in {1,2,4,8}
+ * bits_host [N]    host, in   : b_n in 1..8
  * offsets_host [N] host, out  : may be NULL when only the total is wanted
  * total_host       host, out  : may be NULL
  * Errors: ACTQ_EINVAL on N <= 0, D <= 0, unsupported G, a width outside
- * {1,2,4,8}, or both outputs NULL.
+ * 1..8, or both outputs NULL.
  */
 int actq_packed_bytes(int64_t N, int64_t D, int32_t G, const uint8_t* bits_host,
                       uint64_t* offsets_host, uint64_t* total_host);
@@ -121,14 +123,14 @@ int actq_group_stats(const void* x, actq_dtype dt, int64_t N, int64_t D, int32_t
  * a seed.  Requires N < 2^32 and D < 2^34.
  *
  * x        device, in  : N*D elements of dtype `dt`
- * bits     device, in  : [N] widths b_n in {1,2,4,8}
+ * bits     device, in  : [N] widths b_n in 1..8
  * offsets  device, in  : [N] byte offsets as produced by actq_packed_bytes
  * packed   device, out : the bit stream; `packed_capacity` bytes are writable
  * header   device, out : [N*ng] groups in format hf: {float Z, float scale} or
  *                        {uint16 Z, uint16 R} (bfloat16 bit patterns), 8-byte aligned
  *
  * bits and offsets live on the device, so the host cannot check them: a sample
- * whose width is not in {1,2,4,8} or whose byte range would leave
+ * whose width is not in 1..8 or whose byte range would leave
  * [0, packed_capacity) is skipped (no byte of its output is written).
  */
 int actq_quantize_pack(const void* x, actq_dtype dt, int64_t N, int64_t D, int32_t G,
@@ -171,26 +173,59 @@ int actq_unpack_dequantize(const void* packed, uint64_t packed_capacity,
 int actq_sample_sensitivity(const float* grange, int64_t N, int64_t ng, int32_t G,
                             const float* grad2, float* w, void* stream);
 
+/* Sets of allowed widths for the allocator: bit b set means b bits is allowed. */
+#define ACTQ_WIDTHS_POW2 0x116u /* {1, 2, 4, 8}: a code never straddles a byte */
+#define ACTQ_WIDTHS_ALL 0x1FEu  /* {1, ..., 8}: the one-bit-at-a-time greedy of Sec. 4.3 */
+
 /*
  * Greedy solution of the bit-allocation problem (Sec. 4.2, Prob. (9); greedy
  * with a binary heap as in Sec. 4.3): minimise sum_i w_i / B_i^2 subject to
  * sum_i D_i * b_i <= budget_bits, B_i = 2^{b_i} - 1.
  *
- * Every item starts at 8 bits.  A move lowers one item one rung on the ladder
- * 8 -> 4 -> 2 -> 1.  Its price is the variance it adds per bit it frees,
+ * Every item starts at the widest allowed width.  A move lowers one item to the
+ * next narrower allowed width, b_hi -> b_lo.  Its price is the variance it adds
+ * per bit it frees,
  *   key = (double)w_i * c / (double)D_i,
- *   c(8->4) = (1/225 - 1/65025)/4, c(4->2) = (1/9 - 1/225)/2, c(2->1) = 1 - 1/9,
+ *   c = (1/B_lo^2 - 1/B_hi^2) / (b_hi - b_lo)   evaluated in double,
  * and while the budget is exceeded the move with the smallest (key, i) is
  * applied.  The header cost of the groups is not part of the budget.
  *
  * w        host, in  : [M] sensitivities, finite and >= 0
  * D        host, in  : [M] element counts, > 0
+ * widths             : non-empty subset of bits 1..8, e.g. ACTQ_WIDTHS_POW2
  * bits_out host, out : [M]
- * Errors: ACTQ_EINVAL on bad arguments; ACTQ_EINFEASIBLE when even one bit per
- * element exceeds the budget (bits_out is then all ones).
+ * Errors: ACTQ_EINVAL on bad arguments; ACTQ_EINFEASIBLE when even the narrowest
+ * allowed width everywhere exceeds the budget (bits_out is then all narrowest).
  */
 int actq_allocate_bits(const float* w, const int64_t* D, int64_t M,
-                       int64_t budget_bits, uint8_t* bits_out);
+                       int64_t budget_bits, uint32_t widths, uint8_t* bits_out);
+
+/*
+ * The same allocation computed on the device, so that a step needs no host
+ * round trip between the statistics and the quantizer (Sec. 4.3 runs the
+ * allocator inside the training step).  The result equals actq_allocate_bits
+ * bit for bit: the greedy's answer is fixed by the price of its last move, which
+ * one workgroup finds by radix selection over the 64-bit price patterns; moves
+ * of exactly that price are applied in (i, step) order.  It also writes the byte
+ * offsets that actq_packed_bytes would compute for the chosen widths.
+ *
+ * w        device, in  : [M] sensitivities
+ * D_items  device, in  : [M] element counts, or NULL: every item has D elements
+ * D                    : element count per item when D_items is NULL (else ignored)
+ * G                    : group size used for the offsets (256)
+ * bits     device, out : [M]
+ * offsets  device, out : [M] offsets[i] = sum_{j<i} ceil(D_j / G) * G * b_j / 8
+ * result   device, out : [2] result[0] = total bytes of the bit stream,
+ *                        result[1] = ACTQ_OK, ACTQ_EINVAL (some w not finite or
+ *                        negative, or a D_items entry outside (0, 2^34)) or
+ *                        ACTQ_EINFEASIBLE; in both failure cases every item gets
+ *                        the narrowest width, so the outputs stay usable
+ * Requires sum_i 8 * D_i < 2^63.  Asynchronous on `stream`; the return value covers
+ * only the host-side checks and the launch.
+ */
+int actq_allocate_bits_device(const float* w, const int64_t* D_items, int64_t D, int64_t M,
+                              int32_t G, int64_t budget_bits, uint32_t widths,
+                              uint8_t* bits, uint64_t* offsets, int64_t* result, void* stream);
 
 #ifdef __cplusplus
 }

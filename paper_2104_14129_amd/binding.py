@@ -20,9 +20,11 @@ ACTQ_F32, ACTQ_F16 = 0, 1
 G_DEFAULT = 256
 
 ACTQ_HDR_F32, ACTQ_HDR_BF16 = 0, 1
+ACTQ_WIDTHS_POW2, ACTQ_WIDTHS_ALL = 0x116, 0x1FE  # allowed-width sets of the allocator (bit b = b bits)
 
 EXPORTS = ("actq_version", "actq_last_error", "actq_packed_bytes", "actq_header_bytes", "actq_group_stats",
-           "actq_quantize_pack", "actq_unpack_dequantize", "actq_sample_sensitivity", "actq_allocate_bits")
+           "actq_quantize_pack", "actq_unpack_dequantize", "actq_sample_sensitivity", "actq_allocate_bits",
+           "actq_allocate_bits_device")
 
 
 class ActqError(RuntimeError):
@@ -62,7 +64,9 @@ def lib() -> ctypes.CDLL:
     L.actq_sample_sensitivity.restype = c.c_int
     L.actq_sample_sensitivity.argtypes = [vp, i64, i64, i32, vp, vp, vp]
     L.actq_allocate_bits.restype = c.c_int
-    L.actq_allocate_bits.argtypes = [vp, vp, i64, i64, vp]
+    L.actq_allocate_bits.argtypes = [vp, vp, i64, i64, c.c_uint32, vp]
+    L.actq_allocate_bits_device.restype = c.c_int
+    L.actq_allocate_bits_device.argtypes = [vp, vp, i64, i64, i32, i64, c.c_uint32, vp, vp, vp, vp]
     _lib = L
     return L
 
@@ -206,16 +210,47 @@ def sample_sensitivity(grange, grad2=None, w=None, G: int = G_DEFAULT, stream=No
     return w
 
 
-def allocate_bits(w_host, D_host, budget_bits: int) -> np.ndarray:
-    """Host: greedy widths in {1,2,4,8} for sensitivities w and sizes D under a bit budget."""
+def allocate_bits(w_host, D_host, budget_bits: int, widths: int = ACTQ_WIDTHS_POW2) -> np.ndarray:
+    """Host: greedy widths (from the set `widths`, bit b = b bits) for sensitivities w and sizes D
+    under a bit budget."""
     w = np.ascontiguousarray(w_host, dtype=np.float32)
     D = np.ascontiguousarray(D_host, dtype=np.int64)
     if w.ndim != 1 or D.shape != w.shape:
         raise ValueError("w and D must be 1-D arrays of equal length")
     bits = np.zeros(w.shape[0], dtype=np.uint8)
-    rc = lib().actq_allocate_bits(w.ctypes.data, D.ctypes.data, w.shape[0], int(budget_bits), bits.ctypes.data)
+    rc = lib().actq_allocate_bits(w.ctypes.data, D.ctypes.data, w.shape[0], int(budget_bits), int(widths),
+                                  bits.ctypes.data)
     if rc != ACTQ_OK:
         err = ActqError(rc, lib().actq_last_error().decode())
         err.bits = bits
         raise err
     return bits
+
+
+def allocate_bits_device(w, D, budget_bits: int, widths: int = ACTQ_WIDTHS_POW2, bits=None, offsets=None,
+                         result=None, G: int = G_DEFAULT, stream=None):
+    """Device: the same greedy allocation without a host round trip.  `w` is a float32 device
+    tensor [M]; `D` is an int (every item has D elements) or an int64 device tensor [M].
+    Returns (bits uint8 [M], offsets int64 [M], result int64 [2] = total bytes, status); nothing
+    is synchronised, so the status is the caller's to read when convenient."""
+    torch = _torch()
+    M = int(w.numel())
+    if bits is None:
+        bits = torch.empty(M, dtype=torch.uint8, device=w.device)
+    if offsets is None:
+        offsets = torch.empty(M, dtype=torch.int64, device=w.device)
+    if result is None:
+        result = torch.empty(2, dtype=torch.int64, device=w.device)
+    if bits.numel() != M or offsets.numel() != M or result.numel() != 2:
+        raise ValueError("bits and offsets must have M entries, result 2")
+    if isinstance(D, int):
+        d_items, d_uniform = None, D
+    else:
+        if D.numel() != M:
+            raise ValueError("D must have M entries")
+        d_items, d_uniform = _dev(D, torch.int64, "D"), 0
+    _check(lib().actq_allocate_bits_device(_dev(w, torch.float32, "w"), d_items, d_uniform, M, G,
+                                           int(budget_bits), int(widths), _dev(bits, torch.uint8, "bits"),
+                                           _dev(offsets, torch.int64, "offsets"),
+                                           _dev(result, torch.int64, "result"), _stream(stream)))
+    return bits, offsets, result

@@ -24,7 +24,7 @@ int fail(int code, const char* fmt, ...)
     return code;
 }
 
-static bool width_ok(unsigned b) { return b == 1 || b == 2 || b == 4 || b == 8; }
+static bool width_ok(unsigned b) { return b >= 1 && b <= 8; }
 
 static bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
@@ -57,6 +57,28 @@ static int check_dtype(const char* who, int dt)
 
 using namespace actq;
 
+namespace actq {
+
+// Allowed widths, widest first, and for every step down the variance it adds per bit it
+// frees, for a unit of w / D: (1/B_low^2 - 1/B_high^2) / (b_high - b_low), in double.
+bool make_ladder(uint32_t widths, Ladder* out)
+{
+    if ((widths & ~0x1FEu) != 0 || (widths & 0x1FEu) == 0) return false;
+    out->count = 0;
+    for (int b = 8; b >= 1; --b)
+        if ((widths >> b) & 1u) out->width[out->count++] = b;
+    for (int r = 0; r + 1 < out->count; ++r) {
+        const int hi = out->width[r], lo = out->width[r + 1];
+        const double Bh = static_cast<double>((1 << hi) - 1), Bl = static_cast<double>((1 << lo) - 1);
+        out->price[r] = (1.0 / (Bl * Bl) - 1.0 / (Bh * Bh)) / static_cast<double>(hi - lo);
+    }
+    for (int r = out->count; r < 8; ++r) out->width[r] = 0;
+    for (int r = (out->count > 0 ? out->count - 1 : 0); r < 7; ++r) out->price[r] = 0.0;
+    return true;
+}
+
+}  // namespace actq
+
 extern "C" {
 
 int actq_version(void) { return 200; }
@@ -83,7 +105,7 @@ int actq_packed_bytes(int64_t N, int64_t D, int32_t G, const uint8_t* bits_host,
     const uint64_t group_bytes_per_bit = static_cast<uint64_t>(G) / 8;
     for (int64_t n = 0; n < N; ++n)
         if (!width_ok(bits_host[n]))
-            return fail(ACTQ_EINVAL, "actq_packed_bytes: bits[%lld]=%u is not one of 1,2,4,8", (long long)n, bits_host[n]);
+            return fail(ACTQ_EINVAL, "actq_packed_bytes: bits[%lld]=%u is not in 1..8", (long long)n, bits_host[n]);
     uint64_t acc = 0;
     for (int64_t n = 0; n < N; ++n) {
         if (offsets_host) offsets_host[n] = acc;
@@ -155,55 +177,79 @@ int actq_sample_sensitivity(const float* grange, int64_t N, int64_t ng, int32_t 
     return launch_sample_sensitivity(grange, N, ng, G, grad2, w, stream);
 }
 
-// Greedy allocator of Sec. 4.3 on the ladder 8 -> 4 -> 2 -> 1.  The heap holds, for
-// every item that can still be lowered, the price of its next move; ties go to the
-// lowest item index.  An item's successive prices strictly increase, so popping the
-// cheapest move and pushing the item's next one visits moves in globally sorted order.
+// Greedy allocator of Sec. 4.3 over the allowed widths, widest first.  The heap holds, for
+// every item that can still be lowered, the price of its next move; ties go to the lowest
+// item index.  An item's successive prices never decrease (its cost is convex in the width),
+// so popping the cheapest move and pushing the item's next one visits moves in globally
+// sorted order.
 int actq_allocate_bits(const float* w, const int64_t* D, int64_t M, int64_t budget_bits,
-                       uint8_t* bits_out)
+                       uint32_t widths, uint8_t* bits_out)
 {
     if (!w || !D || !bits_out) return fail(ACTQ_EINVAL, "actq_allocate_bits: null pointer");
     if (M <= 0) return fail(ACTQ_EINVAL, "actq_allocate_bits: M must be positive");
     if (budget_bits < 0) return fail(ACTQ_EINVAL, "actq_allocate_bits: negative budget");
+    actq::Ladder lad;
+    if (!actq::make_ladder(widths, &lad))
+        return fail(ACTQ_EINVAL, "actq_allocate_bits: widths mask 0x%x must be a non-empty subset of bits 1..8", widths);
     __int128 used = 0;
     for (int64_t i = 0; i < M; ++i) {
         if (!(w[i] >= 0.0f) || !std::isfinite(w[i]))
             return fail(ACTQ_EINVAL, "actq_allocate_bits: w[%lld] must be finite and >= 0", (long long)i);
         if (D[i] <= 0) return fail(ACTQ_EINVAL, "actq_allocate_bits: D[%lld] must be positive", (long long)i);
-        used += static_cast<__int128>(D[i]) * 8;
+        used += static_cast<__int128>(D[i]) * lad.width[0];
     }
-    // variance added per bit freed, for a unit of w / D
-    const double step_price[3] = {
-        (1.0 / 225.0 - 1.0 / 65025.0) / 4.0,  // 8 -> 4
-        (1.0 / 9.0 - 1.0 / 225.0) / 2.0,      // 4 -> 2
-        1.0 - 1.0 / 9.0,                      // 2 -> 1
+    auto price = [&](int64_t i, int rung) {
+        return (static_cast<double>(w[i]) * lad.price[rung]) / static_cast<double>(D[i]);
     };
-    auto price = [&](int64_t i, int b_now) {
-        const double c = b_now == 8 ? step_price[0] : (b_now == 4 ? step_price[1] : step_price[2]);
-        return (static_cast<double>(w[i]) * c) / static_cast<double>(D[i]);
+    std::vector<uint8_t> rung(static_cast<size_t>(M), 0);  // position of every item on the ladder
+    auto finish = [&]() {
+        for (int64_t i = 0; i < M; ++i) bits_out[i] = static_cast<uint8_t>(lad.width[rung[i]]);
     };
-    for (int64_t i = 0; i < M; ++i) bits_out[i] = 8;
     const __int128 budget = budget_bits;
-    if (used <= budget) return ACTQ_OK;
+    if (used <= budget) { finish(); return ACTQ_OK; }
 
     using Move = std::pair<double, int64_t>;  // (price, item): lexicographic order is the rule
     std::vector<Move> init;
-    init.reserve(static_cast<size_t>(M));
-    for (int64_t i = 0; i < M; ++i) init.emplace_back(price(i, 8), i);
+    if (lad.count > 1) {
+        init.reserve(static_cast<size_t>(M));
+        for (int64_t i = 0; i < M; ++i) init.emplace_back(price(i, 0), i);
+    }
     std::priority_queue<Move, std::vector<Move>, std::greater<Move>> heap(std::greater<Move>(), std::move(init));
     while (used > budget) {
         if (heap.empty()) {
-            return fail(ACTQ_EINFEASIBLE, "actq_allocate_bits: budget %lld is below one bit per element", (long long)budget_bits);
+            finish();
+            return fail(ACTQ_EINFEASIBLE, "actq_allocate_bits: budget %lld is below %d bit(s) per element",
+                        (long long)budget_bits, lad.width[lad.count - 1]);
         }
         const int64_t i = heap.top().second;
         heap.pop();
-        const int b_now = bits_out[i];
-        const int b_new = b_now / 2;
-        used -= static_cast<__int128>(D[i]) * (b_now - b_new);
-        bits_out[i] = static_cast<uint8_t>(b_new);
-        if (b_new > 1) heap.emplace(price(i, b_new), i);
+        const int r = rung[i];
+        used -= static_cast<__int128>(D[i]) * (lad.width[r] - lad.width[r + 1]);
+        rung[i] = static_cast<uint8_t>(r + 1);
+        if (r + 2 < lad.count) heap.emplace(price(i, r + 1), i);
     }
+    finish();
     return ACTQ_OK;
+}
+
+int actq_allocate_bits_device(const float* w, const int64_t* D_items, int64_t D, int64_t M, int32_t G,
+                              int64_t budget_bits, uint32_t widths, uint8_t* bits, uint64_t* offsets,
+                              int64_t* result, void* stream)
+{
+    if (!w || !bits || !offsets || !result) return fail(ACTQ_EINVAL, "actq_allocate_bits_device: null pointer");
+    if (M <= 0 || M >= (int64_t(1) << 31)) return fail(ACTQ_EINVAL, "actq_allocate_bits_device: M must be in [1, 2^31)");
+    if (G != kGroup) return fail(ACTQ_EINVAL, "actq_allocate_bits_device: unsupported group size G=%d (supported: %d)", G, kGroup);
+    if (!D_items && (D <= 0 || D >= (int64_t(1) << 34)))
+        return fail(ACTQ_EINVAL, "actq_allocate_bits_device: D must be in [1, 2^34) when D_items is null");
+    if (!D_items && static_cast<__int128>(D) * M * 8 >= (static_cast<__int128>(1) << 63))
+        return fail(ACTQ_EINVAL, "actq_allocate_bits_device: 8 * M * D must stay below 2^63");
+    if (budget_bits < 0) return fail(ACTQ_EINVAL, "actq_allocate_bits_device: negative budget");
+    if (!aligned(w, 4) || !aligned(D_items, 8) || !aligned(offsets, 8) || !aligned(result, 8))
+        return fail(ACTQ_EINVAL, "actq_allocate_bits_device: w must be 4-byte aligned, D_items, offsets and result 8-byte aligned");
+    actq::Ladder lad;
+    if (!actq::make_ladder(widths, &lad))
+        return fail(ACTQ_EINVAL, "actq_allocate_bits_device: widths mask 0x%x must be a non-empty subset of bits 1..8", widths);
+    return launch_allocate_bits(w, D_items, D, M, budget_bits, lad, bits, offsets, result, stream);
 }
 
 }  // extern "C"

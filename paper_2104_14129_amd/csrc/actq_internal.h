@@ -13,6 +13,14 @@ constexpr int kGroup = 256;  // the one supported group size: one wavefront x 4 
 // Records a message for actq_last_error() and returns `code`.
 int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 
+// The allowed widths of the allocator, widest first, with the price of every step down.
+struct Ladder {
+    int count;        // number of allowed widths, 1..8
+    int width[8];     // width[0] > width[1] > ... ; unused entries are 0
+    double price[7];  // price[r]: step width[r] -> width[r+1]
+};
+bool make_ladder(uint32_t widths, Ladder* out);
+
 // Launchers (kernels file).  Arguments are already validated.  Each returns ACTQ_OK or
 // ACTQ_EHIP after recording the HIP error text.
 int launch_group_stats(const void* x, int dtype, int64_t N, int64_t D, float* gmin,
@@ -25,6 +33,8 @@ int launch_unpack_dequantize(const void* packed, uint64_t capacity, const void* 
                              int64_t D, void* out, int out_dtype, void* stream);
 int launch_sample_sensitivity(const float* grange, int64_t N, int64_t ng, int32_t G,
                               const float* grad2, float* w, void* stream);
+int launch_allocate_bits(const float* w, const int64_t* D_items, int64_t D, int64_t M, int64_t budget_bits,
+                         const Ladder& lad, uint8_t* bits, uint64_t* offsets, int64_t* result, void* stream);
 
 }  // namespace actq
 

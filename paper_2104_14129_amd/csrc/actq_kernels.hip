@@ -471,6 +471,29 @@ __device__ __forceinline__ void encode_tile(const TileRegs& td, const uint32_t (
         const uint32_t w = stage[lane];
         if (lane * 4 < groups * 64)
             __builtin_nontemporal_store(w, reinterpret_cast<uint32_t*>(dst_tile) + lane);
+    } else if (B != 1) {
+        // B = 3, 5, 6, 7: a lane's 4*B bits start at bit 4*B*lane of the group and may cross a
+        // 32-bit word.  The lanes OR their bits into the zeroed slice, which then leaves as
+        // whole words.
+#pragma unroll
+        for (int j = 0; j < 4; ++j) stage[j * 64 + lane] = 0u;
+        wave_lds_handover();
+#pragma unroll
+        for (int u = 0; u < kTileGroups; ++u) {
+            const uint32_t bit = static_cast<uint32_t>(u) * (256u * B) + static_cast<uint32_t>(lane) * (4u * B);
+            const uint32_t word = bit >> 5, shift = bit & 31u;
+            __hip_atomic_fetch_or(stage + word, piece[u] << shift, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+            if (shift + 4u * B > 32u)
+                __hip_atomic_fetch_or(stage + word + 1, piece[u] >> (32u - shift), __ATOMIC_RELAXED,
+                                      __HIP_MEMORY_SCOPE_WAVEFRONT);
+        }
+        wave_lds_handover();
+#pragma unroll
+        for (int j = 0; j * 64 < 32 * B; ++j) {
+            const int idx = j * 64 + lane;
+            if (idx < groups * 8 * B)
+                __builtin_nontemporal_store(stage[idx], reinterpret_cast<uint32_t*>(dst_tile) + idx);
+        }
     } else {
         // B == 1: a lane holds a nibble per group; neighbours merge into a byte first
         const uint32_t nib = piece[0] | (piece[1] << 8) | (piece[2] << 16) | (piece[3] << 24);
@@ -561,7 +584,11 @@ __device__ __forceinline__ void quantize_one(const TileRegs& r, const Cursor& c,
     switch (b) {
         case 1: encode_tile<NOISE_BITS, VEC, 1>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, geo.hdr_bf16 != 0, stage); break;
         case 2: encode_tile<NOISE_BITS, VEC, 2>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, geo.hdr_bf16 != 0, stage); break;
+        case 3: encode_tile<NOISE_BITS, VEC, 3>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, geo.hdr_bf16 != 0, stage); break;
         case 4: encode_tile<NOISE_BITS, VEC, 4>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, geo.hdr_bf16 != 0, stage); break;
+        case 5: encode_tile<NOISE_BITS, VEC, 5>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, geo.hdr_bf16 != 0, stage); break;
+        case 6: encode_tile<NOISE_BITS, VEC, 6>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, geo.hdr_bf16 != 0, stage); break;
+        case 7: encode_tile<NOISE_BITS, VEC, 7>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, geo.hdr_bf16 != 0, stage); break;
         case 8: encode_tile<NOISE_BITS, VEC, 8>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, geo.hdr_bf16 != 0, stage); break;
         default: break;
     }
@@ -636,23 +663,29 @@ __device__ __forceinline__ void dequantize_tile(const uint8_t* __restrict__ src_
                                                 int64_t D, uint32_t n, uint32_t g0, int groups, uint32_t ng,
                                                 int lane)
 {
-    constexpr int lanes_per_word = 8 / B;  // a lane's four codes are 4*B bits of a 32-bit word
+    // a lane's four codes are the 4*B bits that start at bit 4*B*lane of the group: inside one
+    // 32-bit word when B divides 8, possibly across two words otherwise
+    constexpr bool kAligned = (8 % B) == 0;
     constexpr uint32_t code_mask = (1u << B) - 1u;
-    uint32_t word[kTileGroups];
+    const uint32_t first_word = static_cast<uint32_t>(lane) * (4u * B) >> 5;
+    const uint32_t shift = static_cast<uint32_t>(lane) * (4u * B) & 31u;
+    uint32_t word[kTileGroups], next[kTileGroups];
     f32x2 hd[kTileGroups];
 #pragma unroll
     for (int u = 0; u < kTileGroups; ++u) {
         if (u >= groups) continue;
         const uint32_t g = g0 + u;
         const uint32_t* src = reinterpret_cast<const uint32_t*>(src_sample + static_cast<uint64_t>(g) * (32 * B));
-        word[u] = __builtin_nontemporal_load(src + lane / lanes_per_word);
+        word[u] = __builtin_nontemporal_load(src + first_word);
+        if (!kAligned)  // the last lane's bits end with the group: stay inside it
+            next[u] = __builtin_nontemporal_load(src + min(first_word + 1u, static_cast<uint32_t>(8 * B - 1)));
         hd[u] = load_header<BF16>(header, static_cast<int64_t>(n) * ng + g, static_cast<float>(code_mask));
     }
 #pragma unroll
     for (int u = 0; u < kTileGroups; ++u) {
         if (u >= groups) continue;
         const uint32_t g = g0 + u;
-        const uint32_t piece = word[u] >> ((lane & (lanes_per_word - 1)) * (4 * B));
+        const uint32_t piece = kAligned ? word[u] >> shift : __builtin_amdgcn_alignbit(next[u], word[u], shift);
         float o[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
@@ -730,7 +763,7 @@ __device__ __forceinline__ void dequantize_any(const uint8_t* __restrict__ src_s
                                                const void* __restrict__ header, T* os,
                                                int64_t D, uint32_t n, uint32_t g0, int groups, uint32_t ng, int lane)
 {
-    if constexpr (sizeof(T) == 2)
+    if constexpr (sizeof(T) == 2 && (8 % B) == 0)
         dequantize_tile_f16<VEC, B, BF16>(src_sample, header, os, D, n, g0, groups, ng, lane);
     else
         dequantize_tile<T, VEC, B, BF16>(src_sample, header, os, D, n, g0, groups, ng, lane);
@@ -757,7 +790,11 @@ __global__ __launch_bounds__(kBlock) void unpack_dequantize_kernel(
         switch (b) {
             case 1: dequantize_any<T, VEC, 1, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
             case 2: dequantize_any<T, VEC, 2, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
+            case 3: dequantize_any<T, VEC, 3, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
             case 4: dequantize_any<T, VEC, 4, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
+            case 5: dequantize_any<T, VEC, 5, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
+            case 6: dequantize_any<T, VEC, 6, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
+            case 7: dequantize_any<T, VEC, 7, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
             case 8: dequantize_any<T, VEC, 8, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
             default: return;
         }
@@ -790,6 +827,189 @@ __global__ __launch_bounds__(kBlock) void sample_sensitivity_kernel(const float*
     if (threadIdx.x == 0) {
         const float total = (partial[0] + partial[1]) + (partial[2] + partial[3]);
         w[n] = coeff * total * (grad2 ? grad2[n] : 1.0f);
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// Sec. 4.3 on the device: the greedy allocation without the host in the loop.
+//
+// The greedy applies moves (item i, step r of the width ladder) in ascending order of
+// (price, i, r) until enough bits are freed, and an item's prices never decrease along the
+// ladder.  Its result is therefore fixed by the price of the last applied move: every move
+// strictly cheaper is applied, and the moves of exactly that price are applied in (i, r)
+// order until the budget holds.  That price is found by a radix selection over the 64-bit
+// patterns of the prices (non-negative doubles order like their bit patterns), eight passes
+// of eight bits, each a 256-bin histogram of freed bits; ties are then resolved with a
+// prefix sum in item order, and a second prefix sum turns the widths into byte offsets.
+// One workgroup does all of it out of LDS; prices are recomputed in every pass.
+
+constexpr int kAllocBlock = 1024;
+constexpr int kAllocWaves = kAllocBlock / kWave;
+
+struct AllocArgs {
+    int64_t M;
+    int64_t D;               // element count of every item when D_items is null
+    const int64_t* D_items;  // per-item element counts, or null
+    int64_t budget_bits;
+    Ladder lad;
+};
+
+__device__ __forceinline__ uint64_t wave_inclusive_scan(uint64_t v, int lane)
+{
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const uint64_t t = __shfl_up(v, d);
+        if (lane >= d) v += t;
+    }
+    return v;
+}
+
+// Exclusive prefix sum over the workgroup in thread order; `total` receives the sum.
+__device__ __forceinline__ uint64_t block_exclusive_scan(uint64_t v, uint64_t* wave_totals, uint64_t& total)
+{
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const uint64_t incl = wave_inclusive_scan(v, lane);
+    if (lane == kWave - 1) wave_totals[wave] = incl;
+    __syncthreads();
+    uint64_t before = 0, all = 0;
+#pragma unroll
+    for (int k = 0; k < kAllocWaves; ++k) {
+        const uint64_t t = wave_totals[k];
+        before += k < wave ? t : 0;
+        all += t;
+    }
+    __syncthreads();
+    total = all;
+    return before + incl - v;
+}
+
+// price of step r of item (w, D): two separately rounded double operations; -0.0 becomes +0.0
+__device__ __forceinline__ uint64_t price_bits(float w, int64_t D, double step_price)
+{
+    const double key = (static_cast<double>(w) * step_price) / static_cast<double>(D) + 0.0;
+    return static_cast<uint64_t>(__double_as_longlong(key));
+}
+
+__global__ __launch_bounds__(kAllocBlock) void allocate_bits_kernel(const float* __restrict__ w, AllocArgs a,
+                                                                    uint8_t* __restrict__ bits,
+                                                                    uint64_t* __restrict__ offsets,
+                                                                    int64_t* __restrict__ result)
+{
+    __shared__ uint64_t hist[256];
+    __shared__ uint64_t wave_totals[kAllocWaves];
+    __shared__ uint64_t sel_prefix, sel_below;
+    __shared__ int width[8];      // the ladder, in LDS because lanes index it independently
+    __shared__ double price[8];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int steps = a.lad.count - 1;
+    if (tid < 8) {
+        width[tid] = a.lad.width[tid];
+        price[tid] = tid < 7 ? a.lad.price[tid] : 0.0;
+    }
+    __syncthreads();
+    const int widest = width[0], narrowest = width[steps];
+
+    // totals and validation
+    uint64_t my_elems = 0;
+    bool bad = false;
+    for (int64_t i = tid; i < a.M; i += kAllocBlock) {
+        const float wi = w[i];
+        const int64_t Di = a.D_items ? a.D_items[i] : a.D;
+        if (!(wi >= 0.0f) || !__builtin_isfinite(wi) || Di <= 0 || Di >= (int64_t(1) << 34)) bad = true;
+        else my_elems += static_cast<uint64_t>(Di);
+    }
+    const bool invalid = __syncthreads_or(bad ? 1 : 0) != 0;
+    uint64_t elems;
+    block_exclusive_scan(my_elems, wave_totals, elems);
+    const uint64_t budget = static_cast<uint64_t>(a.budget_bits);
+    const bool loose = !invalid && elems * widest <= budget;
+    const bool infeasible = !invalid && elems * narrowest > budget;
+    int64_t status = invalid ? ACTQ_EINVAL : (infeasible ? ACTQ_EINFEASIBLE : ACTQ_OK);
+
+    uint64_t threshold = 0, below = 0, need = 0;
+    const bool search = !invalid && !loose && !infeasible;
+    if (search) {
+        need = elems * widest - budget;  // bits that must be freed, > 0
+        uint64_t prefix = 0;
+        for (int pass = 7; pass >= 0; --pass) {
+            if (tid < 256) hist[tid] = 0;
+            __syncthreads();
+            for (int64_t i = tid; i < a.M; i += kAllocBlock) {
+                const float wi = w[i];
+                const int64_t Di = a.D_items ? a.D_items[i] : a.D;
+                for (int r = 0; r < steps; ++r) {
+                    const uint64_t key = price_bits(wi, Di, price[r]);
+                    const bool in_range = pass == 7 || (key >> (8 * (pass + 1))) == prefix;
+                    if (in_range) {
+                        const uint64_t freed = static_cast<uint64_t>(Di) * (width[r] - width[r + 1]);
+                        __hip_atomic_fetch_add(&hist[(key >> (8 * pass)) & 255u], freed, __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_WORKGROUP);
+                    }
+                }
+            }
+            __syncthreads();
+            if (tid < kWave) {
+                // the bin in which the running sum of freed bits first reaches `need`
+                uint64_t h[4], mine = 0;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) { h[k] = hist[4 * lane + k]; mine += h[k]; }
+                const uint64_t incl = wave_inclusive_scan(mine, lane);
+                uint64_t run = below + incl - mine;
+                if (run < need && run + mine >= need) {
+                    int digit = 4 * lane;
+#pragma unroll
+                    for (int k = 0; k < 3; ++k)
+                        if (run + h[k] < need) { run += h[k]; ++digit; } else break;
+                    sel_prefix = (prefix << 8) | static_cast<uint64_t>(digit);
+                    sel_below = run;
+                }
+            }
+            __syncthreads();
+            prefix = sel_prefix;
+            below = sel_below;
+            __syncthreads();
+        }
+        threshold = prefix;
+    }
+
+    // widths, then offsets, in item order
+    uint64_t tie_carry = 0, byte_carry = 0;
+    const uint64_t rest = need - below;  // bits still to free among the moves priced exactly at the threshold
+    for (int64_t base = 0; base < a.M; base += kAllocBlock) {
+        const int64_t i = base + tid;
+        const bool live = i < a.M;
+        const float wi = live ? w[i] : 0.0f;
+        int64_t Di = live ? (a.D_items ? a.D_items[i] : a.D) : 0;
+        if (Di <= 0 || Di >= (int64_t(1) << 34)) Di = live ? 1 : 0;  // invalid input: stay memory-safe
+        int rung = loose ? 0 : steps, ties = 0;
+        if (search && live) {
+            rung = 0;
+            for (int r = 0; r < steps; ++r) {
+                const uint64_t key = price_bits(wi, Di, price[r]);
+                rung += key < threshold ? 1 : 0;
+                ties += key == threshold ? 1 : 0;
+            }
+        }
+        const uint64_t tie_bits = static_cast<uint64_t>(Di) * (width[rung] - width[rung + ties]);
+        uint64_t tie_total;
+        uint64_t before = tie_carry + block_exclusive_scan(tie_bits, wave_totals, tie_total);
+        tie_carry += tie_total;
+        for (; ties > 0 && before < rest; --ties, ++rung)
+            before += static_cast<uint64_t>(Di) * (width[rung] - width[rung + 1]);
+        const int b = width[rung];
+        const uint64_t groups = (static_cast<uint64_t>(Di) + kGroup - 1) / kGroup;
+        const uint64_t my_bytes = live ? groups * 32u * b : 0;
+        uint64_t byte_total;
+        const uint64_t off = byte_carry + block_exclusive_scan(my_bytes, wave_totals, byte_total);
+        byte_carry += byte_total;
+        if (live) {
+            bits[i] = static_cast<uint8_t>(b);
+            offsets[i] = off;
+        }
+    }
+    if (tid == 0) {
+        result[0] = static_cast<int64_t>(byte_carry);
+        result[1] = status;
     }
 }
 
@@ -969,6 +1189,19 @@ int launch_unpack_dequantize(const void* packed, uint64_t capacity, const void* 
     }
 #undef ACTQ_DEQ
     return check_launch("actq_unpack_dequantize");
+}
+
+int launch_allocate_bits(const float* w, const int64_t* D_items, int64_t D, int64_t M, int64_t budget_bits,
+                         const Ladder& lad, uint8_t* bits, uint64_t* offsets, int64_t* result, void* stream)
+{
+    AllocArgs a;
+    a.M = M;
+    a.D = D;
+    a.D_items = D_items;
+    a.budget_bits = budget_bits;
+    a.lad = lad;
+    allocate_bits_kernel<<<1, kAllocBlock, 0, static_cast<hipStream_t>(stream)>>>(w, a, bits, offsets, result);
+    return check_launch("actq_allocate_bits_device");
 }
 
 int launch_sample_sensitivity(const float* grange, int64_t N, int64_t ng, int32_t G, const float* grad2,

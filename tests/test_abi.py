@@ -27,8 +27,10 @@ def test_every_declared_symbol_is_exported():
 def test_packed_bytes_and_its_errors():
     off, total = B.packed_bytes(4, 1000, [1, 2, 4, 8])
     assert list(off) == [0, 128, 384, 896] and total == 1920
+    off, total = B.packed_bytes(5, 1000, [3, 5, 6, 7, 0 + 1])
+    assert list(off) == [0, 384, 1024, 1792, 2688] and total == 2816
     with pytest.raises(B.ActqError) as e:
-        B.packed_bytes(2, 512, [2, 3])
+        B.packed_bytes(2, 512, [2, 9])
     assert e.value.code == B.ACTQ_EINVAL and "bits[1]" in str(e.value)
     L = B.lib()
     bits = np.array([2], dtype=np.uint8)
@@ -95,9 +97,22 @@ def test_allocate_bits_errors():
         B.allocate_bits(w, np.array([256, 0, 256], dtype=np.int64), 10 ** 6)
     L = B.lib()
     out = np.zeros(3, dtype=np.uint8)
-    assert L.actq_allocate_bits(None, D.ctypes.data, 3, 100, out.ctypes.data) == B.ACTQ_EINVAL
-    assert L.actq_allocate_bits(w.ctypes.data, D.ctypes.data, 0, 100, out.ctypes.data) == B.ACTQ_EINVAL
-    assert L.actq_allocate_bits(w.ctypes.data, D.ctypes.data, 3, -1, out.ctypes.data) == B.ACTQ_EINVAL
+    P = B.ACTQ_WIDTHS_POW2
+    assert L.actq_allocate_bits(None, D.ctypes.data, 3, 100, P, out.ctypes.data) == B.ACTQ_EINVAL
+    assert L.actq_allocate_bits(w.ctypes.data, D.ctypes.data, 0, 100, P, out.ctypes.data) == B.ACTQ_EINVAL
+    assert L.actq_allocate_bits(w.ctypes.data, D.ctypes.data, 3, -1, P, out.ctypes.data) == B.ACTQ_EINVAL
+    for mask in (0, 1, 1 << 9, P | 1):
+        assert L.actq_allocate_bits(w.ctypes.data, D.ctypes.data, 3, 100, mask, out.ctypes.data) == B.ACTQ_EINVAL
+        assert "widths" in B.last_error()
+    # device allocator: w, D_items, D, M, G, budget, widths, bits, offsets, result, stream
+    ok = [FAKE, None, 4096, 8, 256, 1 << 16, P, FAKE, FAKE, FAKE, None]
+    for idx, bad in [(0, None), (7, None), (8, None), (9, None), (3, 0), (3, 1 << 31), (4, 128), (2, 0),
+                     (2, 1 << 34), (5, -1), (6, 0), (6, 1), (0, FAKE + 2), (8, FAKE + 4), (9, FAKE + 4),
+                     (1, FAKE + 4)]:
+        args = list(ok)
+        args[idx] = bad
+        assert L.actq_allocate_bits_device(*args) == B.ACTQ_EINVAL, (idx, bad)
+        assert B.last_error()
 
 
 def test_allocate_bits_matches_the_oracle_bit_for_bit():
@@ -114,12 +129,13 @@ def test_allocate_bits_matches_the_oracle_bit_for_bit():
             w[rng.integers(0, M, M // 4 + 1)] = 0.0        # free items
         D = rng.choice([256, 512, 1024, 25088, 802816], M).astype(np.int64)
         budget = int(rng.uniform(0.9, 8.5) * D.sum())
+        widths = [B.ACTQ_WIDTHS_POW2, B.ACTQ_WIDTHS_ALL, int(rng.integers(1, 256)) << 1][t % 3]
         try:
-            got, gc = B.allocate_bits(w, D, budget), 0
+            got, gc = B.allocate_bits(w, D, budget, widths), 0
         except B.ActqError as e:
             got, gc = e.bits, e.code
         try:
-            want, wc = oracle.allocate_bits(w, D, budget), 0
+            want, wc = oracle.allocate_bits(w, D, budget, widths), 0
         except oracle.OracleError as e:
             want, wc = e.bits, e.code
         assert gc == wc
@@ -140,3 +156,7 @@ def test_allocate_bits_full_sweep_size():
     assert np.array_equal(got, want)
     used = int((got.astype(np.int64) * D).sum())
     assert used <= budget and budget - used < 4 * D.max()
+    got = B.allocate_bits(w, D, budget, B.ACTQ_WIDTHS_ALL)
+    assert np.array_equal(got, oracle.allocate_bits(w, D, budget, oracle.WIDTHS_ALL))
+    used = int((got.astype(np.int64) * D).sum())
+    assert used <= budget and budget - used < D.max()

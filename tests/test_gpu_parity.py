@@ -74,12 +74,12 @@ def test_config1_tiny(noise_bits):
 def test_shapes_spanning_tiles_and_ragged_tails(N, D, noise_bits, dtype):
     rng = np.random.default_rng(N * 1000 + D)
     x = (rng.standard_normal((N, D)) * np.exp(rng.uniform(-3, 3, (N, 1)))).astype(dtype)
-    bits = rng.choice([1, 2, 4, 8], N).astype(np.uint8)
+    bits = rng.integers(1, 9, N).astype(np.uint8)
     _round_trip(x, bits, seed=0xDEADBEEFCAFE + D, tag=(7 << 32) | N, noise_bits=noise_bits,
                 out_dtypes=(torch.float32, torch.float16))
 
 
-@pytest.mark.parametrize("b", [1, 2, 4, 8])
+@pytest.mark.parametrize("b", [1, 2, 3, 4, 5, 6, 7, 8])
 def test_each_width_uniform_many_tiles(b):
     rng = np.random.default_rng(b)
     N, D = 6, 256 * 70
@@ -100,7 +100,7 @@ def test_degenerate_groups_negative_zero_and_subnormals():
     x[2, :256] = -np.abs(x[2, :256])
     x[2, 10] = -0.0                                     # max is -0.0
     x[3, :512] = np.float32(1e30) * rng.standard_normal(512).astype(np.float32)
-    for b in (1, 2, 4, 8):
+    for b in (1, 2, 3, 4, 7, 8):
         run = _round_trip(x, np.full(N, b, dtype=np.uint8), seed=5, tag=0, noise_bits=24)
         hd = run.header.cpu().numpy().reshape(N, -1, 2)
         assert hd[0, 0, 1] == 0.0 and hd[0, 1, 0] == 0.0 and not np.signbit(hd[0, 1, 0])
@@ -110,7 +110,7 @@ def test_degenerate_groups_negative_zero_and_subnormals():
 def test_grid_points_reconstruct_exactly_on_the_gpu():
     N, ng = 4, 8
     rng = np.random.default_rng(3)
-    for b in (1, 2, 4, 8):
+    for b in (1, 2, 3, 4, 5, 6, 7, 8):
         Bq = (1 << b) - 1
         k = rng.integers(0, Bq + 1, size=(N, ng, 256))
         k[:, :, 0], k[:, :, 255] = 0, Bq
@@ -129,8 +129,8 @@ def test_samples_with_invalid_width_or_range_are_skipped():
     bits = np.array([2, 2, 2, 2], dtype=np.uint8)
     run = GpuRun(x, bits)
     good_packed, good_header = run.quantize(7)
-    # corrupt the DEVICE copies only: width 3 for sample 1, an offset beyond the buffer for sample 2
-    run.bits[1] = 3
+    # corrupt the DEVICE copies only: width 9 for sample 1, an offset beyond the buffer for sample 2
+    run.bits[1] = 9
     run.offsets[2] = run.total - 64
     run.packed_buf.fill_(0xA5)
     run.header_buf.fill_(float("nan"))
@@ -197,7 +197,7 @@ def _round_trip_bf16(x, bits, seed, tag, noise_bits, out_dtypes=(torch.float32,)
 def test_bf16_header_mode(N, D, noise_bits, dtype):
     rng = np.random.default_rng(N * 77 + D)
     x = (rng.standard_normal((N, D)) * np.exp(rng.uniform(-3, 3, (N, 1))) + rng.standard_normal((N, 1))).astype(dtype)
-    bits = rng.choice([1, 2, 4, 8], N).astype(np.uint8)
+    bits = rng.integers(1, 9, N).astype(np.uint8)
     _round_trip_bf16(x, bits, seed=11 + D, tag=N, noise_bits=noise_bits, out_dtypes=(torch.float32, torch.float16))
 
 
@@ -263,6 +263,128 @@ def test_unaligned_device_arrays_are_rejected():
     assert e.value.code == B.ACTQ_EINVAL and "bits" in str(e.value)
     with pytest.raises(B.ActqError):
         B.quantize_pack(x.view(-1)[1:257 + 256 * 6].view(7, 256), bits[:7], offs[:7], packed, header[:14], 1)
+
+
+# ----------------------------------------------------------------------------- device allocator
+
+def _oracle_alloc(w, D, budget, widths):
+    try:
+        return oracle.allocate_bits(w, D, budget, widths), 0
+    except oracle.OracleError as e:
+        return e.bits, e.code
+
+
+def _device_alloc(w, D, budget, widths, uniform):
+    wd = torch.from_numpy(w).cuda()
+    Dd = int(D[0]) if uniform else torch.from_numpy(D).cuda()
+    M = w.size
+    bits = torch.full((M + 64,), 0xA5, dtype=torch.uint8, device="cuda:0")
+    offs = torch.full((M + 8,), -7, dtype=torch.int64, device="cuda:0")
+    res = torch.full((2 + 8,), -7, dtype=torch.int64, device="cuda:0")
+    B.allocate_bits_device(wd, Dd, budget, widths, bits[:M], offs[:M], res[:2])
+    torch.cuda.synchronize()
+    assert (bits[M:] == 0xA5).all() and (offs[M:] == -7).all() and (res[2:] == -7).all()
+    return bits[:M].cpu().numpy(), offs[:M].cpu().numpy(), int(res[0]), int(res[1])
+
+
+def _check_alloc(w, D, budget, widths, uniform):
+    want, code = _oracle_alloc(w, D, budget, widths)
+    got, offs, total, status = _device_alloc(w, D, budget, widths, uniform)
+    assert status == code
+    if not np.array_equal(got, want):
+        bad = np.flatnonzero(got != want)
+        raise AssertionError(f"{bad.size} widths differ, first at {bad[:6]}: {got[bad[:6]]} vs {want[bad[:6]]}")
+    per = ((D + 255) // 256) * 32 * want.astype(np.int64)
+    assert np.array_equal(offs, np.concatenate([[0], np.cumsum(per)[:-1]]))
+    assert total == int(per.sum())
+
+
+@pytest.mark.parametrize("case", range(40))
+def test_device_allocator_equals_the_greedy(case):
+    rng = np.random.default_rng(5000 + case)
+    M = int(rng.choice([1, 2, 7, 64, 128, 500, 1023, 1024, 1025, 3000, 9000]))
+    w = rng.lognormal(0, 2, M).astype(np.float32)
+    if case % 3 == 0:
+        w[rng.integers(0, M, M // 3 + 1)] = w[0]                  # equal prices: ties by index
+    if case % 4 == 0:
+        w[rng.integers(0, M, M // 4 + 1)] = 0.0                   # free items: all their steps tie at 0
+    if case % 7 == 0:
+        w[:] = np.float32(rng.choice([0.0, 1.0, 1e-38, 1e-45]))   # everything ties, subnormal prices
+    uniform = case % 2 == 0
+    D = (np.full(M, int(rng.choice([256, 1000, 802816]))) if uniform
+         else rng.choice([1, 255, 256, 257, 1024, 25088, 802816], M)).astype(np.int64)
+    widths = [B.ACTQ_WIDTHS_POW2, B.ACTQ_WIDTHS_ALL, int(rng.integers(1, 256)) << 1][case % 3]
+    lo = min(b for b in range(1, 9) if widths >> b & 1)
+    hi = max(b for b in range(1, 9) if widths >> b & 1)
+    budget = int(rng.uniform(lo - 0.1, hi + 0.3) * D.sum())
+    _check_alloc(w, D, max(budget, 0), widths, uniform)
+
+
+def test_device_allocator_edges():
+    M = 300
+    rng = np.random.default_rng(1)
+    w = rng.lognormal(0, 2, M).astype(np.float32)
+    D = np.full(M, 512, dtype=np.int64)
+    P = B.ACTQ_WIDTHS_POW2
+    _check_alloc(w, D, 8 * M * 512, P, True)            # exactly loose
+    _check_alloc(w, D, 8 * M * 512 - 1, P, True)        # one move
+    _check_alloc(w, D, M * 512, P, True)                # exactly everything at one bit
+    _check_alloc(w, D, M * 512 - 1, P, True)            # infeasible
+    _check_alloc(w, D, 0, P, False)
+    _check_alloc(w, D, 3 * M * 512, 1 << 3, True)       # a single allowed width
+    _check_alloc(w, D, 3 * M * 512 - 1, 1 << 3, True)
+    w[5] = -0.0                                           # negative zero is a valid, free item
+    _check_alloc(w, D, 2 * M * 512, B.ACTQ_WIDTHS_ALL, True)
+    for bad in (np.nan, np.inf, -1.0):
+        w2 = w.copy()
+        w2[17] = bad
+        got, offs, total, status = _device_alloc(w2, D, 2 * M * 512, P, True)
+        assert status == B.ACTQ_EINVAL and np.all(got == 1) and total == M * 2 * 32
+    D2 = D.copy()
+    D2[3] = 0
+    got, offs, total, status = _device_alloc(w, D2, 2 * M * 512, P, False)
+    assert status == B.ACTQ_EINVAL and np.all(got == 1)
+
+
+def test_device_allocator_feeds_the_quantizer_without_a_host_hop():
+    """stats -> sensitivity -> device allocator -> quantize -> dequantize on one stream, widths
+    and offsets never leaving the device; the result equals the oracle run on the same w."""
+    wl = synth.r50_stage1(N=16)
+    x_np = synth.make_input(wl).reshape(wl.N, wl.D)
+    x = torch.from_numpy(x_np).cuda()
+    gmin, gr = B.group_stats(x)
+    grad2 = torch.from_numpy(np.random.default_rng(4).lognormal(0, 2, wl.N).astype(np.float32)).cuda()
+    w = B.sample_sensitivity(gr, grad2)
+    budget = 3 * wl.N * wl.D
+    bits, offs, res = B.allocate_bits_device(w, wl.D, budget, B.ACTQ_WIDTHS_ALL)
+    ng = (wl.D + 255) // 256
+    packed = torch.full((wl.N * ng * 256 + 256,), 0xA5, dtype=torch.uint8, device="cuda:0")   # 8 bits would fit
+    header = torch.empty(wl.N * ng * 2, dtype=torch.float32, device="cuda:0")
+    out = torch.empty_like(x)
+    B.quantize_pack(x, bits, offs, packed[:-256], header, 77, 3, 16)
+    B.unpack_dequantize(packed[:-256], header, bits, offs, out)
+    torch.cuda.synchronize()
+    total, status = int(res[0]), int(res[1])
+    assert status == 0 and total * 8 <= budget
+    w_np, bits_np = w.cpu().numpy(), bits.cpu().numpy()
+    want_bits = oracle.allocate_bits(w_np, np.full(wl.N, wl.D, dtype=np.int64), budget, oracle.WIDTHS_ALL)
+    assert np.array_equal(bits_np, want_bits)
+    assert len(set(bits_np)) > 2
+    opacked, oheader, ooff = oracle.quantize_pack(x_np, want_bits, 77, 3, noise_bits=16)
+    assert opacked.size == total and np.array_equal(offs.cpu().numpy().view(np.uint64), ooff)
+    assert np.array_equal(packed[:total].cpu().numpy(), opacked)
+    assert (packed[total:] == 0xA5).all()
+    want = oracle.unpack_dequantize(opacked, oheader, want_bits, ooff, wl.N, wl.D)
+    assert np.array_equal(out.cpu().numpy().view(np.uint32), want.view(np.uint32))
+
+
+def test_device_allocator_full_sweep_size():
+    """M = 53 layers x 256 samples with the element counts of the ResNet-50 sweep."""
+    shapes = synth.resnet50_conv_input_shapes()
+    D = np.repeat(np.array([c * h * w for c, h, w in shapes], dtype=np.int64), 256)
+    w = synth.lognormal_sensitivities(D.size, seed=5)
+    for widths in (B.ACTQ_WIDTHS_POW2, B.ACTQ_WIDTHS_ALL):
+        _check_alloc(w, D, 2 * int(D.sum()), widths, False)
 
 
 # ----------------------------------------------------------------------------- full sizes
