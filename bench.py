@@ -2,7 +2,10 @@
 """Benchmark of the activation-compression hot path on one MI355X.
 
 One *step* is one pass of the whole path over one batch that is already resident in HBM:
-  group_stats  ->  allocate_bits (host, greedy)  ->  quantize_pack  ->  unpack_dequantize.
+  group_stats -> sample_sensitivity -> allocate_bits (greedy) -> quantize_pack -> unpack_dequantize.
+By default the allocator runs on the device (actq_allocate_bits_device) and the step never
+touches the host; --allocator host runs the host greedy between the kernels instead (widths
+and offsets then travel host-to-device in every step).
 The default workload is the ResNet-50 stage-1 post-ReLU activation, fp32 [128,256,56,56],
 G = 256, per-sample widths in {1,2,4,8} averaging 2.0 bits.  `value` is input-activation
 bytes per second through the whole step; the per-kernel figures and the HBM roofline of
@@ -36,6 +39,8 @@ def parse():
     p.add_argument("--noise-bits", type=int, default=16, choices=[24, 16])
     p.add_argument("--header", default="f32", choices=["f32", "bf16"],
                    help="group header format: (Z, R/B) binary32, 8 B/group, or (Z, R) bfloat16, 4 B/group")
+    p.add_argument("--allocator", default="device", choices=["device", "host"],
+                   help="where the greedy bit allocation of each step runs")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--profile-pass", action="store_true",
                    help="for rocprofv3 counter runs: a few launches of each kernel plus a plain device copy "
@@ -222,6 +227,14 @@ def main():
     offs_dev = torch.empty(N, dtype=torch.int64, device=dev)
     stream = torch.cuda.current_stream()
 
+    # Per-sample squared gradient norms (an input of the method, Sec. 4.2) chosen so that the
+    # sensitivities computed on the device, (G/6) * grad2_n * sum_g R_ng^2, land on w_host.
+    w_dev = torch.empty(N, dtype=torch.float32, device=dev)
+    result_dev = torch.zeros(2, dtype=torch.int64, device=dev)
+    B.group_stats(x, gmin, grange, G, stream=stream)
+    unit = B.sample_sensitivity(grange, None, G=G, stream=stream).cpu().numpy().astype(np.float64)
+    grad2 = torch.from_numpy(np.where(unit > 0, w_host / np.maximum(unit, 1e-300), 0.0).astype(np.float32)).to(dev)
+
     state = {}
 
     def step(events=None):
@@ -234,20 +247,35 @@ def main():
         mark("group_stats", 0)
         B.group_stats(x, gmin, grange, G, stream=stream)
         mark("group_stats", 1)
-        bits = B.allocate_bits(w_host, D_host, budget)
-        offsets, total = B.packed_bytes(N, D, bits, G)
-        bits_pin.numpy()[:] = bits
-        offs_pin.numpy()[:] = offsets.view(np.int64)
-        bits_dev.copy_(bits_pin, non_blocking=True)
-        offs_dev.copy_(offs_pin, non_blocking=True)
-        packed = packed_buf[:total]
+        if args.allocator == "device":
+            mark("sensitivity+allocate", 0)
+            B.sample_sensitivity(grange, grad2, w_dev, G, stream=stream)
+            B.allocate_bits_device(w_dev, D, budget, B.ACTQ_WIDTHS_POW2, bits_dev, offs_dev, result_dev, G, stream=stream)
+            mark("sensitivity+allocate", 1)
+            packed = packed_buf          # the total is known only on the device: hand over the whole buffer
+        else:
+            bits = B.allocate_bits(w_host, D_host, budget)
+            offsets, total = B.packed_bytes(N, D, bits, G)
+            bits_pin.numpy()[:] = bits
+            offs_pin.numpy()[:] = offsets.view(np.int64)
+            bits_dev.copy_(bits_pin, non_blocking=True)
+            offs_dev.copy_(offs_pin, non_blocking=True)
+            packed = packed_buf[:total]
+            state["bits"], state["total"] = bits, total
         mark("quantize_pack", 0)
         B.quantize_pack(x, bits_dev, offs_dev, packed, header, wl.philox_seed, wl.tag, args.noise_bits, G, stream=stream, hf=hf)
         mark("quantize_pack", 1)
         mark("unpack_dequantize", 0)
         B.unpack_dequantize(packed, header, bits_dev, offs_dev, out, G, stream=stream, hf=hf)
         mark("unpack_dequantize", 1)
-        state["bits"], state["total"] = bits, total
+
+    def read_back():
+        if args.allocator == "device":
+            torch.cuda.synchronize()
+            total, status = (int(v) for v in result_dev.cpu())
+            if status != 0:
+                raise RuntimeError(f"device allocator reported status {status}")
+            state["bits"], state["total"] = bits_dev.cpu().numpy(), total
 
     for _ in range(args.warmup):
         step()
@@ -257,10 +285,11 @@ def main():
         for _ in range(3):
             copy_dst.copy_(x)          # reads and writes N*D*elem_bytes each: the calibration kernel
             step()
-        torch.cuda.synchronize()
+        read_back()
         print(json.dumps({"profile_pass": True, "workload": wl.name, "copy_bytes_each_way": N * D * wl.elem_bytes,
                           "packed_bytes": state["total"], "header_bytes": N * ng * 8}))
         return
+    read_back()
     assert np.array_equal(state["bits"], wl.bits), "allocator did not return the workload's widths"
 
     events = {}
@@ -278,12 +307,16 @@ def main():
         stops = [e for when, e in marks if when == 1]
         kernel_ms[name] = float(np.mean([a.elapsed_time(b) for a, b in zip(starts, stops)]))
 
+    read_back()
+    assert np.array_equal(state["bits"], wl.bits)
     in_bytes = N * D * wl.elem_bytes
     alg = algorithmic_bytes(N, D, ng, wl.elem_bytes, state["total"], 4 if hf == B.ACTQ_HDR_BF16 else 8)
     per_kernel = {k: {"ms": kernel_ms[k], "input_GBps": in_bytes / kernel_ms[k] / 1e6,
                       "algorithmic_GBps": alg[k] / kernel_ms[k] / 1e6,
-                      "frac_of_hbm_peak": alg[k] / kernel_ms[k] / 1e6 / HBM_PEAK_GBS} for k in kernel_ms}
-    dominant = max(kernel_ms, key=kernel_ms.get)
+                      "frac_of_hbm_peak": alg[k] / kernel_ms[k] / 1e6 / HBM_PEAK_GBS} for k in alg}
+    if "sensitivity+allocate" in kernel_ms:   # two small launches that read N*ng ranges and N sensitivities
+        per_kernel["sensitivity+allocate"] = {"ms": kernel_ms["sensitivity+allocate"]}
+    dominant = max(alg, key=kernel_ms.get)
     achieved = alg[dominant] / kernel_ms[dominant] / 1e6
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
@@ -322,7 +355,10 @@ def main():
         "data": "synthetic",
         "config": {"workload": wl.name, "G": G, "mean_bits": float(wl.bits.astype(np.float64).mean()),
                    "noise_bits": args.noise_bits, "header": args.header,
-                   "step": "group_stats + allocate_bits(host) + quantize_pack + unpack_dequantize"},
+                   "allocator": args.allocator,
+                   "step": ("group_stats + sample_sensitivity + allocate_bits_device + quantize_pack + unpack_dequantize"
+                            if args.allocator == "device" else
+                            "group_stats + allocate_bits(host) + quantize_pack + unpack_dequantize")},
         "kernels": per_kernel,
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,

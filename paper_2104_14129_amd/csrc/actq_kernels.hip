@@ -841,10 +841,15 @@ __global__ __launch_bounds__(kBlock) void sample_sensitivity_kernel(const float*
 // patterns of the prices (non-negative doubles order like their bit patterns), eight passes
 // of eight bits, each a 256-bin histogram of freed bits; ties are then resolved with a
 // prefix sum in item order, and a second prefix sum turns the widths into byte offsets.
-// One workgroup does all of it out of LDS; prices are recomputed in every pass.
+// One workgroup does all of it out of LDS.  The prices of a thread's first item stay in
+// registers (all of them when M <= the workgroup size); those of further items are
+// recomputed in every pass.  Three histograms rotate so that a pass needs one barrier:
+// while pass p accumulates into one, every wavefront has already scanned the previous one
+// for itself and the third one is being cleared for the pass after.
 
 constexpr int kAllocBlock = 1024;
-constexpr int kAllocWaves = kAllocBlock / kWave;
+constexpr int kAllocWavesMax = kAllocBlock / kWave;
+constexpr int kMaxSteps = 7;
 
 struct AllocArgs {
     int64_t M;
@@ -854,26 +859,49 @@ struct AllocArgs {
     Ladder lad;
 };
 
+// DPP row_shr:K with zero fill: lane i of a row of 16 receives lane i - K, or 0 when there is none.
+template <int K>
+__device__ __forceinline__ uint64_t row_shift_right(uint64_t v)
+{
+    const uint32_t lo = dpp_u32<0x110 + K>(static_cast<uint32_t>(v));
+    const uint32_t hi = dpp_u32<0x110 + K>(static_cast<uint32_t>(v >> 32));
+    return (static_cast<uint64_t>(hi) << 32) | lo;
+}
+
+__device__ __forceinline__ uint64_t read_lane(uint64_t v, int src)
+{
+    const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(static_cast<uint32_t>(v)), src));
+    const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(static_cast<uint32_t>(v >> 32)), src));
+    return (static_cast<uint64_t>(hi) << 32) | lo;
+}
+
+// Inclusive prefix sum over the 64 lanes: four shift-and-add steps inside each row of 16,
+// then the totals of the preceding rows, read from the rows' last lanes.
 __device__ __forceinline__ uint64_t wave_inclusive_scan(uint64_t v, int lane)
 {
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        const uint64_t t = __shfl_up(v, d);
-        if (lane >= d) v += t;
-    }
-    return v;
+    v += row_shift_right<1>(v);
+    v += row_shift_right<2>(v);
+    v += row_shift_right<4>(v);
+    v += row_shift_right<8>(v);
+    const uint64_t t0 = read_lane(v, 15), t1 = read_lane(v, 31), t2 = read_lane(v, 47);
+    const int row = lane >> 4;
+    uint64_t before = 0;
+    before += row > 0 ? t0 : 0;
+    before += row > 1 ? t1 : 0;
+    before += row > 2 ? t2 : 0;
+    return v + before;
 }
 
 // Exclusive prefix sum over the workgroup in thread order; `total` receives the sum.
 __device__ __forceinline__ uint64_t block_exclusive_scan(uint64_t v, uint64_t* wave_totals, uint64_t& total)
 {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const int waves = blockDim.x >> 6;
     const uint64_t incl = wave_inclusive_scan(v, lane);
     if (lane == kWave - 1) wave_totals[wave] = incl;
     __syncthreads();
     uint64_t before = 0, all = 0;
-#pragma unroll
-    for (int k = 0; k < kAllocWaves; ++k) {
+    for (int k = 0; k < waves; ++k) {
         const uint64_t t = wave_totals[k];
         before += k < wave ? t : 0;
         all += t;
@@ -883,7 +911,7 @@ __device__ __forceinline__ uint64_t block_exclusive_scan(uint64_t v, uint64_t* w
     return before + incl - v;
 }
 
-// price of step r of item (w, D): two separately rounded double operations; -0.0 becomes +0.0
+// price of one step of item (w, D): two separately rounded double operations; -0.0 becomes +0.0
 __device__ __forceinline__ uint64_t price_bits(float w, int64_t D, double step_price)
 {
     const double key = (static_cast<double>(w) * step_price) / static_cast<double>(D) + 0.0;
@@ -895,28 +923,42 @@ __global__ __launch_bounds__(kAllocBlock) void allocate_bits_kernel(const float*
                                                                     uint64_t* __restrict__ offsets,
                                                                     int64_t* __restrict__ result)
 {
-    __shared__ uint64_t hist[256];
-    __shared__ uint64_t wave_totals[kAllocWaves];
-    __shared__ uint64_t sel_prefix, sel_below;
+    __shared__ uint64_t hist[3][256];
+    __shared__ uint64_t wave_totals[kAllocWavesMax];
     __shared__ int width[8];      // the ladder, in LDS because lanes index it independently
     __shared__ double price[8];
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int threads = blockDim.x;
     const int steps = a.lad.count - 1;
     if (tid < 8) {
         width[tid] = a.lad.width[tid];
         price[tid] = tid < 7 ? a.lad.price[tid] : 0.0;
     }
+    for (int k = tid; k < 3 * 256; k += threads) (&hist[0][0])[k] = 0;
     __syncthreads();
     const int widest = width[0], narrowest = width[steps];
 
-    // totals and validation
+    // totals and validation; the first item of every thread keeps its prices in registers
     uint64_t my_elems = 0;
     bool bad = false;
-    for (int64_t i = tid; i < a.M; i += kAllocBlock) {
+    uint64_t first_key[kMaxSteps];
+    uint64_t first_D = 0;
+#pragma unroll
+    for (int r = 0; r < kMaxSteps; ++r) first_key[r] = ~uint64_t(0);
+    for (int64_t i = tid; i < a.M; i += threads) {
         const float wi = w[i];
         const int64_t Di = a.D_items ? a.D_items[i] : a.D;
-        if (!(wi >= 0.0f) || !__builtin_isfinite(wi) || Di <= 0 || Di >= (int64_t(1) << 34)) bad = true;
-        else my_elems += static_cast<uint64_t>(Di);
+        if (!(wi >= 0.0f) || !__builtin_isfinite(wi) || Di <= 0 || Di >= (int64_t(1) << 34)) {
+            bad = true;
+        } else {
+            my_elems += static_cast<uint64_t>(Di);
+            if (i == tid) {
+                first_D = static_cast<uint64_t>(Di);
+#pragma unroll
+                for (int r = 0; r < kMaxSteps; ++r)
+                    if (r < steps) first_key[r] = price_bits(wi, Di, price[r]);
+            }
+        }
     }
     const bool invalid = __syncthreads_or(bad ? 1 : 0) != 0;
     uint64_t elems;
@@ -924,7 +966,7 @@ __global__ __launch_bounds__(kAllocBlock) void allocate_bits_kernel(const float*
     const uint64_t budget = static_cast<uint64_t>(a.budget_bits);
     const bool loose = !invalid && elems * widest <= budget;
     const bool infeasible = !invalid && elems * narrowest > budget;
-    int64_t status = invalid ? ACTQ_EINVAL : (infeasible ? ACTQ_EINFEASIBLE : ACTQ_OK);
+    const int64_t status = invalid ? ACTQ_EINVAL : (infeasible ? ACTQ_EINFEASIBLE : ACTQ_OK);
 
     uint64_t threshold = 0, below = 0, need = 0;
     const bool search = !invalid && !loose && !infeasible;
@@ -932,42 +974,52 @@ __global__ __launch_bounds__(kAllocBlock) void allocate_bits_kernel(const float*
         need = elems * widest - budget;  // bits that must be freed, > 0
         uint64_t prefix = 0;
         for (int pass = 7; pass >= 0; --pass) {
-            if (tid < 256) hist[tid] = 0;
-            __syncthreads();
-            for (int64_t i = tid; i < a.M; i += kAllocBlock) {
+            uint64_t* h = hist[pass % 3];
+            const int shift = 8 * pass;
+            // first item: cached prices
+            if (tid < a.M) {
+#pragma unroll
+                for (int r = 0; r < kMaxSteps; ++r) {
+                    if (r >= steps) continue;
+                    const uint64_t key = first_key[r];
+                    if (pass == 7 || (key >> (shift + 8)) == prefix)
+                        __hip_atomic_fetch_add(&h[(key >> shift) & 255u], first_D * (width[r] - width[r + 1]),
+                                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                }
+            }
+            for (int64_t i = tid + threads; i < a.M; i += threads) {
                 const float wi = w[i];
                 const int64_t Di = a.D_items ? a.D_items[i] : a.D;
                 for (int r = 0; r < steps; ++r) {
                     const uint64_t key = price_bits(wi, Di, price[r]);
-                    const bool in_range = pass == 7 || (key >> (8 * (pass + 1))) == prefix;
-                    if (in_range) {
-                        const uint64_t freed = static_cast<uint64_t>(Di) * (width[r] - width[r + 1]);
-                        __hip_atomic_fetch_add(&hist[(key >> (8 * pass)) & 255u], freed, __ATOMIC_RELAXED,
-                                               __HIP_MEMORY_SCOPE_WORKGROUP);
-                    }
+                    if (pass == 7 || (key >> (shift + 8)) == prefix)
+                        __hip_atomic_fetch_add(&h[(key >> shift) & 255u],
+                                               static_cast<uint64_t>(Di) * (width[r] - width[r + 1]),
+                                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                 }
             }
             __syncthreads();
-            if (tid < kWave) {
-                // the bin in which the running sum of freed bits first reaches `need`
-                uint64_t h[4], mine = 0;
+            // Every wavefront finds, for itself, the bin in which the running sum of freed bits
+            // first reaches `need`.  Exactly one lane holds it.
+            uint64_t hb[4], mine = 0;
 #pragma unroll
-                for (int k = 0; k < 4; ++k) { h[k] = hist[4 * lane + k]; mine += h[k]; }
-                const uint64_t incl = wave_inclusive_scan(mine, lane);
-                uint64_t run = below + incl - mine;
-                if (run < need && run + mine >= need) {
-                    int digit = 4 * lane;
+            for (int k = 0; k < 4; ++k) { hb[k] = h[4 * lane + k]; mine += hb[k]; }
+            const uint64_t incl = wave_inclusive_scan(mine, lane);
+            uint64_t run = below + incl - mine;
+            const bool winner = run < need && run + mine >= need;
+            int digit = 4 * lane;
 #pragma unroll
-                    for (int k = 0; k < 3; ++k)
-                        if (run + h[k] < need) { run += h[k]; ++digit; } else break;
-                    sel_prefix = (prefix << 8) | static_cast<uint64_t>(digit);
-                    sel_below = run;
-                }
-            }
-            __syncthreads();
-            prefix = sel_prefix;
-            below = sel_below;
-            __syncthreads();
+            for (int k = 0; k < 3; ++k)
+                if (winner && run + hb[k] < need) { run += hb[k]; ++digit; }
+                else break;
+            const uint64_t vote = __ballot(winner);
+            const int src = vote ? __builtin_ctzll(vote) : 0;
+            digit = __builtin_amdgcn_readlane(digit, src);
+            below = read_lane(run, src);
+            prefix = (prefix << 8) | static_cast<uint64_t>(digit);
+            // the histogram of the pass before this one is free again: clear it for the pass after the next
+            uint64_t* stale = hist[(pass + 1) % 3];
+            for (int k = tid; k < 256; k += threads) stale[k] = 0;
         }
         threshold = prefix;
     }
@@ -975,7 +1027,7 @@ __global__ __launch_bounds__(kAllocBlock) void allocate_bits_kernel(const float*
     // widths, then offsets, in item order
     uint64_t tie_carry = 0, byte_carry = 0;
     const uint64_t rest = need - below;  // bits still to free among the moves priced exactly at the threshold
-    for (int64_t base = 0; base < a.M; base += kAllocBlock) {
+    for (int64_t base = 0; base < a.M; base += threads) {
         const int64_t i = base + tid;
         const bool live = i < a.M;
         const float wi = live ? w[i] : 0.0f;
@@ -1200,7 +1252,10 @@ int launch_allocate_bits(const float* w, const int64_t* D_items, int64_t D, int6
     a.D_items = D_items;
     a.budget_bits = budget_bits;
     a.lad = lad;
-    allocate_bits_kernel<<<1, kAllocBlock, 0, static_cast<hipStream_t>(stream)>>>(w, a, bits, offsets, result);
+    // a workgroup no larger than the problem: barriers and scans get cheaper with fewer wavefronts
+    const int64_t lanes = (M + kWave - 1) / kWave * kWave;
+    const int block = static_cast<int>(lanes < kAllocBlock ? lanes : kAllocBlock);
+    allocate_bits_kernel<<<1, block, 0, static_cast<hipStream_t>(stream)>>>(w, a, bits, offsets, result);
     return check_launch("actq_allocate_bits_device");
 }
 
