@@ -41,6 +41,8 @@ def parse():
                    help="group header format: (Z, R/B) binary32, 8 B/group, or (Z, R) bfloat16, 4 B/group")
     p.add_argument("--allocator", default="device", choices=["device", "host"],
                    help="where the greedy bit allocation of each step runs")
+    p.add_argument("--uniform-bits", type=int, default=0, choices=range(0, 9), metavar="B",
+                   help="give every sample the width B (1..8) instead of the workload's mixed widths")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--profile-pass", action="store_true",
                    help="for rocprofv3 counter runs: a few launches of each kernel plus a plain device copy "
@@ -93,7 +95,13 @@ def sweep(args, torch, B, synth, dev):
     gmin = torch.empty(N * ngmax, dtype=torch.float32, device=dev)
     grange = torch.empty(N * ngmax, dtype=torch.float32, device=dev)
     header = torch.empty(N * ngmax * 2, dtype=torch.float32, device=dev)
-    packed_buf = torch.empty(N * Dmax, dtype=torch.uint8, device=dev)   # room for 8 bits everywhere
+    device_alloc = args.allocator == "device"
+    # host allocator: one layer's stream at a time, room for 8 bits everywhere; device allocator: the
+    # offsets run over all layers, so the buffer holds every layer's stream at once (budget / 8 bytes)
+    packed_buf = torch.empty(budget // 8 + 4096 if device_alloc else N * Dmax, dtype=torch.uint8, device=dev)
+    w_dev = torch.from_numpy(w_host).to(dev)
+    D_dev = torch.from_numpy(D_host).to(dev)
+    result_dev = torch.zeros(2, dtype=torch.int64, device=dev)
     out = torch.empty(N * Dmax, dtype=torch.float32, device=dev)
     bits_pin = torch.empty(N * L, dtype=torch.uint8, pin_memory=True)
     offs_pin = torch.empty(N * L, dtype=torch.int64, pin_memory=True)
@@ -116,15 +124,19 @@ def sweep(args, torch, B, synth, dev):
             for _ in range(args.steps)]
 
     def step(ev=None):
-        bits = B.allocate_bits(w_host, D_host, budget)
-        totals = []
-        for l, D in enumerate(Dl):
-            offsets, total = B.packed_bytes(N, D, bits[l * N:(l + 1) * N], G)
-            offs_pin.numpy()[l * N:(l + 1) * N] = offsets.view(np.int64)
-            totals.append(total)
-        bits_pin.numpy()[:] = bits
-        bits_dev.copy_(bits_pin, non_blocking=True)
-        offs_dev.copy_(offs_pin, non_blocking=True)
+        if device_alloc:
+            B.allocate_bits_device(w_dev, D_dev, budget, B.ACTQ_WIDTHS_POW2, bits_dev, offs_dev, result_dev, G, stream=stream)
+        else:
+            bits = B.allocate_bits(w_host, D_host, budget)
+            totals = []
+            for l, D in enumerate(Dl):
+                offsets, total = B.packed_bytes(N, D, bits[l * N:(l + 1) * N], G)
+                offs_pin.numpy()[l * N:(l + 1) * N] = offsets.view(np.int64)
+                totals.append(total)
+            bits_pin.numpy()[:] = bits
+            bits_dev.copy_(bits_pin, non_blocking=True)
+            offs_dev.copy_(offs_pin, non_blocking=True)
+            state["bits"], state["totals"] = bits, totals
         gm, gr, hd, pk, o = gmin.data_ptr(), grange.data_ptr(), header.data_ptr(), packed_buf.data_ptr(), out.data_ptr()
         for l, (xp, D, bp, op) in enumerate(layer_args):
             if ev is not None:
@@ -142,7 +154,6 @@ def sweep(args, torch, B, synth, dev):
                 ev[3 * l + 2][1].record(stream)
             if rc:
                 raise RuntimeError(B.last_error())
-        state["bits"], state["totals"] = bits, totals
 
     for _ in range(args.warmup):
         step()
@@ -157,6 +168,11 @@ def sweep(args, torch, B, synth, dev):
         for j, (a, b) in enumerate(ev):
             kernel_ms[names[j % 3]] += a.elapsed_time(b) / args.steps
 
+    if device_alloc:
+        total, status = (int(v) for v in result_dev.cpu())
+        if status != 0:
+            raise RuntimeError(f"device allocator reported status {status}")
+        state["bits"], state["totals"] = bits_dev.cpu().numpy(), [total]
     in_bytes = 4 * N * sum(Dl)
     hdr = sum(N * (D // G) * 8 for D in Dl)
     code = sum(state["totals"])
@@ -174,7 +190,8 @@ def sweep(args, torch, B, synth, dev):
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "r50_sweep_f32_53x[256,C,H,W]", "G": G, "mean_bits": mean_bits,
                    "noise_bits": args.noise_bits, "launches_per_step": 3 * L,
-                   "step": "allocate_bits(host, M=13568) + per layer: group_stats + quantize_pack + unpack_dequantize"},
+                   "allocator": args.allocator,
+                   "step": f"allocate_bits({args.allocator}, M=13568) + per layer: group_stats + quantize_pack + unpack_dequantize"},
         "kernels": per_kernel,
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
@@ -210,7 +227,13 @@ def main():
     x = torch.from_numpy(x_np).to(dev)
 
     # sensitivities whose greedy allocation at a 2.0-bit budget is the workload's width multiset
-    w_host = synth.tiered_sensitivities(wl.bits, seed=7)
+    widths = B.ACTQ_WIDTHS_POW2
+    if args.uniform_bits:
+        wl.bits = np.full(N, args.uniform_bits, dtype=np.uint8)
+        widths = 1 << args.uniform_bits           # the only allowed width
+        w_host = np.ones(N, dtype=np.float32)
+    else:
+        w_host = synth.tiered_sensitivities(wl.bits, seed=7)
     D_host = np.full(N, D, dtype=np.int64)
     budget = int(round(float(wl.bits.astype(np.float64).mean()) * N * D))
 
@@ -250,11 +273,11 @@ def main():
         if args.allocator == "device":
             mark("sensitivity+allocate", 0)
             B.sample_sensitivity(grange, grad2, w_dev, G, stream=stream)
-            B.allocate_bits_device(w_dev, D, budget, B.ACTQ_WIDTHS_POW2, bits_dev, offs_dev, result_dev, G, stream=stream)
+            B.allocate_bits_device(w_dev, D, budget, widths, bits_dev, offs_dev, result_dev, G, stream=stream)
             mark("sensitivity+allocate", 1)
             packed = packed_buf          # the total is known only on the device: hand over the whole buffer
         else:
-            bits = B.allocate_bits(w_host, D_host, budget)
+            bits = B.allocate_bits(w_host, D_host, budget, widths)
             offsets, total = B.packed_bytes(N, D, bits, G)
             bits_pin.numpy()[:] = bits
             offs_pin.numpy()[:] = offsets.view(np.int64)
@@ -320,7 +343,7 @@ def main():
     achieved = alg[dominant] / kernel_ms[dominant] / 1e6
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                "traffic": measured_traffic(wl.name, args.noise_bits, dominant),
+                "traffic": None if args.uniform_bits else measured_traffic(wl.name, args.noise_bits, dominant),
                 "algorithmic_bytes_per_launch": alg[dominant], "avg_launch_ms": kernel_ms[dominant]}
 
     cpu_baseline = None

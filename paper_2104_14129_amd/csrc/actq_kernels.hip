@@ -661,7 +661,7 @@ template <typename T, bool VEC, int B, bool BF16>
 __device__ __forceinline__ void dequantize_tile(const uint8_t* __restrict__ src_sample,
                                                 const void* __restrict__ header, T* os,
                                                 int64_t D, uint32_t n, uint32_t g0, int groups, uint32_t ng,
-                                                int lane)
+                                                int lane, uint32_t* stage)
 {
     // a lane's four codes are the 4*B bits that start at bit 4*B*lane of the group: inside one
     // 32-bit word when B divides 8, possibly across two words otherwise
@@ -671,15 +671,42 @@ __device__ __forceinline__ void dequantize_tile(const uint8_t* __restrict__ src_
     const uint32_t shift = static_cast<uint32_t>(lane) * (4u * B) & 31u;
     uint32_t word[kTileGroups], next[kTileGroups];
     f32x2 hd[kTileGroups];
+    if (!kAligned) {
+        // The tile's bit stream (groups * 32 * B contiguous bytes) comes in with coalesced word
+        // loads and is handed over through the wavefront's LDS slice; every lane then picks the
+        // two words that hold its bits.
+        const uint32_t* tile_src = reinterpret_cast<const uint32_t*>(src_sample + static_cast<uint64_t>(g0) * (32 * B));
+        const int words = groups * 8 * B;
+        constexpr int kLoads = (32 * B + 63) / 64;
+        uint32_t in[kLoads];
 #pragma unroll
-    for (int u = 0; u < kTileGroups; ++u) {
-        if (u >= groups) continue;
-        const uint32_t g = g0 + u;
-        const uint32_t* src = reinterpret_cast<const uint32_t*>(src_sample + static_cast<uint64_t>(g) * (32 * B));
-        word[u] = __builtin_nontemporal_load(src + first_word);
-        if (!kAligned)  // the last lane's bits end with the group: stay inside it
-            next[u] = __builtin_nontemporal_load(src + min(first_word + 1u, static_cast<uint32_t>(8 * B - 1)));
-        hd[u] = load_header<BF16>(header, static_cast<int64_t>(n) * ng + g, static_cast<float>(code_mask));
+        for (int j = 0; j < kLoads; ++j) {
+            const int idx = min(j * 64 + lane, words - 1);  // clamped: lanes past the end re-read the last word
+            in[j] = __builtin_nontemporal_load(tile_src + idx);
+        }
+#pragma unroll
+        for (int u = 0; u < kTileGroups; ++u)
+            if (u < groups)
+                hd[u] = load_header<BF16>(header, static_cast<int64_t>(n) * ng + g0 + u, static_cast<float>(code_mask));
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j) stage[j * 64 + lane] = in[j];  // at most 256 words
+        wave_lds_handover();
+#pragma unroll
+        for (int u = 0; u < kTileGroups; ++u) {
+            // past the tile's last word the neighbour is never used: those lanes' bits end with the word
+            word[u] = stage[u * 8 * B + first_word];
+            next[u] = stage[u * 8 * B + first_word + 1];
+        }
+        wave_lds_handover();  // the slice is reused by the next tile of this wavefront
+    } else {
+#pragma unroll
+        for (int u = 0; u < kTileGroups; ++u) {
+            if (u >= groups) continue;
+            const uint32_t g = g0 + u;
+            const uint32_t* src = reinterpret_cast<const uint32_t*>(src_sample + static_cast<uint64_t>(g) * (32 * B));
+            word[u] = __builtin_nontemporal_load(src + first_word);
+            hd[u] = load_header<BF16>(header, static_cast<int64_t>(n) * ng + g, static_cast<float>(code_mask));
+        }
     }
 #pragma unroll
     for (int u = 0; u < kTileGroups; ++u) {
@@ -761,12 +788,13 @@ __device__ __forceinline__ void dequantize_tile_f16(const uint8_t* __restrict__ 
 template <typename T, bool VEC, int B, bool BF16>
 __device__ __forceinline__ void dequantize_any(const uint8_t* __restrict__ src_sample,
                                                const void* __restrict__ header, T* os,
-                                               int64_t D, uint32_t n, uint32_t g0, int groups, uint32_t ng, int lane)
+                                               int64_t D, uint32_t n, uint32_t g0, int groups, uint32_t ng, int lane,
+                                               uint32_t* stage)
 {
     if constexpr (sizeof(T) == 2 && (8 % B) == 0)
         dequantize_tile_f16<VEC, B, BF16>(src_sample, header, os, D, n, g0, groups, ng, lane);
     else
-        dequantize_tile<T, VEC, B, BF16>(src_sample, header, os, D, n, g0, groups, ng, lane);
+        dequantize_tile<T, VEC, B, BF16>(src_sample, header, os, D, n, g0, groups, ng, lane, stage);
 }
 
 template <typename T, bool VEC, bool BF16>
@@ -775,7 +803,9 @@ __global__ __launch_bounds__(kBlock) void unpack_dequantize_kernel(
     const uint8_t* __restrict__ bits, const uint64_t* __restrict__ offsets, Geometry geo,
     T* __restrict__ out)
 {
+    __shared__ uint32_t stage_all[kWavesPerBlock][256];  // 1 KiB per wavefront, private to it (odd widths)
     const int lane = threadIdx.x & (kWave - 1);
+    uint32_t* stage = stage_all[threadIdx.x >> 6];
     uint32_t n, tile, tile_end;
     if (!wave_work(geo, n, tile, tile_end)) return;
     T* os = out + static_cast<int64_t>(n) * geo.D;
@@ -788,14 +818,14 @@ __global__ __launch_bounds__(kBlock) void unpack_dequantize_kernel(
         const uint32_t g0 = tile * kTileGroups;
         const int groups = static_cast<int>(min(static_cast<uint32_t>(kTileGroups), geo.ng - g0));
         switch (b) {
-            case 1: dequantize_any<T, VEC, 1, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
-            case 2: dequantize_any<T, VEC, 2, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
-            case 3: dequantize_any<T, VEC, 3, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
-            case 4: dequantize_any<T, VEC, 4, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
-            case 5: dequantize_any<T, VEC, 5, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
-            case 6: dequantize_any<T, VEC, 6, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
-            case 7: dequantize_any<T, VEC, 7, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
-            case 8: dequantize_any<T, VEC, 8, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane); break;
+            case 1: dequantize_any<T, VEC, 1, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
+            case 2: dequantize_any<T, VEC, 2, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
+            case 3: dequantize_any<T, VEC, 3, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
+            case 4: dequantize_any<T, VEC, 4, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
+            case 5: dequantize_any<T, VEC, 5, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
+            case 6: dequantize_any<T, VEC, 6, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
+            case 7: dequantize_any<T, VEC, 7, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
+            case 8: dequantize_any<T, VEC, 8, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
             default: return;
         }
     }
