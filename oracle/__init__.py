@@ -84,6 +84,17 @@ def lib() -> ctypes.CDLL:
         L.orc_allocate_bits.argtypes = [vp, vp, i64, i64, vp]
         L.orc_allocate_bits_ladder.restype = c.c_int
         L.orc_allocate_bits_ladder.argtypes = [vp, vp, i64, i64, c.c_uint32, vp]
+        i32 = c.c_int32
+        L.orc_relu_forward.restype = c.c_int
+        L.orc_relu_forward.argtypes = [vp, c.c_int, i64, vp, vp]
+        L.orc_relu_backward.restype = c.c_int
+        L.orc_relu_backward.argtypes = [vp, vp, c.c_int, i64, vp]
+        L.orc_pool2d_output_size.restype = c.c_int
+        L.orc_pool2d_output_size.argtypes = [i32] * 10 + [vp, vp]
+        L.orc_maxpool2d_forward.restype = c.c_int
+        L.orc_maxpool2d_forward.argtypes = [vp, c.c_int, i64] + [i32] * 10 + [vp, vp]
+        L.orc_maxpool2d_backward.restype = c.c_int
+        L.orc_maxpool2d_backward.argtypes = [vp, vp, c.c_int, i64] + [i32] * 10 + [vp]
         L.orc_objective.restype = c.c_double
         L.orc_objective.argtypes = [vp, vp, i64]
         _lib = L
@@ -318,3 +329,64 @@ def objective(w, bits) -> float:
     w = np.ascontiguousarray(w, dtype=np.float32)
     bits = np.ascontiguousarray(bits, dtype=np.uint8)
     return float(lib().orc_objective(_p(w), _p(bits), w.shape[0]))
+
+
+# ----------------------------------------------------------------------------- exact contexts
+
+def relu_forward(x: np.ndarray):
+    """y = x where x > 0 else +0, and the 1-bit context (uint8, ceil(n/256)*32 bytes)."""
+    x = np.ascontiguousarray(x)
+    y = np.empty_like(x)
+    mask = np.empty((x.size + 255) // 256 * 32, dtype=np.uint8)
+    rc = lib().orc_relu_forward(_p(x), _dtype_code(x), x.size, _p(y), _p(mask))
+    if rc != OK:
+        raise OracleError(rc, "relu_forward")
+    return y, mask
+
+
+def relu_backward(mask: np.ndarray, grad_y: np.ndarray) -> np.ndarray:
+    grad_y = np.ascontiguousarray(grad_y)
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    gx = np.empty_like(grad_y)
+    rc = lib().orc_relu_backward(_p(mask), _p(grad_y), _dtype_code(grad_y), grad_y.size, _p(gx))
+    if rc != OK:
+        raise OracleError(rc, "relu_backward")
+    return gx
+
+
+def pool2d_output_size(H, W, kernel, stride, padding=(0, 0), dilation=(1, 1)):
+    import ctypes as c
+    oh, ow = c.c_int32(), c.c_int32()
+    rc = lib().orc_pool2d_output_size(H, W, *kernel, *stride, *padding, *dilation, c.addressof(oh), c.addressof(ow))
+    if rc != OK:
+        raise OracleError(rc, "pool2d_output_size")
+    return oh.value, ow.value
+
+
+def maxpool2d_forward(x: np.ndarray, kernel, stride, padding=(0, 0), dilation=(1, 1)):
+    """x [..., H, W] -> (y [..., OH, OW], argmax uint8 [..., OH, OW] = position inside the window)."""
+    x = np.ascontiguousarray(x)
+    H, W = x.shape[-2:]
+    planes = x.size // (H * W)
+    OH, OW = pool2d_output_size(H, W, kernel, stride, padding, dilation)
+    y = np.empty(x.shape[:-2] + (OH, OW), dtype=x.dtype)
+    arg = np.empty(y.shape, dtype=np.uint8)
+    rc = lib().orc_maxpool2d_forward(_p(x), _dtype_code(x), planes, H, W, *kernel, *stride, *padding, *dilation,
+                                     _p(y), _p(arg))
+    if rc != OK:
+        raise OracleError(rc, "maxpool2d_forward")
+    return y, arg
+
+
+def maxpool2d_backward(argmax: np.ndarray, grad_y: np.ndarray, H: int, W: int, kernel, stride,
+                       padding=(0, 0), dilation=(1, 1)) -> np.ndarray:
+    grad_y = np.ascontiguousarray(grad_y)
+    argmax = np.ascontiguousarray(argmax, dtype=np.uint8)
+    OH, OW = grad_y.shape[-2:]
+    planes = grad_y.size // (OH * OW)
+    gx = np.empty(grad_y.shape[:-2] + (H, W), dtype=grad_y.dtype)
+    rc = lib().orc_maxpool2d_backward(_p(argmax), _p(grad_y), _dtype_code(grad_y), planes, H, W, *kernel, *stride,
+                                      *padding, *dilation, _p(gx))
+    if rc != OK:
+        raise OracleError(rc, "maxpool2d_backward")
+    return gx

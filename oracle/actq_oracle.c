@@ -4,8 +4,10 @@
  * A plain, slow CPU statement of what the activation-compression hot path of
  * ActNN (arXiv 2104.14129) computes: per-group min/range, stochastic rounding
  * to b-bit codes, a linear bit stream, dequantization, and the greedy bit
- * allocator.  It follows the paper step by step (Sec. 4.1 for the quantizer,
- * Sec. 4.2 Prob. (9) and Sec. 4.3 for the allocator) and shares no code,
+ * allocator, plus the exact contexts of ReLU and max-pooling layers.  It follows
+ * the paper step by step (Sec. 4.1 for the quantizer, Sec. 4.2 Prob. (9) and
+ * Sec. 4.3 for the allocator, the appendix sections "Activation Layers" and
+ * "Pooling Layers" for the exact contexts) and shares no code,
  * header, table or constant with the GPU library.  Only tests, the smoke check
  * and the cpu_baseline leg of the benchmark may call it.
  *
@@ -22,6 +24,7 @@
  */
 #include <math.h>
 #include <stdint.h>
+#include <stdlib.h>
 #include <string.h>
 
 #define ORC_OK 0
@@ -569,4 +572,130 @@ double orc_objective(const float* w, const uint8_t* bits, int64_t M)
         acc += (double)w[i] / (B * B);
     }
     return acc;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Appendix, "Activation Layers": a ReLU layer's context is one bit per         */
+/* element, f'(x) = [x > 0], with no approximation.  The bits form the same     */
+/* LSB-first stream as 1-bit codes and are padded with zeros to a whole number  */
+/* of 256-bit groups.  Forward: y = x where x > 0, +0 elsewhere (so NaN and     */
+/* -0.0 give +0).  Backward: grad_x = grad_y where the bit is set, +0 elsewhere. */
+
+static void store_elem(void* y, int dtype, int64_t idx, float v)
+{
+    if (dtype == 0)
+        ((float*)y)[idx] = v;
+    else
+        ((uint16_t*)y)[idx] = orc_float_to_half(v);
+}
+
+int orc_relu_forward(const void* x, int dtype, int64_t n, void* y, uint8_t* mask)
+{
+    if (!x || !y || !mask || n <= 0 || (dtype != 0 && dtype != 1)) return ORC_EINVAL;
+    memset(mask, 0, (size_t)((n + 255) / 256) * 32);
+    for (int64_t i = 0; i < n; ++i) {
+        float v = load_elem(x, dtype, i);
+        int positive = v > 0.0f;
+        store_elem(y, dtype, i, positive ? v : 0.0f);
+        if (positive) put_code(mask, i, 1, 1u);
+    }
+    return ORC_OK;
+}
+
+int orc_relu_backward(const uint8_t* mask, const void* grad_y, int dtype, int64_t n, void* grad_x)
+{
+    if (!mask || !grad_y || !grad_x || n <= 0 || (dtype != 0 && dtype != 1)) return ORC_EINVAL;
+    for (int64_t i = 0; i < n; ++i) {
+        float g = load_elem(grad_y, dtype, i);
+        store_elem(grad_x, dtype, i, get_code(mask, i, 1) ? g : 0.0f);
+    }
+    return ORC_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Appendix, "Max Pooling": y = max over the window; the context is, for every  */
+/* output location, the position k of the maximum inside the window,            */
+/* 0 <= k < K = kh*kw, stored in 8 bits.  k counts window positions row by row  */
+/* (k = a*kw + b for window row a, column b); padded positions never win; among */
+/* equal values the first in that order wins.  The gradient of an input         */
+/* location is the sum of the output gradients whose stored position points at  */
+/* it; outputs are visited row by row and added in binary32.                    */
+
+int orc_pool2d_output_size(int32_t H, int32_t W, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
+                           int32_t ph, int32_t pw, int32_t dh, int32_t dw, int32_t* OH, int32_t* OW)
+{
+    if (H <= 0 || W <= 0 || kh <= 0 || kw <= 0 || sh <= 0 || sw <= 0 || ph < 0 || pw < 0 ||
+        dh <= 0 || dw <= 0 || kh * kw > 256 || 2 * ph > kh || 2 * pw > kw)
+        return ORC_EINVAL;
+    int64_t eh = (int64_t)dh * (kh - 1) + 1, ew = (int64_t)dw * (kw - 1) + 1;
+    if (H + 2 * ph < eh || W + 2 * pw < ew) return ORC_EINVAL;
+    *OH = (int32_t)((H + 2 * ph - eh) / sh + 1);
+    *OW = (int32_t)((W + 2 * pw - ew) / sw + 1);
+    return ORC_OK;
+}
+
+int orc_maxpool2d_forward(const void* x, int dtype, int64_t planes, int32_t H, int32_t W,
+                          int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
+                          int32_t dh, int32_t dw, void* y, uint8_t* argmax)
+{
+    int32_t OH, OW;
+    if (!x || !y || !argmax || planes <= 0 || (dtype != 0 && dtype != 1)) return ORC_EINVAL;
+    if (orc_pool2d_output_size(H, W, kh, kw, sh, sw, ph, pw, dh, dw, &OH, &OW)) return ORC_EINVAL;
+#pragma omp parallel for schedule(static)
+    for (int64_t p = 0; p < planes; ++p)
+        for (int32_t i = 0; i < OH; ++i)
+            for (int32_t j = 0; j < OW; ++j) {
+                int have = 0, best_k = 0;
+                float best = 0.0f;
+                for (int32_t a = 0; a < kh; ++a)
+                    for (int32_t b = 0; b < kw; ++b) {
+                        int64_t r = (int64_t)sh * i - ph + (int64_t)dh * a;
+                        int64_t c = (int64_t)sw * j - pw + (int64_t)dw * b;
+                        if (r < 0 || r >= H || c < 0 || c >= W) continue;
+                        float v = load_elem(x, dtype, (p * H + r) * W + c);
+                        if (!have || v > best) {
+                            have = 1;
+                            best = v;
+                            best_k = a * kw + b;
+                        }
+                    }
+                int64_t o = (p * OH + i) * OW + j;
+                store_elem(y, dtype, o, best);
+                argmax[o] = (uint8_t)best_k;
+            }
+    return ORC_OK;
+}
+
+int orc_maxpool2d_backward(const uint8_t* argmax, const void* grad_y, int dtype, int64_t planes,
+                           int32_t H, int32_t W, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
+                           int32_t ph, int32_t pw, int32_t dh, int32_t dw, void* grad_x)
+{
+    int32_t OH, OW;
+    if (!argmax || !grad_y || !grad_x || planes <= 0 || (dtype != 0 && dtype != 1)) return ORC_EINVAL;
+    if (orc_pool2d_output_size(H, W, kh, kw, sh, sw, ph, pw, dh, dw, &OH, &OW)) return ORC_EINVAL;
+    int bad = 0;
+#pragma omp parallel for schedule(static)
+    for (int64_t p = 0; p < planes; ++p) {
+        float* acc = (float*)malloc(sizeof(float) * (size_t)H * (size_t)W); /* binary32 accumulators of one plane */
+        if (!acc) {
+            bad = 1;
+            continue;
+        }
+        for (int64_t t = 0; t < (int64_t)H * W; ++t) acc[t] = 0.0f;
+        for (int32_t i = 0; i < OH; ++i)
+            for (int32_t j = 0; j < OW; ++j) {
+                int64_t o = (p * OH + i) * OW + j;
+                int k = argmax[o];
+                int64_t r = (int64_t)sh * i - ph + (int64_t)dh * (k / kw);
+                int64_t c = (int64_t)sw * j - pw + (int64_t)dw * (k % kw);
+                if (k >= kh * kw || r < 0 || r >= H || c < 0 || c >= W) {
+                    bad = 1; /* a position the forward pass cannot have produced */
+                    continue;
+                }
+                acc[r * W + c] += load_elem(grad_y, dtype, o);
+            }
+        for (int64_t t = 0; t < (int64_t)H * W; ++t) store_elem(grad_x, dtype, p * H * W + t, acc[t]);
+        free(acc);
+    }
+    return bad ? ORC_EINVAL : ORC_OK;
 }
