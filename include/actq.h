@@ -227,6 +227,57 @@ int actq_allocate_bits_device(const float* w, const int64_t* D_items, int64_t D,
                               int32_t G, int64_t budget_bits, uint32_t widths,
                               uint8_t* bits, uint64_t* offsets, int64_t* result, void* stream);
 
+/*
+ * Exact context of a ReLU layer (appendix, "Activation Layers"): one bit per
+ * element, f'(x) = [x > 0], nothing approximated.
+ *
+ * Forward: y[i] = x[i] where x[i] > 0, +0 elsewhere; bit i of the stream (bit
+ * i mod 8 of byte floor(i / 8), the layout of 1-bit codes) is [x[i] > 0].  The
+ * stream is padded with zero bits to a whole number of 256-bit groups:
+ * actq_relu_mask_bytes(n) = ceil(n / 256) * 32 bytes.
+ * Backward: grad_x[i] = grad_y[i] where bit i is set, +0 elsewhere.
+ *
+ * x, y           device : n elements of dtype dt; y may be the same buffer as x
+ * grad_y, grad_x device : likewise; grad_x may be the same buffer as grad_y
+ * mask           device : actq_relu_mask_bytes(n) bytes
+ * All three 16-byte aligned; n in [1, 2^40).
+ */
+int actq_relu_mask_bytes(int64_t n, uint64_t* bytes_host);
+int actq_relu_forward(const void* x, actq_dtype dt, int64_t n, void* y, uint8_t* mask, void* stream);
+int actq_relu_backward(const uint8_t* mask, const void* grad_y, actq_dtype dt, int64_t n,
+                       void* grad_x, void* stream);
+
+/*
+ * Exact context of a max-pooling layer (appendix, "Pooling Layers", "Max
+ * Pooling"): for every output location the position k of the maximum inside
+ * its window, 0 <= k < kh*kw <= 256, in 8 bits.
+ *
+ * The tensors are `planes` (= batch * channels) row-major images, H x W in,
+ * OH x OW out with OH = floor((H + 2*ph - dh*(kh-1) - 1) / sh) + 1 (likewise
+ * OW), as returned by actq_pool2d_output_size.  Window position k = a*kw + b
+ * is input row sh*i - ph + dh*a, column sw*j - pw + dw*b; padded positions
+ * never win; among equal values the smallest k wins.
+ * Backward: grad_x of an input location is the sum, in binary32 and in
+ * ascending (i, j), of the grad_y whose stored position points at it; a stored
+ * position that points outside the image is ignored.
+ *
+ * x, grad_x  device : planes*H*W elements;  y, grad_y : planes*OH*OW elements
+ * argmax     device : planes*OH*OW bytes
+ * Errors: ACTQ_EINVAL on a window of more than 256 positions, padding above
+ * half the window size, a window larger than the padded image, non-positive
+ * sizes, strides or dilations, planes*H*W >= 2^40, or misaligned tensors.
+ */
+int actq_pool2d_output_size(int32_t H, int32_t W, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
+                            int32_t ph, int32_t pw, int32_t dh, int32_t dw,
+                            int32_t* OH_host, int32_t* OW_host);
+int actq_maxpool2d_forward(const void* x, actq_dtype dt, int64_t planes, int32_t H, int32_t W,
+                           int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
+                           int32_t dh, int32_t dw, void* y, uint8_t* argmax, void* stream);
+int actq_maxpool2d_backward(const uint8_t* argmax, const void* grad_y, actq_dtype dt, int64_t planes,
+                            int32_t H, int32_t W, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
+                            int32_t ph, int32_t pw, int32_t dh, int32_t dw, void* grad_x,
+                            void* stream);
+
 #ifdef __cplusplus
 }
 #endif

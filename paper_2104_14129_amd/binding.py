@@ -24,7 +24,8 @@ ACTQ_WIDTHS_POW2, ACTQ_WIDTHS_ALL = 0x116, 0x1FE  # allowed-width sets of the al
 
 EXPORTS = ("actq_version", "actq_last_error", "actq_packed_bytes", "actq_header_bytes", "actq_group_stats",
            "actq_quantize_pack", "actq_unpack_dequantize", "actq_sample_sensitivity", "actq_allocate_bits",
-           "actq_allocate_bits_device")
+           "actq_allocate_bits_device", "actq_relu_mask_bytes", "actq_relu_forward", "actq_relu_backward",
+           "actq_pool2d_output_size", "actq_maxpool2d_forward", "actq_maxpool2d_backward")
 
 
 class ActqError(RuntimeError):
@@ -65,6 +66,18 @@ def lib() -> ctypes.CDLL:
     L.actq_sample_sensitivity.argtypes = [vp, i64, i64, i32, vp, vp, vp]
     L.actq_allocate_bits.restype = c.c_int
     L.actq_allocate_bits.argtypes = [vp, vp, i64, i64, c.c_uint32, vp]
+    L.actq_relu_mask_bytes.restype = c.c_int
+    L.actq_relu_mask_bytes.argtypes = [i64, vp]
+    L.actq_relu_forward.restype = c.c_int
+    L.actq_relu_forward.argtypes = [vp, c.c_int, i64, vp, vp, vp]
+    L.actq_relu_backward.restype = c.c_int
+    L.actq_relu_backward.argtypes = [vp, vp, c.c_int, i64, vp, vp]
+    L.actq_pool2d_output_size.restype = c.c_int
+    L.actq_pool2d_output_size.argtypes = [i32] * 10 + [vp, vp]
+    L.actq_maxpool2d_forward.restype = c.c_int
+    L.actq_maxpool2d_forward.argtypes = [vp, c.c_int, i64] + [i32] * 10 + [vp, vp, vp]
+    L.actq_maxpool2d_backward.restype = c.c_int
+    L.actq_maxpool2d_backward.argtypes = [vp, vp, c.c_int, i64] + [i32] * 10 + [vp, vp]
     L.actq_allocate_bits_device.restype = c.c_int
     L.actq_allocate_bits_device.argtypes = [vp, vp, i64, i64, i32, i64, c.c_uint32, vp, vp, vp, vp]
     _lib = L
@@ -254,3 +267,83 @@ def allocate_bits_device(w, D, budget_bits: int, widths: int = ACTQ_WIDTHS_POW2,
                                            _dev(offsets, torch.int64, "offsets"),
                                            _dev(result, torch.int64, "result"), _stream(stream)))
     return bits, offsets, result
+
+
+# ----------------------------------------------------------------------------- exact layer contexts
+
+def relu_mask_bytes(n: int) -> int:
+    out = ctypes.c_uint64()
+    _check(lib().actq_relu_mask_bytes(int(n), ctypes.addressof(out)))
+    return out.value
+
+
+def relu_forward(x, y=None, mask=None, stream=None):
+    """Device: y = max(x, 0) and the 1-bit context.  Returns (y, mask uint8)."""
+    torch = _torch()
+    n = int(x.numel())
+    if y is None:
+        y = torch.empty_like(x)
+    if mask is None:
+        mask = torch.empty(relu_mask_bytes(n), dtype=torch.uint8, device=x.device)
+    if y.numel() != n or y.dtype != x.dtype or mask.numel() != relu_mask_bytes(n):
+        raise ValueError("y must match x and mask must have relu_mask_bytes(n) bytes")
+    _check(lib().actq_relu_forward(_dev(x, None, "x"), _dtype_code(x), n, _dev(y, None, "y"),
+                                   _dev(mask, torch.uint8, "mask"), _stream(stream)))
+    return y, mask
+
+
+def relu_backward(mask, grad_y, grad_x=None, stream=None):
+    """Device: grad_x = grad_y where the stored bit is set, +0 elsewhere."""
+    torch = _torch()
+    n = int(grad_y.numel())
+    if grad_x is None:
+        grad_x = torch.empty_like(grad_y)
+    if grad_x.numel() != n or grad_x.dtype != grad_y.dtype or mask.numel() != relu_mask_bytes(n):
+        raise ValueError("grad_x must match grad_y and mask must have relu_mask_bytes(n) bytes")
+    _check(lib().actq_relu_backward(_dev(mask, torch.uint8, "mask"), _dev(grad_y, None, "grad_y"), _dtype_code(grad_y),
+                                    n, _dev(grad_x, None, "grad_x"), _stream(stream)))
+    return grad_x
+
+
+def pool2d_output_size(H, W, kernel, stride, padding=(0, 0), dilation=(1, 1)):
+    oh, ow = ctypes.c_int32(), ctypes.c_int32()
+    _check(lib().actq_pool2d_output_size(H, W, *kernel, *stride, *padding, *dilation,
+                                         ctypes.addressof(oh), ctypes.addressof(ow)))
+    return oh.value, ow.value
+
+
+def maxpool2d_forward(x, kernel, stride, padding=(0, 0), dilation=(1, 1), y=None, argmax=None, stream=None):
+    """Device: x [..., H, W] -> (y [..., OH, OW], argmax uint8 [..., OH, OW])."""
+    torch = _torch()
+    H, W = int(x.shape[-2]), int(x.shape[-1])
+    planes = int(x.numel() // (H * W))
+    OH, OW = pool2d_output_size(H, W, kernel, stride, padding, dilation)
+    shape = tuple(x.shape[:-2]) + (OH, OW)
+    if y is None:
+        y = torch.empty(shape, dtype=x.dtype, device=x.device)
+    if argmax is None:
+        argmax = torch.empty(shape, dtype=torch.uint8, device=x.device)
+    if y.numel() != planes * OH * OW or argmax.numel() != planes * OH * OW or y.dtype != x.dtype:
+        raise ValueError("y and argmax must have planes*OH*OW elements")
+    _check(lib().actq_maxpool2d_forward(_dev(x, None, "x"), _dtype_code(x), planes, H, W, *kernel, *stride, *padding,
+                                        *dilation, _dev(y, None, "y"), _dev(argmax, torch.uint8, "argmax"),
+                                        _stream(stream)))
+    return y, argmax
+
+
+def maxpool2d_backward(argmax, grad_y, H, W, kernel, stride, padding=(0, 0), dilation=(1, 1), grad_x=None,
+                       stream=None):
+    """Device: gradient of the input from the stored window positions."""
+    torch = _torch()
+    OH, OW = pool2d_output_size(H, W, kernel, stride, padding, dilation)
+    if tuple(grad_y.shape[-2:]) != (OH, OW) or argmax.numel() != grad_y.numel():
+        raise ValueError("grad_y and argmax must be [..., OH, OW]")
+    planes = int(grad_y.numel() // (OH * OW))
+    if grad_x is None:
+        grad_x = torch.empty(tuple(grad_y.shape[:-2]) + (H, W), dtype=grad_y.dtype, device=grad_y.device)
+    if grad_x.numel() != planes * H * W or grad_x.dtype != grad_y.dtype:
+        raise ValueError("grad_x must have planes*H*W elements")
+    _check(lib().actq_maxpool2d_backward(_dev(argmax, torch.uint8, "argmax"), _dev(grad_y, None, "grad_y"),
+                                         _dtype_code(grad_y), planes, H, W, *kernel, *stride, *padding, *dilation,
+                                         _dev(grad_x, None, "grad_x"), _stream(stream)))
+    return grad_x

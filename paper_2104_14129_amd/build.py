@@ -10,7 +10,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libactq.so")
-SOURCES = ["actq_api.cpp", "actq_kernels.hip"]
+SOURCES = ["actq_api.cpp", "actq_kernels.hip", "actq_context.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -252,4 +252,99 @@ int actq_allocate_bits_device(const float* w, const int64_t* D_items, int64_t D,
     return launch_allocate_bits(w, D_items, D, M, budget_bits, lad, bits, offsets, result, stream);
 }
 
+int actq_relu_mask_bytes(int64_t n, uint64_t* bytes_host)
+{
+    if (n <= 0 || !bytes_host) return fail(ACTQ_EINVAL, "actq_relu_mask_bytes: n must be positive and bytes_host non-null");
+    *bytes_host = static_cast<uint64_t>((n + 255) / 256) * 32;
+    return ACTQ_OK;
+}
+
+static int check_elementwise(const char* who, const void* a, const void* b, const void* mask, int dt, int64_t n)
+{
+    if (int rc = check_dtype(who, dt)) return rc;
+    if (!a || !b || !mask) return fail(ACTQ_EINVAL, "%s: null pointer", who);
+    if (n <= 0 || n >= (int64_t(1) << 40)) return fail(ACTQ_EINVAL, "%s: n must be in [1, 2^40)", who);
+    if (!aligned(a, 16) || !aligned(b, 16) || !aligned(mask, 16))
+        return fail(ACTQ_EINVAL, "%s: tensors and mask must be 16-byte aligned", who);
+    return ACTQ_OK;
+}
+
+int actq_relu_forward(const void* x, actq_dtype dt, int64_t n, void* y, uint8_t* mask, void* stream)
+{
+    if (int rc = check_elementwise("actq_relu_forward", x, y, mask, dt, n)) return rc;
+    return launch_relu_forward(x, dt, n, y, mask, stream);
+}
+
+int actq_relu_backward(const uint8_t* mask, const void* grad_y, actq_dtype dt, int64_t n, void* grad_x,
+                       void* stream)
+{
+    if (int rc = check_elementwise("actq_relu_backward", grad_y, grad_x, mask, dt, n)) return rc;
+    return launch_relu_backward(mask, grad_y, dt, n, grad_x, stream);
+}
+
+static int make_pool_shape(const char* who, int32_t H, int32_t W, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
+                           int32_t ph, int32_t pw, int32_t dh, int32_t dw, PoolShape* p)
+{
+    if (H <= 0 || W <= 0) return fail(ACTQ_EINVAL, "%s: H and W must be positive", who);
+    if (kh <= 0 || kw <= 0 || static_cast<int64_t>(kh) * kw > 256)
+        return fail(ACTQ_EINVAL, "%s: window %d x %d must have 1..256 positions (8-bit context)", who, kh, kw);
+    if (sh <= 0 || sw <= 0 || dh <= 0 || dw <= 0) return fail(ACTQ_EINVAL, "%s: strides and dilations must be positive", who);
+    if (ph < 0 || pw < 0 || 2 * ph > kh || 2 * pw > kw)
+        return fail(ACTQ_EINVAL, "%s: padding must be between 0 and half the window size", who);
+    const int64_t eh = static_cast<int64_t>(dh) * (kh - 1) + 1, ew = static_cast<int64_t>(dw) * (kw - 1) + 1;
+    if (H + 2 * static_cast<int64_t>(ph) < eh || W + 2 * static_cast<int64_t>(pw) < ew)
+        return fail(ACTQ_EINVAL, "%s: the window does not fit the padded input", who);
+    if (eh > (int64_t(1) << 20) || ew > (int64_t(1) << 20) || H > (1 << 24) || W > (1 << 24) ||
+        sh > (1 << 20) || sw > (1 << 20))
+        return fail(ACTQ_EINVAL, "%s: geometry too large", who);
+    p->H = H; p->W = W;
+    p->kh = kh; p->kw = kw; p->sh = sh; p->sw = sw; p->ph = ph; p->pw = pw; p->dh = dh; p->dw = dw;
+    p->OH = static_cast<int32_t>((H + 2 * static_cast<int64_t>(ph) - eh) / sh + 1);
+    p->OW = static_cast<int32_t>((W + 2 * static_cast<int64_t>(pw) - ew) / sw + 1);
+    return ACTQ_OK;
+}
+
+int actq_pool2d_output_size(int32_t H, int32_t W, int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph,
+                            int32_t pw, int32_t dh, int32_t dw, int32_t* OH_host, int32_t* OW_host)
+{
+    if (!OH_host || !OW_host) return fail(ACTQ_EINVAL, "actq_pool2d_output_size: null output");
+    PoolShape p;
+    if (int rc = make_pool_shape("actq_pool2d_output_size", H, W, kh, kw, sh, sw, ph, pw, dh, dw, &p)) return rc;
+    *OH_host = p.OH;
+    *OW_host = p.OW;
+    return ACTQ_OK;
+}
+
+static int check_pool_call(const char* who, const void* a, const void* b, const void* arg, int dt, int64_t planes,
+                           const PoolShape& p)
+{
+    if (int rc = check_dtype(who, dt)) return rc;
+    if (!a || !b || !arg) return fail(ACTQ_EINVAL, "%s: null pointer", who);
+    if (planes <= 0 || static_cast<__int128>(planes) * p.H * p.W >= (static_cast<__int128>(1) << 40))
+        return fail(ACTQ_EINVAL, "%s: planes * H * W must be in [1, 2^40)", who);
+    const uintptr_t elem = dt == ACTQ_F32 ? 4 : 2;
+    if (!aligned(a, elem) || !aligned(b, elem)) return fail(ACTQ_EINVAL, "%s: tensors must be aligned to their element size", who);
+    return ACTQ_OK;
+}
+
+int actq_maxpool2d_forward(const void* x, actq_dtype dt, int64_t planes, int32_t H, int32_t W, int32_t kh,
+                           int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw, int32_t dh, int32_t dw,
+                           void* y, uint8_t* argmax, void* stream)
+{
+    PoolShape p;
+    if (int rc = make_pool_shape("actq_maxpool2d_forward", H, W, kh, kw, sh, sw, ph, pw, dh, dw, &p)) return rc;
+    if (int rc = check_pool_call("actq_maxpool2d_forward", x, y, argmax, dt, planes, p)) return rc;
+    return launch_maxpool2d_forward(x, dt, planes, p, y, argmax, stream);
+}
+
+int actq_maxpool2d_backward(const uint8_t* argmax, const void* grad_y, actq_dtype dt, int64_t planes, int32_t H,
+                            int32_t W, int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
+                            int32_t dh, int32_t dw, void* grad_x, void* stream)
+{
+    PoolShape p;
+    if (int rc = make_pool_shape("actq_maxpool2d_backward", H, W, kh, kw, sh, sw, ph, pw, dh, dw, &p)) return rc;
+    if (int rc = check_pool_call("actq_maxpool2d_backward", grad_y, grad_x, argmax, dt, planes, p)) return rc;
+    return launch_maxpool2d_backward(argmax, grad_y, dt, planes, p, grad_x, stream);
+}
+
 }  // extern "C"

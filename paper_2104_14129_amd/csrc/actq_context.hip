@@ -1,0 +1,340 @@
+// HIP kernels of libactq for gfx950 (MI355X): the exact layer contexts of ActNN's appendix.
+//
+//   * ReLU ("Activation Layers"): the context is one bit per element, f'(x) = [x > 0].
+//     Forward writes y = max(x, 0) and the bit stream; backward multiplies the incoming
+//     gradient by the stored bit (as a selection, so a cleared bit always gives +0).
+//   * Max pooling ("Pooling Layers"): the context is, per output location, the 8-bit
+//     position of the maximum inside its window.  Backward gathers, for every input
+//     location, the output gradients whose stored position points at it.
+//
+// Both are pure streaming kernels bound by HBM.  ReLU uses the same decomposition as the
+// quantizer: one wavefront per tile of four 128-bit loads per lane; the comparison masks
+// come out of v_cmp as 64-bit wavefront masks, and a few lanes interleave them into the
+// LSB-first stream, so the bits leave as one coalesced store per tile without LDS.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "actq_internal.h"
+
+namespace actq {
+namespace {
+
+constexpr int kWave = 64;
+constexpr int kWavesPerBlock = 4;
+constexpr int kBlock = kWave * kWavesPerBlock;
+constexpr int kLoadsPerTile = 4;
+
+int launched(const char* who)
+{
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(ACTQ_EHIP, "%s: launch failed: %s", who, hipGetErrorString(e));
+    return ACTQ_OK;
+}
+
+// ------------------------------------------------------------------------------------
+// ReLU.  A lane owns E consecutive elements per load (E = 4 binary32 or 8 binary16 values:
+// 128 bits); a load of the wavefront covers 64*E elements = 2*E words of the bit stream.
+
+template <typename T>
+struct Lanes;
+
+template <>
+struct Lanes<float> {
+    static constexpr int E = 4;
+    typedef float vec __attribute__((ext_vector_type(4)));
+};
+
+template <>
+struct Lanes<_Float16> {
+    static constexpr int E = 8;
+    typedef _Float16 vec __attribute__((ext_vector_type(8)));
+};
+
+// Moves bit t of `piece` (32 / E bits wide) to bit E * t.
+template <int E>
+__device__ __forceinline__ uint32_t spread(uint32_t piece)
+{
+    if (E == 4) {  // 8 bits -> every 4th bit
+        uint32_t x = piece & 0xffu;
+        x = (x | (x << 12)) & 0x000f000fu;
+        x = (x | (x << 6)) & 0x03030303u;
+        x = (x | (x << 3)) & 0x11111111u;
+        return x;
+    } else {  // 4 bits -> every 8th bit
+        uint32_t x = piece & 0xfu;
+        x = (x | (x << 14)) & 0x00030003u;
+        x = (x | (x << 7)) & 0x01010101u;
+        return x;
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kBlock) void relu_forward_kernel(const T* x, int64_t n, int64_t mask_words,
+                                                              T* y, uint32_t* __restrict__ mask)
+{
+    constexpr int E = Lanes<T>::E;
+    typedef typename Lanes<T>::vec vec;
+    constexpr int kWordsPerLoad = 2 * E;           // 64 * E bits
+    constexpr int kLanesPerWord = 32 / E;          // lanes whose bits share one word
+    constexpr int64_t kTileElems = int64_t(kLoadsPerTile) * kWave * E;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t tile = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6);
+    const int64_t first = tile * kTileElems;
+    if (first >= n) return;
+    const bool full = first + kTileElems <= n;
+
+    vec v[kLoadsPerTile];
+    if (full) {
+#pragma unroll
+        for (int u = 0; u < kLoadsPerTile; ++u)
+            v[u] = __builtin_nontemporal_load(reinterpret_cast<const vec*>(x + first + (u * kWave + lane) * E));
+    } else {
+#pragma unroll
+        for (int u = 0; u < kLoadsPerTile; ++u)
+#pragma unroll
+            for (int k = 0; k < E; ++k) {
+                const int64_t i = first + (u * kWave + lane) * E + k;
+                v[u][k] = i < n ? x[i] : static_cast<T>(0.0f);  // past the end: bit 0, nothing stored
+            }
+    }
+
+    // m[u][k]: lane l's bit says whether element k of lane l in load u is positive
+    uint64_t m[kLoadsPerTile][E];
+#pragma unroll
+    for (int u = 0; u < kLoadsPerTile; ++u) {
+        vec out;
+#pragma unroll
+        for (int k = 0; k < E; ++k) {
+            const bool positive = static_cast<float>(v[u][k]) > 0.0f;
+            m[u][k] = __ballot(positive);
+            out[k] = positive ? v[u][k] : static_cast<T>(0.0f);
+        }
+        if (full) {
+            __builtin_nontemporal_store(out, reinterpret_cast<vec*>(y + first + (u * kWave + lane) * E));
+        } else {
+#pragma unroll
+            for (int k = 0; k < E; ++k) {
+                const int64_t i = first + (u * kWave + lane) * E + k;
+                if (i < n) y[i] = out[k];
+            }
+        }
+    }
+
+    // Word j of the tile's stream (j = lane) holds the bits of kLanesPerWord lanes of load
+    // u = j / kWordsPerLoad: stream bit E*l + k is bit l of m[u][k].
+    const int u_sel = lane / kWordsPerLoad;
+    const int first_lane = (lane % kWordsPerLoad) * kLanesPerWord;
+    uint32_t word = 0;
+#pragma unroll
+    for (int k = 0; k < E; ++k) {
+        uint64_t mk = m[0][k];
+#pragma unroll
+        for (int u = 1; u < kLoadsPerTile; ++u) mk = u_sel == u ? m[u][k] : mk;
+        word |= spread<E>(static_cast<uint32_t>(mk >> first_lane)) << k;
+    }
+    const int64_t w = tile * (kLoadsPerTile * kWordsPerLoad) + lane;
+    if (lane < kLoadsPerTile * kWordsPerLoad && w < mask_words) __builtin_nontemporal_store(word, mask + w);
+}
+
+template <typename T>
+__global__ __launch_bounds__(kBlock) void relu_backward_kernel(const uint32_t* __restrict__ mask, int64_t mask_words,
+                                                               const T* grad_y, int64_t n, T* grad_x)
+{
+    constexpr int E = Lanes<T>::E;
+    typedef typename Lanes<T>::vec vec;
+    constexpr int kWordsPerLoad = 2 * E;
+    constexpr int64_t kTileElems = int64_t(kLoadsPerTile) * kWave * E;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t tile = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6);
+    const int64_t first = tile * kTileElems;
+    if (first >= n) return;
+    const bool full = first + kTileElems <= n;
+
+    vec g[kLoadsPerTile];
+    uint32_t word[kLoadsPerTile];
+#pragma unroll
+    for (int u = 0; u < kLoadsPerTile; ++u) {
+        // the lane's E bits start at bit E*lane of the load's 64*E-bit stretch
+        int64_t w = tile * (kLoadsPerTile * kWordsPerLoad) + u * kWordsPerLoad + (lane * E >> 5);
+        w = w < mask_words ? w : mask_words - 1;  // past the end: any word, its elements are not stored
+        word[u] = __builtin_nontemporal_load(mask + w);
+        if (full) {
+            g[u] = __builtin_nontemporal_load(reinterpret_cast<const vec*>(grad_y + first + (u * kWave + lane) * E));
+        } else {
+#pragma unroll
+            for (int k = 0; k < E; ++k) {
+                const int64_t i = first + (u * kWave + lane) * E + k;
+                g[u][k] = i < n ? grad_y[i] : static_cast<T>(0.0f);
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < kLoadsPerTile; ++u) {
+        const uint32_t mine = word[u] >> ((lane * E) & 31);
+        vec out;
+#pragma unroll
+        for (int k = 0; k < E; ++k) out[k] = (mine >> k) & 1u ? g[u][k] : static_cast<T>(0.0f);
+        if (full) {
+            __builtin_nontemporal_store(out, reinterpret_cast<vec*>(grad_x + first + (u * kWave + lane) * E));
+        } else {
+#pragma unroll
+            for (int k = 0; k < E; ++k) {
+                const int64_t i = first + (u * kWave + lane) * E + k;
+                if (i < n) grad_x[i] = out[k];
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// Max pooling.
+
+struct Pool {
+    int32_t H, W, OH, OW;
+    int32_t kh, kw, sh, sw, ph, pw, dh, dw;
+};
+
+// One thread per output location, consecutive threads along a row of the output.  The window
+// is scanned row by row and only a strictly larger value replaces the running maximum, so
+// among equal values the first position wins; padded positions are skipped.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void maxpool2d_forward_kernel(const T* __restrict__ x, int64_t outputs, Pool g,
+                                                                   T* __restrict__ y, uint8_t* __restrict__ argmax)
+{
+    const int64_t o = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (o >= outputs) return;
+    const int64_t row = o / g.OW;
+    const int32_t j = static_cast<int32_t>(o - row * g.OW);
+    const int64_t plane = row / g.OH;
+    const int32_t i = static_cast<int32_t>(row - plane * g.OH);
+    const T* xp = x + plane * g.H * g.W;
+    const int32_t r0 = g.sh * i - g.ph, c0 = g.sw * j - g.pw;
+    bool have = false;
+    float best = 0.0f;
+    int32_t best_k = 0;
+    for (int32_t a = 0; a < g.kh; ++a) {
+        const int32_t r = r0 + g.dh * a;
+        if (r < 0 || r >= g.H) continue;
+        for (int32_t b = 0; b < g.kw; ++b) {
+            const int32_t c = c0 + g.dw * b;
+            if (c < 0 || c >= g.W) continue;
+            const float v = static_cast<float>(xp[static_cast<int64_t>(r) * g.W + c]);
+            if (!have || v > best) {
+                have = true;
+                best = v;
+                best_k = a * g.kw + b;
+            }
+        }
+    }
+    y[o] = static_cast<T>(best);  // exact: `best` is one of the inputs
+    argmax[o] = static_cast<uint8_t>(best_k);
+}
+
+// One thread per input location.  The outputs whose window contains it are visited row by row
+// (ascending output row, then column) and those whose stored position points here are added
+// in binary32, the order in which a scatter over the outputs would have added them.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void maxpool2d_backward_kernel(const uint8_t* __restrict__ argmax,
+                                                                    const T* __restrict__ grad_y, int64_t inputs,
+                                                                    Pool g, T* __restrict__ grad_x)
+{
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (t >= inputs) return;
+    const int64_t row = t / g.W;
+    const int32_t c = static_cast<int32_t>(t - row * g.W);
+    const int64_t plane = row / g.H;
+    const int32_t r = static_cast<int32_t>(row - plane * g.H);
+    const int64_t obase = plane * g.OH * g.OW;
+    float acc = 0.0f;
+    for (int32_t a = g.kh - 1; a >= 0; --a) {  // descending window row = ascending output row
+        const int32_t tr = r + g.ph - g.dh * a;
+        if (tr < 0) continue;
+        const int32_t i = tr / g.sh;
+        if (i * g.sh != tr || i >= g.OH) continue;
+        for (int32_t b = g.kw - 1; b >= 0; --b) {
+            const int32_t tc = c + g.pw - g.dw * b;
+            if (tc < 0) continue;
+            const int32_t j = tc / g.sw;
+            if (j * g.sw != tc || j >= g.OW) continue;
+            const int64_t o = obase + static_cast<int64_t>(i) * g.OW + j;
+            if (argmax[o] == static_cast<uint8_t>(a * g.kw + b)) acc += static_cast<float>(grad_y[o]);
+        }
+    }
+    grad_x[t] = static_cast<T>(acc);
+}
+
+}  // namespace
+
+int launch_relu_forward(const void* x, int dtype, int64_t n, void* y, uint8_t* mask, void* stream)
+{
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t mask_words = (n + 255) / 256 * 8;
+    if (dtype == ACTQ_F32) {
+        const int64_t tiles = (n + 1023) / 1024;
+        relu_forward_kernel<float><<<static_cast<unsigned>((tiles + kWavesPerBlock - 1) / kWavesPerBlock), kBlock, 0, s>>>(
+            static_cast<const float*>(x), n, mask_words, static_cast<float*>(y), reinterpret_cast<uint32_t*>(mask));
+    } else {
+        const int64_t tiles = (n + 2047) / 2048;
+        relu_forward_kernel<_Float16><<<static_cast<unsigned>((tiles + kWavesPerBlock - 1) / kWavesPerBlock), kBlock, 0, s>>>(
+            static_cast<const _Float16*>(x), n, mask_words, static_cast<_Float16*>(y), reinterpret_cast<uint32_t*>(mask));
+    }
+    return launched("actq_relu_forward");
+}
+
+int launch_relu_backward(const uint8_t* mask, const void* grad_y, int dtype, int64_t n, void* grad_x, void* stream)
+{
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t mask_words = (n + 255) / 256 * 8;
+    if (dtype == ACTQ_F32) {
+        const int64_t tiles = (n + 1023) / 1024;
+        relu_backward_kernel<float><<<static_cast<unsigned>((tiles + kWavesPerBlock - 1) / kWavesPerBlock), kBlock, 0, s>>>(
+            reinterpret_cast<const uint32_t*>(mask), mask_words, static_cast<const float*>(grad_y), n, static_cast<float*>(grad_x));
+    } else {
+        const int64_t tiles = (n + 2047) / 2048;
+        relu_backward_kernel<_Float16><<<static_cast<unsigned>((tiles + kWavesPerBlock - 1) / kWavesPerBlock), kBlock, 0, s>>>(
+            reinterpret_cast<const uint32_t*>(mask), mask_words, static_cast<const _Float16*>(grad_y), n, static_cast<_Float16*>(grad_x));
+    }
+    return launched("actq_relu_backward");
+}
+
+static Pool make_pool(const PoolShape& p)
+{
+    Pool g;
+    g.H = p.H; g.W = p.W; g.OH = p.OH; g.OW = p.OW;
+    g.kh = p.kh; g.kw = p.kw; g.sh = p.sh; g.sw = p.sw;
+    g.ph = p.ph; g.pw = p.pw; g.dh = p.dh; g.dw = p.dw;
+    return g;
+}
+
+int launch_maxpool2d_forward(const void* x, int dtype, int64_t planes, const PoolShape& p, void* y,
+                             uint8_t* argmax, void* stream)
+{
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t outputs = planes * p.OH * p.OW;
+    const unsigned blocks = static_cast<unsigned>((outputs + kBlock - 1) / kBlock);
+    if (dtype == ACTQ_F32)
+        maxpool2d_forward_kernel<float><<<blocks, kBlock, 0, s>>>(static_cast<const float*>(x), outputs, make_pool(p),
+                                                                  static_cast<float*>(y), argmax);
+    else
+        maxpool2d_forward_kernel<_Float16><<<blocks, kBlock, 0, s>>>(static_cast<const _Float16*>(x), outputs, make_pool(p),
+                                                                     static_cast<_Float16*>(y), argmax);
+    return launched("actq_maxpool2d_forward");
+}
+
+int launch_maxpool2d_backward(const uint8_t* argmax, const void* grad_y, int dtype, int64_t planes,
+                              const PoolShape& p, void* grad_x, void* stream)
+{
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t inputs = planes * p.H * p.W;
+    const unsigned blocks = static_cast<unsigned>((inputs + kBlock - 1) / kBlock);
+    if (dtype == ACTQ_F32)
+        maxpool2d_backward_kernel<float><<<blocks, kBlock, 0, s>>>(argmax, static_cast<const float*>(grad_y), inputs,
+                                                                   make_pool(p), static_cast<float*>(grad_x));
+    else
+        maxpool2d_backward_kernel<_Float16><<<blocks, kBlock, 0, s>>>(argmax, static_cast<const _Float16*>(grad_y), inputs,
+                                                                      make_pool(p), static_cast<_Float16*>(grad_x));
+    return launched("actq_maxpool2d_backward");
+}
+
+}  // namespace actq

@@ -36,6 +36,20 @@ int launch_sample_sensitivity(const float* grange, int64_t N, int64_t ng, int32_
 int launch_allocate_bits(const float* w, const int64_t* D_items, int64_t D, int64_t M, int64_t budget_bits,
                          const Ladder& lad, uint8_t* bits, uint64_t* offsets, int64_t* result, void* stream);
 
+// Geometry of a 2-D pooling window, validated, with the output size worked out.
+struct PoolShape {
+    int32_t H, W, OH, OW;
+    int32_t kh, kw, sh, sw, ph, pw, dh, dw;
+};
+
+// Launchers of the exact layer contexts (context kernels file).
+int launch_relu_forward(const void* x, int dtype, int64_t n, void* y, uint8_t* mask, void* stream);
+int launch_relu_backward(const uint8_t* mask, const void* grad_y, int dtype, int64_t n, void* grad_x, void* stream);
+int launch_maxpool2d_forward(const void* x, int dtype, int64_t planes, const PoolShape& p, void* y,
+                             uint8_t* argmax, void* stream);
+int launch_maxpool2d_backward(const uint8_t* argmax, const void* grad_y, int dtype, int64_t planes,
+                              const PoolShape& p, void* grad_x, void* stream);
+
 }  // namespace actq
 
 #endif

@@ -16,7 +16,7 @@ FAKE = 0x1000  # a non-null, 16-byte aligned address that is never dereferenced 
 def test_every_declared_symbol_is_exported():
     header = open(os.path.join(ROOT, "include", "actq.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(actq_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(actq_[a-z0-9_]+)\s*\(", header))
     assert declared == set(B.EXPORTS)
     L = B.lib()
     for name in declared:
@@ -160,3 +160,45 @@ def test_allocate_bits_full_sweep_size():
     assert np.array_equal(got, oracle.allocate_bits(w, D, budget, oracle.WIDTHS_ALL))
     used = int((got.astype(np.int64) * D).sum())
     assert used <= budget and budget - used < D.max()
+
+
+def test_context_calls_validate_before_launching():
+    L = B.lib()
+    E = B.ACTQ_EINVAL
+    assert B.relu_mask_bytes(1) == 32 and B.relu_mask_bytes(256) == 32 and B.relu_mask_bytes(257) == 64
+    assert L.actq_relu_mask_bytes(0, FAKE) == E and L.actq_relu_mask_bytes(5, None) == E
+    # relu_forward: x, dt, n, y, mask, stream
+    ok = [FAKE, 0, 1000, FAKE, FAKE, None]
+    for idx, bad in [(0, None), (3, None), (4, None), (1, 5), (2, 0), (2, 1 << 40), (0, FAKE + 4), (3, FAKE + 8), (4, FAKE + 1)]:
+        args = list(ok)
+        args[idx] = bad
+        assert L.actq_relu_forward(*args) == E, (idx, bad)
+    # relu_backward: mask, grad_y, dt, n, grad_x, stream
+    ok = [FAKE, FAKE, 1, 1000, FAKE, None]
+    for idx, bad in [(0, None), (1, None), (4, None), (2, 2), (3, -1), (0, FAKE + 2), (1, FAKE + 2)]:
+        args = list(ok)
+        args[idx] = bad
+        assert L.actq_relu_backward(*args) == E, (idx, bad)
+    # output size
+    assert B.pool2d_output_size(112, 112, (3, 3), (2, 2), (1, 1)) == (56, 56)
+    assert B.pool2d_output_size(9, 11, (3, 2), (1, 2), (1, 0), (2, 1)) == (7, 5)
+    for kw in [dict(kernel=(3, 3), stride=(2, 2), padding=(2, 1)), dict(kernel=(17, 16), stride=(1, 1)),
+               dict(kernel=(2, 2), stride=(0, 1)), dict(kernel=(2, 2), stride=(1, 1), dilation=(0, 1)),
+               dict(kernel=(5, 5), stride=(1, 1)), dict(kernel=(0, 2), stride=(1, 1)),
+               dict(kernel=(2, 2), stride=(1, 1), padding=(-1, 0))]:
+        with pytest.raises(B.ActqError):
+            B.pool2d_output_size(4, 4, **kw)
+    # maxpool2d_forward: x, dt, planes, H, W, kh, kw, sh, sw, ph, pw, dh, dw, y, argmax, stream
+    ok = [FAKE, 0, 6, 8, 8, 3, 3, 2, 2, 1, 1, 1, 1, FAKE, FAKE, None]
+    for idx, bad in [(0, None), (13, None), (14, None), (1, 9), (2, 0), (2, 1 << 40), (3, 0), (5, 20), (7, 0), (9, 2),
+                     (0, FAKE + 2), (13, FAKE + 1)]:
+        args = list(ok)
+        args[idx] = bad
+        assert L.actq_maxpool2d_forward(*args) == E, (idx, bad)
+        assert B.last_error()
+    # maxpool2d_backward: argmax, grad_y, dt, planes, H, W, kh..dw, grad_x, stream
+    ok = [FAKE, FAKE, 1, 6, 8, 8, 3, 3, 2, 2, 1, 1, 1, 1, FAKE, None]
+    for idx, bad in [(0, None), (1, None), (14, None), (2, 3), (3, -2), (4, 0), (1, FAKE + 1)]:
+        args = list(ok)
+        args[idx] = bad
+        assert L.actq_maxpool2d_backward(*args) == E, (idx, bad)
