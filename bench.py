@@ -35,7 +35,7 @@ def parse():
     p.add_argument("--gpus", type=int, default=1)
     p.add_argument("--steps", type=int, default=30)
     p.add_argument("--warmup", type=int, default=5)
-    p.add_argument("--workload", default="r50_stage1", choices=["r50_stage1", "tiny", "r50_stem_f16", "fpn", "r50_sweep"])
+    p.add_argument("--workload", default="r50_stage1", choices=["r50_stage1", "tiny", "r50_stem_f16", "fpn", "r50_sweep", "contexts"])
     p.add_argument("--noise-bits", type=int, default=16, choices=[24, 16])
     p.add_argument("--header", default="f32", choices=["f32", "bf16"],
                    help="group header format: (Z, R/B) binary32, 8 B/group, or (Z, R) bfloat16, 4 B/group")
@@ -201,6 +201,82 @@ def sweep(args, torch, B, synth, dev):
     print(json.dumps(result))
 
 
+def contexts(args, torch, B, dev):
+    """Exact layer contexts on the ResNet-50 stem at batch 256, fp32 [256,64,112,112]: ReLU forward
+    and backward (1-bit mask), then the 3x3 / stride 2 / padding 1 max pooling forward and backward
+    (8-bit window positions).  One step is the four launches."""
+    N, C, H, W = 256, 64, 112, 112
+    k, s_, p = (3, 3), (2, 2), (1, 1)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(77)
+    x = torch.randn((N, C, H, W), generator=gen, device=dev, dtype=torch.float32)
+    OH, OW = B.pool2d_output_size(H, W, k, s_, p)
+    gy_pool = torch.randn((N, C, OH, OW), generator=gen, device=dev, dtype=torch.float32)
+    y = torch.empty_like(x)
+    mask = torch.empty(B.relu_mask_bytes(x.numel()), dtype=torch.uint8, device=dev)
+    pooled = torch.empty((N, C, OH, OW), dtype=torch.float32, device=dev)
+    arg = torch.empty((N, C, OH, OW), dtype=torch.uint8, device=dev)
+    g_act = torch.empty_like(x)
+    g_in = torch.empty_like(x)
+    stream = torch.cuda.current_stream()
+    n_in, n_out = x.numel(), pooled.numel()
+    alg = {"relu_forward": n_in * 8 + mask.numel(), "maxpool2d_forward": n_in * 4 + n_out * 5,
+           "maxpool2d_backward": n_out * 5 + n_in * 4, "relu_backward": n_in * 8 + mask.numel()}
+
+    def step(events=None):
+        def timed(name, fn):
+            if events is None:
+                return fn()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            fn()
+            b.record(stream)
+            events.setdefault(name, []).append((a, b))
+        timed("relu_forward", lambda: B.relu_forward(x, y, mask, stream=stream))
+        timed("maxpool2d_forward", lambda: B.maxpool2d_forward(y, k, s_, p, y=pooled, argmax=arg, stream=stream))
+        timed("maxpool2d_backward", lambda: B.maxpool2d_backward(arg, gy_pool, H, W, k, s_, p, grad_x=g_act, stream=stream))
+        timed("relu_backward", lambda: B.relu_backward(mask, g_act, g_in, stream=stream))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = {}
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    kernel_ms = {k_: float(np.mean([a.elapsed_time(b) for a, b in v])) for k_, v in events.items()}
+    per_kernel = {k_: {"ms": kernel_ms[k_], "algorithmic_GBps": alg[k_] / kernel_ms[k_] / 1e6,
+                       "frac_of_hbm_peak": alg[k_] / kernel_ms[k_] / 1e6 / HBM_PEAK_GBS} for k_ in kernel_ms}
+    dominant = max(kernel_ms, key=kernel_ms.get)
+    achieved = alg[dominant] / kernel_ms[dominant] / 1e6
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        import oracle
+        sample = x[:8].cpu().numpy()
+        t = time.perf_counter()
+        oy, om = oracle.relu_forward(sample.reshape(-1))
+        py, pa = oracle.maxpool2d_forward(oy.reshape(sample.shape), k, s_, p)
+        gx = oracle.maxpool2d_backward(pa, gy_pool[:8].cpu().numpy(), H, W, k, s_, p)
+        oracle.relu_backward(om, gx.reshape(-1))
+        cpu_s = time.perf_counter() - t
+        cpu_baseline = {"value": sample.nbytes / cpu_s / 1e9, "unit": "GB/s", "cores": oracle.threads(), "kind": "oracle",
+                        "sample": f"the same four calls on 8 of the 256 samples, {cpu_s:.2f} s"}
+    print(json.dumps({
+        "metric": "exact layer contexts (ReLU mask, max-pool positions): GB/s of fp32 input per step; % of HBM peak",
+        "value": n_in * 4 / (ms_per_step * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "contexts_r50_stem_f32_256x64x112x112", "pool": "3x3 stride 2 padding 1",
+                   "step": "relu_forward + maxpool2d_forward + maxpool2d_backward + relu_backward"},
+        "kernels": per_kernel,
+        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": alg[dominant], "avg_launch_ms": kernel_ms[dominant]},
+        "cpu_baseline": cpu_baseline}))
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -219,6 +295,8 @@ def main():
     torch.cuda.set_device(dev)
     if args.workload == "r50_sweep":
         return sweep(args, torch, B, synth, dev)
+    if args.workload == "contexts":
+        return contexts(args, torch, B, dev)
 
     wl = {"r50_stage1": synth.r50_stage1, "tiny": synth.tiny, "r50_stem_f16": synth.r50_stem_f16,
           "fpn": synth.fpn}[args.workload]()

@@ -297,6 +297,9 @@ static int make_pool_shape(const char* who, int32_t H, int32_t W, int32_t kh, in
     if (eh > (int64_t(1) << 20) || ew > (int64_t(1) << 20) || H > (1 << 24) || W > (1 << 24) ||
         sh > (1 << 20) || sw > (1 << 20))
         return fail(ACTQ_EINVAL, "%s: geometry too large", who);
+    if (static_cast<int64_t>(H) * W >= (int64_t(1) << 31) ||
+        (static_cast<int64_t>(H) + 2 * ph) * (static_cast<int64_t>(W) + 2 * pw) >= (int64_t(1) << 31))
+        return fail(ACTQ_EINVAL, "%s: one image must have fewer than 2^31 locations", who);
     p->H = H; p->W = W;
     p->kh = kh; p->kw = kw; p->sh = sh; p->sw = sw; p->ph = ph; p->pw = pw; p->dh = dh; p->dw = dw;
     p->OH = static_cast<int32_t>((H + 2 * static_cast<int64_t>(ph) - eh) / sh + 1);

@@ -190,43 +190,90 @@ __global__ __launch_bounds__(kBlock) void relu_backward_kernel(const uint32_t* _
 // ------------------------------------------------------------------------------------
 // Max pooling.
 
+// Exact n / d for 0 <= n < 2^31 by one multiply-high, an add and a shift (division by an
+// invariant integer after Granlund and Montgomery): with s = ceil(log2 d) and
+// m = floor(2^32 (2^s - d) / d) + 1,  n / d = (mulhi(n, m) + n) >> s.
+struct FastDiv {
+    uint32_t m, s;
+};
+
+FastDiv make_fastdiv(uint32_t d)
+{
+    uint32_t s = 0;
+    while ((uint64_t(1) << s) < d) ++s;
+    FastDiv f;
+    f.m = static_cast<uint32_t>(((uint64_t(1) << 32) * ((uint64_t(1) << s) - d)) / d + 1);
+    f.s = s;
+    return f;
+}
+
+__device__ __forceinline__ uint32_t fastdiv(uint32_t n, FastDiv f) { return (__umulhi(n, f.m) + n) >> f.s; }
+
 struct Pool {
     int32_t H, W, OH, OW;
     int32_t kh, kw, sh, sw, ph, pw, dh, dw;
+    FastDiv by_OW, by_W, by_sh, by_sw, by_dh, by_dw;
+    uint32_t grid_y;  // planes are spread over blockIdx.y and blockIdx.z
 };
 
-// One thread per output location, consecutive threads along a row of the output.  The window
-// is scanned row by row and only a strictly larger value replaces the running maximum, so
-// among equal values the first position wins; padded positions are skipped.
-template <typename T>
-__global__ __launch_bounds__(kBlock) void maxpool2d_forward_kernel(const T* __restrict__ x, int64_t outputs, Pool g,
+// One thread per output location; blockIdx.x runs over the locations of one plane, so
+// consecutive lanes walk along the rows of the output.  The window is scanned row by row and
+// only a strictly larger value replaces the running maximum, so among equal values the first
+// position wins; padded positions are skipped.  KH = KW = 0 takes the window size at run time.
+template <typename T, int KH, int KW>
+__global__ __launch_bounds__(kBlock) void maxpool2d_forward_kernel(const T* __restrict__ x, int64_t planes, Pool g,
                                                                    T* __restrict__ y, uint8_t* __restrict__ argmax)
 {
-    const int64_t o = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
-    if (o >= outputs) return;
-    const int64_t row = o / g.OW;
-    const int32_t j = static_cast<int32_t>(o - row * g.OW);
-    const int64_t plane = row / g.OH;
-    const int32_t i = static_cast<int32_t>(row - plane * g.OH);
+    const int64_t plane = static_cast<int64_t>(blockIdx.z) * g.grid_y + blockIdx.y;
+    const uint32_t idx = blockIdx.x * kBlock + threadIdx.x;
+    if (plane >= planes || idx >= static_cast<uint32_t>(g.OH * g.OW)) return;
+    const int32_t i = static_cast<int32_t>(fastdiv(idx, g.by_OW));
+    const int32_t j = static_cast<int32_t>(idx) - i * g.OW;
     const T* xp = x + plane * g.H * g.W;
     const int32_t r0 = g.sh * i - g.ph, c0 = g.sw * j - g.pw;
+    const int32_t kh = KH ? KH : g.kh, kw = KW ? KW : g.kw;
     bool have = false;
     float best = 0.0f;
     int32_t best_k = 0;
-    for (int32_t a = 0; a < g.kh; ++a) {
-        const int32_t r = r0 + g.dh * a;
-        if (r < 0 || r >= g.H) continue;
-        for (int32_t b = 0; b < g.kw; ++b) {
-            const int32_t c = c0 + g.dw * b;
-            if (c < 0 || c >= g.W) continue;
-            const float v = static_cast<float>(xp[static_cast<int64_t>(r) * g.W + c]);
-            if (!have || v > best) {
-                have = true;
-                best = v;
-                best_k = a * g.kw + b;
+    if (KH) {
+        // fixed window: every load is issued up front from a clamped address, then the scan
+        float v[KH ? KH : 1][KW ? KW : 1];
+        bool ok[KH ? KH : 1][KW ? KW : 1];
+#pragma unroll
+        for (int32_t a = 0; a < KH; ++a)
+#pragma unroll
+            for (int32_t b = 0; b < KW; ++b) {
+                const int32_t r = r0 + g.dh * a, c = c0 + g.dw * b;
+                ok[a][b] = r >= 0 && r < g.H && c >= 0 && c < g.W;
+                const int32_t rc = min(max(r, 0), g.H - 1), cc = min(max(c, 0), g.W - 1);
+                v[a][b] = static_cast<float>(xp[rc * g.W + cc]);
+            }
+#pragma unroll
+        for (int32_t a = 0; a < KH; ++a)
+#pragma unroll
+            for (int32_t b = 0; b < KW; ++b) {
+                const bool take = ok[a][b] && (!have || v[a][b] > best);
+                best = take ? v[a][b] : best;
+                best_k = take ? a * KW + b : best_k;
+                have = have || ok[a][b];
+            }
+    } else {
+        for (int32_t a = 0; a < kh; ++a) {
+            const int32_t r = r0 + g.dh * a;
+            if (r < 0 || r >= g.H) continue;
+            for (int32_t b = 0; b < kw; ++b) {
+                const int32_t c = c0 + g.dw * b;
+                if (c < 0 || c >= g.W) continue;
+                const float v = static_cast<float>(xp[r * g.W + c]);
+                if (!have || v > best) {
+                    have = true;
+                    best = v;
+                    best_k = a * kw + b;
+                }
             }
         }
     }
+    const int64_t o = plane * g.OH * g.OW + idx;
     y[o] = static_cast<T>(best);  // exact: `best` is one of the inputs
     argmax[o] = static_cast<uint8_t>(best_k);
 }
@@ -234,34 +281,67 @@ __global__ __launch_bounds__(kBlock) void maxpool2d_forward_kernel(const T* __re
 // One thread per input location.  The outputs whose window contains it are visited row by row
 // (ascending output row, then column) and those whose stored position points here are added
 // in binary32, the order in which a scatter over the outputs would have added them.
-template <typename T>
+// MC > 0: at most MC output rows (and MC output columns) have a window that contains a given
+// input location, i.e. ceil((d*(k-1)+1) / s) <= MC in both directions; the candidates are then
+// enumerated directly and all their loads are issued up front from clamped addresses.
+// MC = 0: any geometry, window positions scanned one by one.
+template <typename T, int MC>
 __global__ __launch_bounds__(kBlock) void maxpool2d_backward_kernel(const uint8_t* __restrict__ argmax,
-                                                                    const T* __restrict__ grad_y, int64_t inputs,
+                                                                    const T* __restrict__ grad_y, int64_t planes,
                                                                     Pool g, T* __restrict__ grad_x)
 {
-    const int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
-    if (t >= inputs) return;
-    const int64_t row = t / g.W;
-    const int32_t c = static_cast<int32_t>(t - row * g.W);
-    const int64_t plane = row / g.H;
-    const int32_t r = static_cast<int32_t>(row - plane * g.H);
-    const int64_t obase = plane * g.OH * g.OW;
+    const int64_t plane = static_cast<int64_t>(blockIdx.z) * g.grid_y + blockIdx.y;
+    const uint32_t idx = blockIdx.x * kBlock + threadIdx.x;
+    if (plane >= planes || idx >= static_cast<uint32_t>(g.H * g.W)) return;
+    const int32_t r = static_cast<int32_t>(fastdiv(idx, g.by_W));
+    const int32_t c = static_cast<int32_t>(idx) - r * g.W;
+    const uint8_t* ap = argmax + plane * g.OH * g.OW;
+    const T* gp = grad_y + plane * g.OH * g.OW;
     float acc = 0.0f;
-    for (int32_t a = g.kh - 1; a >= 0; --a) {  // descending window row = ascending output row
-        const int32_t tr = r + g.ph - g.dh * a;
-        if (tr < 0) continue;
-        const int32_t i = tr / g.sh;
-        if (i * g.sh != tr || i >= g.OH) continue;
-        for (int32_t b = g.kw - 1; b >= 0; --b) {
-            const int32_t tc = c + g.pw - g.dw * b;
-            if (tc < 0) continue;
-            const int32_t j = tc / g.sw;
-            if (j * g.sw != tc || j >= g.OW) continue;
-            const int64_t o = obase + static_cast<int64_t>(i) * g.OW + j;
-            if (argmax[o] == static_cast<uint8_t>(a * g.kw + b)) acc += static_cast<float>(grad_y[o]);
+    if (MC) {
+        // output rows i with 0 <= r + ph - sh*i <= dh*(kh-1), the offset a multiple of dh
+        const int32_t i_hi = static_cast<int32_t>(fastdiv(static_cast<uint32_t>(r + g.ph), g.by_sh));
+        const int32_t j_hi = static_cast<int32_t>(fastdiv(static_cast<uint32_t>(c + g.pw), g.by_sw));
+        uint32_t code[MC ? MC : 1][MC ? MC : 1];
+        float gy[MC ? MC : 1][MC ? MC : 1];
+        int32_t want[MC ? MC : 1][MC ? MC : 1];
+#pragma unroll
+        for (int32_t u = MC - 1; u >= 0; --u)
+#pragma unroll
+            for (int32_t v = MC - 1; v >= 0; --v) {
+                const int32_t i = i_hi - u, j = j_hi - v;
+                const int32_t off_r = r + g.ph - g.sh * i, off_c = c + g.pw - g.sw * j;  // >= 0
+                const int32_t a = static_cast<int32_t>(fastdiv(static_cast<uint32_t>(off_r), g.by_dh));
+                const int32_t b = static_cast<int32_t>(fastdiv(static_cast<uint32_t>(off_c), g.by_dw));
+                const bool ok = i >= 0 && j >= 0 && i < g.OH && j < g.OW && a < g.kh && b < g.kw &&
+                                a * g.dh == off_r && b * g.dw == off_c;
+                const int32_t ic = min(max(i, 0), g.OH - 1), jc = min(max(j, 0), g.OW - 1);
+                code[u][v] = ap[ic * g.OW + jc];
+                gy[u][v] = static_cast<float>(gp[ic * g.OW + jc]);
+                want[u][v] = ok ? a * g.kw + b : -1;
+            }
+        // ascending output row, then column
+#pragma unroll
+        for (int32_t u = MC - 1; u >= 0; --u)
+#pragma unroll
+            for (int32_t v = MC - 1; v >= 0; --v)
+                acc += static_cast<int32_t>(code[u][v]) == want[u][v] ? gy[u][v] : 0.0f;  // + 0 changes nothing
+    } else {
+        for (int32_t a = g.kh - 1; a >= 0; --a) {  // descending window row = ascending output row
+            const int32_t tr = r + g.ph - g.dh * a;
+            if (tr < 0) continue;
+            const int32_t i = static_cast<int32_t>(fastdiv(static_cast<uint32_t>(tr), g.by_sh));
+            if (i * g.sh != tr || i >= g.OH) continue;
+            for (int32_t b = g.kw - 1; b >= 0; --b) {
+                const int32_t tc = c + g.pw - g.dw * b;
+                if (tc < 0) continue;
+                const int32_t j = static_cast<int32_t>(fastdiv(static_cast<uint32_t>(tc), g.by_sw));
+                if (j * g.sw != tc || j >= g.OW) continue;
+                if (ap[i * g.OW + j] == static_cast<uint8_t>(a * g.kw + b)) acc += static_cast<float>(gp[i * g.OW + j]);
+            }
         }
     }
-    grad_x[t] = static_cast<T>(acc);
+    grad_x[plane * g.H * g.W + idx] = static_cast<T>(acc);
 }
 
 }  // namespace
@@ -298,27 +378,57 @@ int launch_relu_backward(const uint8_t* mask, const void* grad_y, int dtype, int
     return launched("actq_relu_backward");
 }
 
-static Pool make_pool(const PoolShape& p)
+static Pool make_pool(const PoolShape& p, int64_t planes, int64_t per_plane, dim3* grid)
 {
     Pool g;
     g.H = p.H; g.W = p.W; g.OH = p.OH; g.OW = p.OW;
     g.kh = p.kh; g.kw = p.kw; g.sh = p.sh; g.sw = p.sw;
     g.ph = p.ph; g.pw = p.pw; g.dh = p.dh; g.dw = p.dw;
+    g.by_OW = make_fastdiv(static_cast<uint32_t>(p.OW));
+    g.by_W = make_fastdiv(static_cast<uint32_t>(p.W));
+    g.by_sh = make_fastdiv(static_cast<uint32_t>(p.sh));
+    g.by_sw = make_fastdiv(static_cast<uint32_t>(p.sw));
+    g.by_dh = make_fastdiv(static_cast<uint32_t>(p.dh));
+    g.by_dw = make_fastdiv(static_cast<uint32_t>(p.dw));
+    const int64_t gy = planes < 65535 ? planes : 65535;
+    g.grid_y = static_cast<uint32_t>(gy);
+    *grid = dim3(static_cast<unsigned>((per_plane + kBlock - 1) / kBlock), static_cast<unsigned>(gy),
+                 static_cast<unsigned>((planes + gy - 1) / gy));
     return g;
+}
+
+template <typename T>
+static void maxpool_forward_typed(const T* x, int64_t planes, const PoolShape& p, T* y, uint8_t* argmax, hipStream_t s)
+{
+    dim3 grid;
+    const Pool g = make_pool(p, planes, static_cast<int64_t>(p.OH) * p.OW, &grid);
+    if (p.kh == 3 && p.kw == 3) maxpool2d_forward_kernel<T, 3, 3><<<grid, kBlock, 0, s>>>(x, planes, g, y, argmax);
+    else if (p.kh == 2 && p.kw == 2) maxpool2d_forward_kernel<T, 2, 2><<<grid, kBlock, 0, s>>>(x, planes, g, y, argmax);
+    else maxpool2d_forward_kernel<T, 0, 0><<<grid, kBlock, 0, s>>>(x, planes, g, y, argmax);
+}
+
+template <typename T>
+static void maxpool_backward_typed(const uint8_t* argmax, const T* grad_y, int64_t planes, const PoolShape& p,
+                                   T* grad_x, hipStream_t s)
+{
+    dim3 grid;
+    const Pool g = make_pool(p, planes, static_cast<int64_t>(p.H) * p.W, &grid);
+    // how many output rows / columns can contain one input location
+    const int64_t reach_h = (static_cast<int64_t>(p.dh) * (p.kh - 1) + p.sh) / p.sh;
+    const int64_t reach_w = (static_cast<int64_t>(p.dw) * (p.kw - 1) + p.sw) / p.sw;
+    const int64_t reach = reach_h > reach_w ? reach_h : reach_w;
+    if (reach <= 1) maxpool2d_backward_kernel<T, 1><<<grid, kBlock, 0, s>>>(argmax, grad_y, planes, g, grad_x);
+    else if (reach == 2) maxpool2d_backward_kernel<T, 2><<<grid, kBlock, 0, s>>>(argmax, grad_y, planes, g, grad_x);
+    else if (reach == 3) maxpool2d_backward_kernel<T, 3><<<grid, kBlock, 0, s>>>(argmax, grad_y, planes, g, grad_x);
+    else maxpool2d_backward_kernel<T, 0><<<grid, kBlock, 0, s>>>(argmax, grad_y, planes, g, grad_x);
 }
 
 int launch_maxpool2d_forward(const void* x, int dtype, int64_t planes, const PoolShape& p, void* y,
                              uint8_t* argmax, void* stream)
 {
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int64_t outputs = planes * p.OH * p.OW;
-    const unsigned blocks = static_cast<unsigned>((outputs + kBlock - 1) / kBlock);
-    if (dtype == ACTQ_F32)
-        maxpool2d_forward_kernel<float><<<blocks, kBlock, 0, s>>>(static_cast<const float*>(x), outputs, make_pool(p),
-                                                                  static_cast<float*>(y), argmax);
-    else
-        maxpool2d_forward_kernel<_Float16><<<blocks, kBlock, 0, s>>>(static_cast<const _Float16*>(x), outputs, make_pool(p),
-                                                                     static_cast<_Float16*>(y), argmax);
+    if (dtype == ACTQ_F32) maxpool_forward_typed(static_cast<const float*>(x), planes, p, static_cast<float*>(y), argmax, s);
+    else maxpool_forward_typed(static_cast<const _Float16*>(x), planes, p, static_cast<_Float16*>(y), argmax, s);
     return launched("actq_maxpool2d_forward");
 }
 
@@ -326,14 +436,10 @@ int launch_maxpool2d_backward(const uint8_t* argmax, const void* grad_y, int dty
                               const PoolShape& p, void* grad_x, void* stream)
 {
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int64_t inputs = planes * p.H * p.W;
-    const unsigned blocks = static_cast<unsigned>((inputs + kBlock - 1) / kBlock);
     if (dtype == ACTQ_F32)
-        maxpool2d_backward_kernel<float><<<blocks, kBlock, 0, s>>>(argmax, static_cast<const float*>(grad_y), inputs,
-                                                                   make_pool(p), static_cast<float*>(grad_x));
+        maxpool_backward_typed(argmax, static_cast<const float*>(grad_y), planes, p, static_cast<float*>(grad_x), s);
     else
-        maxpool2d_backward_kernel<_Float16><<<blocks, kBlock, 0, s>>>(argmax, static_cast<const _Float16*>(grad_y), inputs,
-                                                                      make_pool(p), static_cast<_Float16*>(grad_x));
+        maxpool_backward_typed(argmax, static_cast<const _Float16*>(grad_y), planes, p, static_cast<_Float16*>(grad_x), s);
     return launched("actq_maxpool2d_backward");
 }
 
