@@ -344,6 +344,96 @@ __global__ __launch_bounds__(kBlock) void maxpool2d_backward_kernel(const uint8_
     grad_x[plane * g.H * g.W + idx] = static_cast<T>(acc);
 }
 
+// ------------------------------------------------------------------------------------
+// Backward fast path for the common geometries: square window K in {2, 3}, stride S in {1, 2},
+// dilation 1, any legal padding.  With one element per lane the backward kernel is bound by
+// instruction issue, not by HBM (a wavefront that produces 256 bytes can afford only about two
+// dozen vector instructions), so here a lane produces four consecutive elements of a row: the
+// index arithmetic, the row checks and the loads of the neighbouring outputs are shared, and
+// the result leaves as one 128-bit (binary16: 64-bit) store.  The arithmetic and its order are
+// those of the kernel above.  (The same regrouping of the forward kernel was measured slower:
+// four windows per lane spread every load of the wavefront over four times as many cache lines.)
+
+template <typename T>
+struct Quad;
+template <>
+struct Quad<float> {
+    typedef float vec __attribute__((ext_vector_type(4)));
+};
+template <>
+struct Quad<_Float16> {
+    typedef _Float16 vec __attribute__((ext_vector_type(4)));
+};
+
+struct QuadGeometry {
+    int32_t quads_per_row;  // ceil(row length / 4) of the tensor the kernel produces
+    FastDiv by_quads;
+    uint32_t vector_ok;     // rows are a multiple of 4 long and the outputs are aligned for vector stores
+};
+
+template <typename T, int K, int S>
+__global__ __launch_bounds__(kBlock) void maxpool2d_backward_quad_kernel(const uint8_t* __restrict__ argmax,
+                                                                         const T* __restrict__ grad_y, int64_t planes,
+                                                                         Pool g, QuadGeometry q, T* __restrict__ grad_x)
+{
+    constexpr int LOG_S = S == 2 ? 1 : 0;
+    constexpr int MR = (K - 1) / S + 1;      // output rows whose window can contain one input row
+    constexpr int NJ = (S + K + 1) / S + 1;  // output columns whose window can contain one of four input columns
+    const int64_t plane = static_cast<int64_t>(blockIdx.z) * g.grid_y + blockIdx.y;
+    const uint32_t idx = blockIdx.x * kBlock + threadIdx.x;
+    if (plane >= planes || idx >= static_cast<uint32_t>(g.H * q.quads_per_row)) return;
+    const int32_t r = static_cast<int32_t>(fastdiv(idx, q.by_quads));
+    const int32_t c0 = (static_cast<int32_t>(idx) - r * q.quads_per_row) * 4;
+    const uint8_t* ap = argmax + plane * g.OH * g.OW;
+    const T* gp = grad_y + plane * g.OH * g.OW;
+    // c0 is a multiple of 4 and S divides 4, so the position of column c0 + e inside the window
+    // of output column j_lo + t is the same for every lane: b = spare + (K - 1) + e - S*t
+    const int32_t spare = S == 2 ? ((g.pw - (K - 1)) & 1) : 0;  // (c0 + pw - (K-1)) mod S
+    const int32_t j_lo = (c0 + g.pw - (K - 1) - spare) >> LOG_S;  // exact; arithmetic shift for negative values
+    const int32_t i_hi = (r + g.ph) >> LOG_S;
+    uint32_t code[MR][NJ];
+    float gy[MR][NJ];
+    int32_t row_code[MR];                    // a * K for the row, or a value no stored position can match
+#pragma unroll
+    for (int u = 0; u < MR; ++u) {
+        const int32_t i = i_hi - u;
+        const int32_t a = r + g.ph - S * i;  // >= 0
+        const bool row_ok = i >= 0 && i < g.OH && a < K;
+        row_code[u] = row_ok ? a * K : -1000;
+        const int32_t ic = min(max(i, 0), g.OH - 1);
+#pragma unroll
+        for (int t = 0; t < NJ; ++t) {
+            const int32_t j = j_lo + t;
+            const int32_t jc = min(max(j, 0), g.OW - 1);
+            const bool ok = j >= 0 && j < g.OW;
+            code[u][t] = ok ? static_cast<uint32_t>(ap[ic * g.OW + jc]) : 0xffffu;
+            gy[u][t] = static_cast<float>(gp[ic * g.OW + jc]);
+        }
+    }
+    typename Quad<T>::vec out;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        float acc = 0.0f;
+#pragma unroll
+        for (int u = MR - 1; u >= 0; --u)    // ascending output row
+#pragma unroll
+            for (int t = 0; t < NJ; ++t) {   // ascending output column
+                const int32_t b = spare + (K - 1) + e - S * t;  // the same in every lane
+                if (b < 0 || b >= K) continue;
+                acc += static_cast<int32_t>(code[u][t]) == row_code[u] + b ? gy[u][t] : 0.0f;  // + 0 changes nothing
+            }
+        out[e] = static_cast<T>(acc);
+    }
+    const int64_t o = plane * g.H * g.W + r * g.W + c0;
+    if (q.vector_ok) {
+        __builtin_nontemporal_store(out, reinterpret_cast<typename Quad<T>::vec*>(grad_x + o));
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (c0 + e < g.W) grad_x[o + e] = out[e];
+    }
+}
+
 }  // namespace
 
 int launch_relu_forward(const void* x, int dtype, int64_t n, void* y, uint8_t* mask, void* stream)
@@ -397,6 +487,12 @@ static Pool make_pool(const PoolShape& p, int64_t planes, int64_t per_plane, dim
     return g;
 }
 
+static bool aligned_to(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+static bool quad_geometry(const PoolShape& p) {
+    return p.kh == p.kw && (p.kh == 2 || p.kh == 3) && p.sh == p.sw && (p.sh == 1 || p.sh == 2) && p.dh == 1 && p.dw == 1;
+}
+
 template <typename T>
 static void maxpool_forward_typed(const T* x, int64_t planes, const PoolShape& p, T* y, uint8_t* argmax, hipStream_t s)
 {
@@ -412,6 +508,20 @@ static void maxpool_backward_typed(const uint8_t* argmax, const T* grad_y, int64
                                    T* grad_x, hipStream_t s)
 {
     dim3 grid;
+    if (quad_geometry(p)) {
+        QuadGeometry q;
+        q.quads_per_row = (p.W + 3) / 4;
+        q.by_quads = make_fastdiv(static_cast<uint32_t>(q.quads_per_row));
+        q.vector_ok = p.W % 4 == 0 && aligned_to(grad_x, 4 * sizeof(T));
+        const Pool g = make_pool(p, planes, static_cast<int64_t>(p.H) * q.quads_per_row, &grid);
+#define ACTQ_POOL_BWD(K, S) maxpool2d_backward_quad_kernel<T, K, S><<<grid, kBlock, 0, s>>>(argmax, grad_y, planes, g, q, grad_x)
+        if (p.kh == 3 && p.sh == 2) ACTQ_POOL_BWD(3, 2);
+        else if (p.kh == 3) ACTQ_POOL_BWD(3, 1);
+        else if (p.sh == 2) ACTQ_POOL_BWD(2, 2);
+        else ACTQ_POOL_BWD(2, 1);
+#undef ACTQ_POOL_BWD
+        return;
+    }
     const Pool g = make_pool(p, planes, static_cast<int64_t>(p.H) * p.W, &grid);
     // how many output rows / columns can contain one input location
     const int64_t reach_h = (static_cast<int64_t>(p.dh) * (p.kh - 1) + p.sh) / p.sh;

@@ -89,7 +89,13 @@ CONFIGS = [
     ((3,), 33, 65, (3, 3), (2, 2), (1, 1), (1, 1)),
     ((2,), 40, 37, (7, 5), (5, 3), (3, 2), (1, 1)),
     ((2,), 29, 31, (4, 6), (7, 6), (2, 3), (3, 2)),
-    ((70000,), 4, 4, (2, 2), (2, 2), (0, 0), (1, 1)),     # more planes than one grid dimension holds
+    ((70000,), 4, 4, (2, 2), (2, 2), (0, 0), (1, 1)),
+    ((3,), 12, 16, (3, 3), (1, 1), (1, 1), (1, 1)),     # fast path, stride 1
+    ((3,), 11, 13, (2, 2), (1, 1), (1, 1), (1, 1)),
+    ((3,), 14, 20, (2, 2), (2, 2), (1, 1), (1, 1)),
+    ((3,), 15, 19, (3, 3), (2, 2), (0, 0), (1, 1)),
+    ((2,), 17, 24, (3, 3), (2, 2), (1, 0), (1, 1)),
+     # more planes than one grid dimension holds
 ]
 
 
