@@ -95,6 +95,12 @@ def lib() -> ctypes.CDLL:
         L.orc_maxpool2d_forward.argtypes = [vp, c.c_int, i64] + [i32] * 10 + [vp, vp]
         L.orc_maxpool2d_backward.restype = c.c_int
         L.orc_maxpool2d_backward.argtypes = [vp, vp, c.c_int, i64] + [i32] * 10 + [vp]
+        L.orc_tensor_stats.restype = c.c_int
+        L.orc_tensor_stats.argtypes = [vp, c.c_int, i64, vp]
+        L.orc_quantize_pack_tensor.restype = c.c_int
+        L.orc_quantize_pack_tensor.argtypes = [vp, c.c_int, i64, i64, c.c_int32, vp, vp, u64, u64, c.c_int32, vp, vp]
+        L.orc_unpack_dequantize_tensor.restype = c.c_int
+        L.orc_unpack_dequantize_tensor.argtypes = [vp, vp, vp, vp, i64, i64, c.c_int32, vp, c.c_int]
         L.orc_objective.restype = c.c_double
         L.orc_objective.argtypes = [vp, vp, i64]
         _lib = L
@@ -390,3 +396,43 @@ def maxpool2d_backward(argmax: np.ndarray, grad_y: np.ndarray, H: int, W: int, k
     if rc != OK:
         raise OracleError(rc, "maxpool2d_backward")
     return gx
+
+
+# ----------------------------------------------------------------------------- per-tensor baseline
+
+def tensor_stats(x: np.ndarray) -> np.ndarray:
+    """float32 [2]: (Z, R) = (min, max - min) over the whole tensor."""
+    x = np.ascontiguousarray(x)
+    zr = np.empty(2, dtype=np.float32)
+    rc = lib().orc_tensor_stats(_p(x), _dtype_code(x), x.size, _p(zr))
+    if rc != OK:
+        raise OracleError(rc, "tensor_stats")
+    return zr
+
+
+def quantize_pack_tensor(x: np.ndarray, bits, zr, seed: int, tag: int = 0, G: int = 256, noise_bits: int = 24):
+    """Per-tensor quantizer: one (Z, R) for all groups.  Returns (packed, offsets)."""
+    x = _as2d(x)
+    N, D = x.shape
+    bits = np.ascontiguousarray(bits, dtype=np.uint8)
+    zr = np.ascontiguousarray(zr, dtype=np.float32)
+    offsets, total = packed_bytes(N, D, G, bits)
+    packed = np.zeros(total, dtype=np.uint8)
+    rc = lib().orc_quantize_pack_tensor(_p(x), _dtype_code(x), N, D, G, _p(bits), _p(offsets), seed, tag,
+                                        noise_bits, _p(zr), _p(packed))
+    if rc != OK:
+        raise OracleError(rc, "quantize_pack_tensor")
+    return packed, offsets
+
+
+def unpack_dequantize_tensor(packed, zr, bits, offsets, N: int, D: int, G: int = 256, out_dtype=np.float32):
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    zr = np.ascontiguousarray(zr, dtype=np.float32)
+    bits = np.ascontiguousarray(bits, dtype=np.uint8)
+    offsets = np.ascontiguousarray(offsets, dtype=np.uint64)
+    out = np.empty((N, D), dtype=out_dtype)
+    rc = lib().orc_unpack_dequantize_tensor(_p(packed), _p(zr), _p(bits), _p(offsets), N, D, G, _p(out),
+                                            _dtype_code(out))
+    if rc != OK:
+        raise OracleError(rc, "unpack_dequantize_tensor")
+    return out

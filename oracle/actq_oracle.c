@@ -699,3 +699,71 @@ int orc_maxpool2d_backward(const uint8_t* argmax, const void* grad_y, int dtype,
     }
     return bad ? ORC_EINVAL : ORC_OK;
 }
+
+/* ------------------------------------------------------------------------- */
+/* Sec. 4.1 (the comparison made there) and Sec. 6.1 (the per-tensor baseline): */
+/* one range and one zero point for the whole tensor, i.e. a single group.      */
+/* Z = min over all elements, R = max - min; everything else (scaling, rounding, */
+/* the bit stream, the widths per sample) is as in the per-group quantizer.      */
+
+int orc_tensor_stats(const void* x, int dtype, int64_t n, float* zr)
+{
+    if (!x || !zr || n <= 0 || (dtype != 0 && dtype != 1)) return ORC_EINVAL;
+    float mn, range;
+    group_min_range(x, dtype, 0, n, &mn, &range);
+    zr[0] = mn;
+    zr[1] = range;
+    return ORC_OK;
+}
+
+int orc_quantize_pack_tensor(const void* x, int dtype, int64_t N, int64_t D, int32_t G,
+                             const uint8_t* bits, const uint64_t* offsets, uint64_t seed, uint64_t tag,
+                             int32_t noise_bits, const float* zr, uint8_t* packed)
+{
+    if (!x || !bits || !offsets || !packed || !zr) return ORC_EINVAL;
+    if (N <= 0 || D <= 0 || G <= 0 || (G % 8) != 0) return ORC_EINVAL;
+    if (noise_bits != 24 && noise_bits != 16) return ORC_EINVAL;
+    for (int64_t n = 0; n < N; ++n)
+        if (!width_ok(bits[n])) return ORC_EINVAL;
+    int64_t ng = (D + G - 1) / G;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < N * ng; ++t) {
+        int64_t n = t / ng, g = t % ng;
+        int b = bits[n];
+        float B = (float)((1 << b) - 1);
+        float inv, scale;
+        group_scale(B, zr[1], &inv, &scale);
+        int64_t len = (g * G + G <= D) ? G : D - g * G;
+        uint8_t* dst = packed + offsets[n] + (uint64_t)g * G * b / 8;
+        memset(dst, 0, (size_t)G * b / 8);
+        for (int64_t j = 0; j < len; ++j) {
+            float h = load_elem(x, dtype, n * D + g * G + j);
+            float noise = orc_noise(seed, tag, (uint32_t)n, (uint64_t)(g * G + j), noise_bits);
+            put_code(dst, j, b, stochastic_code(h, zr[0], inv, B, noise, noise_bits));
+        }
+    }
+    return ORC_OK;
+}
+
+int orc_unpack_dequantize_tensor(const uint8_t* packed, const float* zr, const uint8_t* bits,
+                                 const uint64_t* offsets, int64_t N, int64_t D, int32_t G,
+                                 void* out, int out_dtype)
+{
+    if (!packed || !zr || !bits || !offsets || !out) return ORC_EINVAL;
+    if (N <= 0 || D <= 0 || G <= 0 || (G % 8) != 0) return ORC_EINVAL;
+    for (int64_t n = 0; n < N; ++n)
+        if (!width_ok(bits[n])) return ORC_EINVAL;
+    int64_t ng = (D + G - 1) / G;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < N * ng; ++t) {
+        int64_t n = t / ng, g = t % ng;
+        int b = bits[n];
+        float hd[2], inv;
+        hd[0] = zr[0];
+        group_scale((float)((1 << b) - 1), zr[1], &inv, &hd[1]); /* the step R / B of this width */
+        int64_t len = (g * G + G <= D) ? G : D - g * G;
+        const uint8_t* src = packed + offsets[n] + (uint64_t)g * G * b / 8;
+        orc_dequantize_group(src, hd, b, len, out, out_dtype, n * D + g * G);
+    }
+    return ORC_OK;
+}
