@@ -50,9 +50,13 @@ typedef enum actq_dtype {
 /* Per-group header kept beside the codes. */
 typedef enum actq_header_format {
     ACTQ_HDR_F32 = 0, /* (Z, R/B) in binary32: 8 bytes per group, 0.25 bit per element at G = 256 */
-    ACTQ_HDR_BF16 = 1 /* (Z, R) in bfloat16 as in Sec. 4.1: 4 bytes per group, 0.125 bit per
+    ACTQ_HDR_BF16 = 1, /* (Z, R) in bfloat16 as in Sec. 4.1: 4 bytes per group, 0.125 bit per
                          element.  Z is rounded down to bfloat16 and R = max - Z is rounded up, so
                          every element still scales into [0, B]; a degenerate group stores R = 0 */
+    ACTQ_HDR_TENSOR = 2 /* one pair (Z, R) in binary32 for the whole tensor, 8 bytes in all: the
+                           per-tensor baseline the paper compares with (Sec. 4.1, Sec. 6.1).  The
+                           pair is an INPUT of actq_quantize_pack, written beforehand by
+                           actq_tensor_stats (or by the caller: it must cover every element) */
 } actq_header_format;
 
 /* Library version, major*10000 + minor*100 + patch. */
@@ -84,7 +88,7 @@ const char* actq_last_error(void);
 int actq_packed_bytes(int64_t N, int64_t D, int32_t G, const uint8_t* bits_host,
                       uint64_t* offsets_host, uint64_t* total_host);
 
-/* Bytes of the header array for N*ng groups in format hf (host arithmetic only). */
+/* Bytes of the header for N*ng groups in format hf (host arithmetic only; 8 for ACTQ_HDR_TENSOR). */
 int actq_header_bytes(int64_t N, int64_t D, int32_t G, actq_header_format hf, uint64_t* bytes_host);
 
 /*
@@ -92,7 +96,7 @@ int actq_header_bytes(int64_t N, int64_t D, int32_t G, actq_header_format hf, ui
  *
  * x      device, in  : N*D elements of dtype `dt`
  * gmin   device, out : [N*ng] float, Z of every group; -0.0 is stored as +0.0
- * grange device, out : [N*ng] float, R = max - min rounded to nearest
+ * grange device, out : [N*ng] float, R = max - min rounded to nearest; a zero range is +0.0
  * Only the valid elements of a ragged group take part.
  */
 int actq_group_stats(const void* x, actq_dtype dt, int64_t N, int64_t D, int32_t G,
@@ -127,7 +131,8 @@ int actq_group_stats(const void* x, actq_dtype dt, int64_t N, int64_t D, int32_t
  * offsets  device, in  : [N] byte offsets as produced by actq_packed_bytes
  * packed   device, out : the bit stream; `packed_capacity` bytes are writable
  * header   device, out : [N*ng] groups in format hf: {float Z, float scale} or
- *                        {uint16 Z, uint16 R} (bfloat16 bit patterns), 8-byte aligned
+ *                        {uint16 Z, uint16 R} (bfloat16 bit patterns), 8-byte aligned;
+ *                        with ACTQ_HDR_TENSOR it is device, IN: one {float Z, float R}
  *
  * bits and offsets live on the device, so the host cannot check them: a sample
  * whose width is not in 1..8 or whose byte range would leave
@@ -157,6 +162,18 @@ int actq_unpack_dequantize(const void* packed, uint64_t packed_capacity,
                            const void* header, actq_header_format hf, const uint8_t* bits,
                            const uint64_t* offsets, int64_t N, int64_t D, int32_t G,
                            void* out, actq_dtype out_dt, void* stream);
+
+/*
+ * Range and zero point of a whole tensor (the single-group quantizer of Sec. 4.1's
+ * comparison): zr[0] = Z = min over all n elements (-0.0 stored as +0.0),
+ * zr[1] = R = max - min rounded to nearest.  The pair is the header of
+ * ACTQ_HDR_TENSOR.  Three small launches on `stream`; the result does not depend
+ * on the order in which the hardware combines partial results.
+ *
+ * x  device, in  : n elements of dtype dt, 16-byte aligned, n in [1, 2^40)
+ * zr device, out : two floats, 8-byte aligned
+ */
+int actq_tensor_stats(const void* x, actq_dtype dt, int64_t n, float* zr, void* stream);
 
 /*
  * Per-sample sensitivity of a linear layer (Sec. 4.2, Eq. (8) and the sentence

@@ -182,7 +182,9 @@ static void group_min_range(const void* x, int dtype, int64_t base, int64_t len,
     }
     mn = mn + 0.0f; /* -0.0 becomes +0.0: one canonical stored zero point */
     *mn_out = mn;
-    *range_out = mx - mn;
+    /* a range of zero is +0.0 whichever zeros the extremes were (the maximum of -0.0 and +0.0 is
+     * either of them) */
+    *range_out = (mx - mn) + 0.0f;
 }
 
 int orc_group_stats(const void* x, int dtype, int64_t N, int64_t D, int32_t G,

@@ -19,13 +19,13 @@ ACTQ_OK, ACTQ_EINVAL, ACTQ_EINFEASIBLE, ACTQ_EHIP = 0, -1, -2, -3
 ACTQ_F32, ACTQ_F16 = 0, 1
 G_DEFAULT = 256
 
-ACTQ_HDR_F32, ACTQ_HDR_BF16 = 0, 1
+ACTQ_HDR_F32, ACTQ_HDR_BF16, ACTQ_HDR_TENSOR = 0, 1, 2
 ACTQ_WIDTHS_POW2, ACTQ_WIDTHS_ALL = 0x116, 0x1FE  # allowed-width sets of the allocator (bit b = b bits)
 
 EXPORTS = ("actq_version", "actq_last_error", "actq_packed_bytes", "actq_header_bytes", "actq_group_stats",
            "actq_quantize_pack", "actq_unpack_dequantize", "actq_sample_sensitivity", "actq_allocate_bits",
            "actq_allocate_bits_device", "actq_relu_mask_bytes", "actq_relu_forward", "actq_relu_backward",
-           "actq_pool2d_output_size", "actq_maxpool2d_forward", "actq_maxpool2d_backward")
+           "actq_pool2d_output_size", "actq_maxpool2d_forward", "actq_maxpool2d_backward", "actq_tensor_stats")
 
 
 class ActqError(RuntimeError):
@@ -66,6 +66,8 @@ def lib() -> ctypes.CDLL:
     L.actq_sample_sensitivity.argtypes = [vp, i64, i64, i32, vp, vp, vp]
     L.actq_allocate_bits.restype = c.c_int
     L.actq_allocate_bits.argtypes = [vp, vp, i64, i64, c.c_uint32, vp]
+    L.actq_tensor_stats.restype = c.c_int
+    L.actq_tensor_stats.argtypes = [vp, c.c_int, i64, vp, vp]
     L.actq_relu_mask_bytes.restype = c.c_int
     L.actq_relu_mask_bytes.argtypes = [i64, vp]
     L.actq_relu_forward.restype = c.c_int
@@ -167,18 +169,19 @@ def header_bytes(N: int, D: int, hf: int = ACTQ_HDR_F32, G: int = G_DEFAULT) -> 
 
 def _header_ptr(header, N, ng, hf):
     torch = _torch()
-    want = torch.float32 if hf == ACTQ_HDR_F32 else torch.int16
+    want = torch.int16 if hf == ACTQ_HDR_BF16 else torch.float32
     if header.dtype != want:
         raise TypeError(f"header must be {want} for this header format, got {header.dtype}")
-    if header.numel() != N * ng * 2:
-        raise ValueError("header must hold N*ng*2 entries")
+    if header.numel() != (2 if hf == ACTQ_HDR_TENSOR else N * ng * 2):
+        raise ValueError("header must hold N*ng*2 entries (2 for ACTQ_HDR_TENSOR)")
     return _dev(header, want, "header")
 
 
 def quantize_pack(x, bits, offsets, packed, header, seed: int, tag: int = 0, noise_bits: int = 24,
                   G: int = G_DEFAULT, stream=None, hf: int = ACTQ_HDR_F32):
     """Device: writes the bit stream into `packed` (uint8) and the group headers into `header`
-    (float32 [N*ng*2] for ACTQ_HDR_F32, int16 [N*ng*2] bfloat16 bit patterns for ACTQ_HDR_BF16)."""
+    (float32 [N*ng*2] for ACTQ_HDR_F32, int16 [N*ng*2] bfloat16 bit patterns for ACTQ_HDR_BF16).
+    With ACTQ_HDR_TENSOR `header` is the float32 [2] pair from tensor_stats and is only read."""
     torch = _torch()
     N, D = _view2d(x)
     ng = (D + G - 1) // G
@@ -347,3 +350,15 @@ def maxpool2d_backward(argmax, grad_y, H, W, kernel, stride, padding=(0, 0), dil
                                          _dtype_code(grad_y), planes, H, W, *kernel, *stride, *padding, *dilation,
                                          _dev(grad_x, None, "grad_x"), _stream(stream)))
     return grad_x
+
+
+def tensor_stats(x, zr=None, stream=None):
+    """Device: (Z, R) = (min, max - min) of the whole tensor, float32 [2]: the header of ACTQ_HDR_TENSOR."""
+    torch = _torch()
+    if zr is None:
+        zr = torch.empty(2, dtype=torch.float32, device=x.device)
+    if zr.numel() != 2:
+        raise ValueError("zr must have two entries")
+    _check(lib().actq_tensor_stats(_dev(x, None, "x"), _dtype_code(x), int(x.numel()), _dev(zr, torch.float32, "zr"),
+                                   _stream(stream)))
+    return zr

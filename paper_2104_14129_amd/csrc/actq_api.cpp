@@ -43,7 +43,7 @@ static int check_view(const char* who, int64_t N, int64_t D, int32_t G)
 
 static int check_header(const char* who, int hf)
 {
-    if (hf != ACTQ_HDR_F32 && hf != ACTQ_HDR_BF16) return fail(ACTQ_EINVAL, "%s: unknown header format %d", who, hf);
+    if (hf != ACTQ_HDR_F32 && hf != ACTQ_HDR_BF16 && hf != ACTQ_HDR_TENSOR) return fail(ACTQ_EINVAL, "%s: unknown header format %d", who, hf);
     return ACTQ_OK;
 }
 
@@ -89,7 +89,7 @@ int actq_header_bytes(int64_t N, int64_t D, int32_t G, actq_header_format hf, ui
     if (int rc = check_header("actq_header_bytes", hf)) return rc;
     if (!bytes_host) return fail(ACTQ_EINVAL, "actq_header_bytes: null output");
     const uint64_t ng = static_cast<uint64_t>((D + G - 1) / G);
-    *bytes_host = static_cast<uint64_t>(N) * ng * (hf == ACTQ_HDR_BF16 ? 4u : 8u);
+    *bytes_host = hf == ACTQ_HDR_TENSOR ? 8u : static_cast<uint64_t>(N) * ng * (hf == ACTQ_HDR_BF16 ? 4u : 8u);
     return ACTQ_OK;
 }
 
@@ -250,6 +250,16 @@ int actq_allocate_bits_device(const float* w, const int64_t* D_items, int64_t D,
     if (!actq::make_ladder(widths, &lad))
         return fail(ACTQ_EINVAL, "actq_allocate_bits_device: widths mask 0x%x must be a non-empty subset of bits 1..8", widths);
     return launch_allocate_bits(w, D_items, D, M, budget_bits, lad, bits, offsets, result, stream);
+}
+
+int actq_tensor_stats(const void* x, actq_dtype dt, int64_t n, float* zr, void* stream)
+{
+    if (int rc = check_dtype("actq_tensor_stats", dt)) return rc;
+    if (!x || !zr) return fail(ACTQ_EINVAL, "actq_tensor_stats: null pointer");
+    if (n <= 0 || n >= (int64_t(1) << 40)) return fail(ACTQ_EINVAL, "actq_tensor_stats: n must be in [1, 2^40)");
+    if (!aligned(x, 16)) return fail(ACTQ_EINVAL, "actq_tensor_stats: x must be 16-byte aligned");
+    if (!aligned(zr, 8)) return fail(ACTQ_EINVAL, "actq_tensor_stats: zr must be 8-byte aligned");
+    return launch_tensor_stats(x, dt, n, zr, stream);
 }
 
 int actq_relu_mask_bytes(int64_t n, uint64_t* bytes_host)

@@ -31,6 +31,7 @@ int launch_quantize_pack(const void* x, int dtype, int64_t N, int64_t D, const u
 int launch_unpack_dequantize(const void* packed, uint64_t capacity, const void* header, int hdr,
                              const uint8_t* bits, const uint64_t* offsets, int64_t N,
                              int64_t D, void* out, int out_dtype, void* stream);
+int launch_tensor_stats(const void* x, int dtype, int64_t n, float* zr, void* stream);
 int launch_sample_sensitivity(const float* grange, int64_t N, int64_t ng, int32_t G,
                               const float* grad2, float* w, void* stream);
 int launch_allocate_bits(const float* w, const int64_t* D_items, int64_t D, int64_t M, int64_t budget_bits,

@@ -190,7 +190,7 @@ struct Geometry {
     uint32_t tiles_per_sample;  // ceil(ng / 4)
     uint32_t tiles_per_wave;    // consecutive tiles handled by one wavefront
     uint32_t grid_y;            // samples per grid.z slice
-    uint32_t hdr_bf16;          // header format: 0 = (Z, R/B) binary32, 1 = (Z, R) bfloat16
+    uint32_t hdr_mode;          // header: 0 = (Z, R/B) binary32, 1 = (Z, R) bfloat16, 2 = one (Z, R) for the tensor
 };
 
 // First tile (inside its sample) and sample of this wavefront; false if it has no work.
@@ -279,10 +279,20 @@ __device__ __forceinline__ uint32_t bf16_ceil_bits(float f)
 }
 
 // (Z, scale = R / B) of group `index` from either header format.
-template <bool BF16>
+// Header of group `index` as (Z, step R / B).  HDR: 0 = stored as such in binary32; 1 = (Z, R) in
+// bfloat16; 2 = one (Z, R) pair in binary32 for the whole tensor, the step being 0 when R is 0
+// or B / R overflows (the degenerate rule of the quantizer).
+template <int HDR>
 __device__ __forceinline__ f32x2 load_header(const void* __restrict__ header, int64_t index, float kB)
 {
-    if (BF16) {
+    if (HDR == 2) {
+        const f32x2 zr = static_cast<const f32x2*>(header)[0];
+        f32x2 h;
+        h.x = zr.x;
+        h.y = (zr.y != 0.0f && __builtin_isfinite(kB / zr.y)) ? zr.y / kB : 0.0f;
+        return h;
+    }
+    if (HDR == 1) {
         const uint32_t w = static_cast<const uint32_t*>(header)[index];
         f32x2 h;
         h.x = __uint_as_float(w << 16);
@@ -319,7 +329,7 @@ __global__ __launch_bounds__(kBlock) void group_stats_kernel(const T* __restrict
         if ((lane & 15) == 0 && row < groups) {
             const int64_t gi = static_cast<int64_t>(n) * geo.ng + g0 + row;
             gmin[gi] = mn;
-            grange[gi] = mx - mn;
+            grange[gi] = (mx - mn) + 0.0f;  // a zero range is +0.0 whichever zeros the extremes were
         }
     }
 }
@@ -386,14 +396,20 @@ __device__ __forceinline__ void encode_tile(const TileRegs& td, const uint32_t (
                                             float row_min, float row_max, uint32_t n, uint32_t g0,
                                             int groups, uint32_t ng, int lane,
                                             uint8_t* __restrict__ dst_sample,
-                                            void* __restrict__ header, bool hdr_bf16, uint32_t* stage)
+                                            void* __restrict__ header, uint32_t hdr_mode, uint32_t* stage)
 {
     constexpr float kB = static_cast<float>((1 << B) - 1);
     constexpr float kNoiseGrid = 16777216.0f;  // 24-bit noise is compared as an integer with frac * 2^24
+    const bool hdr_bf16 = hdr_mode == 1, hdr_tensor = hdr_mode == 2;
     float mn = row_min;
     float range;
     uint32_t zb = 0, rb = 0;
-    if (hdr_bf16) {
+    if (hdr_tensor) {
+        // one (Z, R) for the whole tensor, given by the caller: the group's own extremes are not used
+        const f32x2 zr = static_cast<const f32x2*>(header)[0];
+        mn = zr.x;
+        range = zr.y;
+    } else if (hdr_bf16) {
         zb = bf16_floor_bits(mn);
         mn = __uint_as_float(zb << 16);
         rb = bf16_ceil_bits(row_max - mn);
@@ -410,7 +426,7 @@ __device__ __forceinline__ void encode_tile(const TileRegs& td, const uint32_t (
         rb = 0;
     }
     const int row = lane >> 4;
-    if ((lane & 15) == 0 && row < groups) {
+    if (!hdr_tensor && (lane & 15) == 0 && row < groups) {
         const int64_t gi = static_cast<int64_t>(n) * ng + g0 + row;
         if (hdr_bf16) {
             __builtin_nontemporal_store(zb | (rb << 16), static_cast<uint32_t*>(header) + gi);
@@ -522,7 +538,7 @@ struct StreamGeometry {
     uint32_t tiles_per_sample;
     uint32_t total_tiles;
     uint32_t step_n, step_t;  // waves = step_n * tiles_per_sample + step_t
-    uint32_t hdr_bf16;        // header format: 0 = (Z, R/B) binary32, 1 = (Z, R) bfloat16
+    uint32_t hdr_mode;        // header: 0 = (Z, R/B) binary32 per group, 1 = (Z, R) bfloat16 per group, 2 = one (Z, R) given
 };
 
 // Position of a wavefront in its sequence of tiles, with the scalar facts of the sample.
@@ -582,14 +598,14 @@ __device__ __forceinline__ void quantize_one(const TileRegs& r, const Cursor& c,
     if ((off & 31u) != 0 || off > capacity || bytes > capacity - off) return;
     uint8_t* dst = packed + off;
     switch (b) {
-        case 1: encode_tile<NOISE_BITS, VEC, 1>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, geo.hdr_bf16 != 0, stage); break;
-        case 2: encode_tile<NOISE_BITS, VEC, 2>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, geo.hdr_bf16 != 0, stage); break;
-        case 3: encode_tile<NOISE_BITS, VEC, 3>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, geo.hdr_bf16 != 0, stage); break;
-        case 4: encode_tile<NOISE_BITS, VEC, 4>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, geo.hdr_bf16 != 0, stage); break;
-        case 5: encode_tile<NOISE_BITS, VEC, 5>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, geo.hdr_bf16 != 0, stage); break;
-        case 6: encode_tile<NOISE_BITS, VEC, 6>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, geo.hdr_bf16 != 0, stage); break;
-        case 7: encode_tile<NOISE_BITS, VEC, 7>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, geo.hdr_bf16 != 0, stage); break;
-        case 8: encode_tile<NOISE_BITS, VEC, 8>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, geo.hdr_bf16 != 0, stage); break;
+        case 1: encode_tile<NOISE_BITS, VEC, 1>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, geo.hdr_mode, stage); break;
+        case 2: encode_tile<NOISE_BITS, VEC, 2>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, geo.hdr_mode, stage); break;
+        case 3: encode_tile<NOISE_BITS, VEC, 3>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, geo.hdr_mode, stage); break;
+        case 4: encode_tile<NOISE_BITS, VEC, 4>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, geo.hdr_mode, stage); break;
+        case 5: encode_tile<NOISE_BITS, VEC, 5>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, geo.hdr_mode, stage); break;
+        case 6: encode_tile<NOISE_BITS, VEC, 6>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, geo.hdr_mode, stage); break;
+        case 7: encode_tile<NOISE_BITS, VEC, 7>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, geo.hdr_mode, stage); break;
+        case 8: encode_tile<NOISE_BITS, VEC, 8>(r, rnd, row_min, row_max, c.n, g0, groups, geo.ng, lane, dst, header, geo.hdr_mode, stage); break;
         default: break;
     }
 }
@@ -657,7 +673,7 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_tile_kernel(
 // ------------------------------------------------------------------------------------
 // Sec. 4.1: h^ = code * scale + Z.
 
-template <typename T, bool VEC, int B, bool BF16>
+template <typename T, bool VEC, int B, int HDR>
 __device__ __forceinline__ void dequantize_tile(const uint8_t* __restrict__ src_sample,
                                                 const void* __restrict__ header, T* os,
                                                 int64_t D, uint32_t n, uint32_t g0, int groups, uint32_t ng,
@@ -687,7 +703,7 @@ __device__ __forceinline__ void dequantize_tile(const uint8_t* __restrict__ src_
 #pragma unroll
         for (int u = 0; u < kTileGroups; ++u)
             if (u < groups)
-                hd[u] = load_header<BF16>(header, static_cast<int64_t>(n) * ng + g0 + u, static_cast<float>(code_mask));
+                hd[u] = load_header<HDR>(header, static_cast<int64_t>(n) * ng + g0 + u, static_cast<float>(code_mask));
 #pragma unroll
         for (int j = 0; j < kLoads; ++j) stage[j * 64 + lane] = in[j];  // at most 256 words
         wave_lds_handover();
@@ -705,7 +721,7 @@ __device__ __forceinline__ void dequantize_tile(const uint8_t* __restrict__ src_
             const uint32_t g = g0 + u;
             const uint32_t* src = reinterpret_cast<const uint32_t*>(src_sample + static_cast<uint64_t>(g) * (32 * B));
             word[u] = __builtin_nontemporal_load(src + first_word);
-            hd[u] = load_header<BF16>(header, static_cast<int64_t>(n) * ng + g, static_cast<float>(code_mask));
+            hd[u] = load_header<HDR>(header, static_cast<int64_t>(n) * ng + g, static_cast<float>(code_mask));
         }
     }
 #pragma unroll
@@ -734,7 +750,7 @@ __device__ __forceinline__ void dequantize_tile(const uint8_t* __restrict__ src_
 // takes eight consecutive elements (16 bytes) and the wavefront covers two groups per step
 // (lanes 0..31 the even group, lanes 32..63 the odd one).  Unpacking is free to choose its
 // lane-to-element map: nothing is reduced across lanes.
-template <bool VEC, int B, bool BF16>
+template <bool VEC, int B, int HDR>
 __device__ __forceinline__ void dequantize_tile_f16(const uint8_t* __restrict__ src_sample,
                                                     const void* __restrict__ header,
                                                     _Float16* os, int64_t D, uint32_t n, uint32_t g0,
@@ -761,7 +777,7 @@ __device__ __forceinline__ void dequantize_tile_f16(const uint8_t* __restrict__ 
             code_lo[p] = w.x;
             code_hi[p] = w.y;
         }
-        hd[p] = load_header<BF16>(header, static_cast<int64_t>(n) * ng + g, static_cast<float>(code_mask));
+        hd[p] = load_header<HDR>(header, static_cast<int64_t>(n) * ng + g, static_cast<float>(code_mask));
     }
 #pragma unroll
     for (int p = 0; p < 2; ++p) {
@@ -785,19 +801,19 @@ __device__ __forceinline__ void dequantize_tile_f16(const uint8_t* __restrict__ 
     }
 }
 
-template <typename T, bool VEC, int B, bool BF16>
+template <typename T, bool VEC, int B, int HDR>
 __device__ __forceinline__ void dequantize_any(const uint8_t* __restrict__ src_sample,
                                                const void* __restrict__ header, T* os,
                                                int64_t D, uint32_t n, uint32_t g0, int groups, uint32_t ng, int lane,
                                                uint32_t* stage)
 {
     if constexpr (sizeof(T) == 2 && (8 % B) == 0)
-        dequantize_tile_f16<VEC, B, BF16>(src_sample, header, os, D, n, g0, groups, ng, lane);
+        dequantize_tile_f16<VEC, B, HDR>(src_sample, header, os, D, n, g0, groups, ng, lane);
     else
-        dequantize_tile<T, VEC, B, BF16>(src_sample, header, os, D, n, g0, groups, ng, lane, stage);
+        dequantize_tile<T, VEC, B, HDR>(src_sample, header, os, D, n, g0, groups, ng, lane, stage);
 }
 
-template <typename T, bool VEC, bool BF16>
+template <typename T, bool VEC, int HDR>
 __global__ __launch_bounds__(kBlock) void unpack_dequantize_kernel(
     const uint8_t* __restrict__ packed, uint64_t capacity, const void* __restrict__ header,
     const uint8_t* __restrict__ bits, const uint64_t* __restrict__ offsets, Geometry geo,
@@ -818,16 +834,104 @@ __global__ __launch_bounds__(kBlock) void unpack_dequantize_kernel(
         const uint32_t g0 = tile * kTileGroups;
         const int groups = static_cast<int>(min(static_cast<uint32_t>(kTileGroups), geo.ng - g0));
         switch (b) {
-            case 1: dequantize_any<T, VEC, 1, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
-            case 2: dequantize_any<T, VEC, 2, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
-            case 3: dequantize_any<T, VEC, 3, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
-            case 4: dequantize_any<T, VEC, 4, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
-            case 5: dequantize_any<T, VEC, 5, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
-            case 6: dequantize_any<T, VEC, 6, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
-            case 7: dequantize_any<T, VEC, 7, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
-            case 8: dequantize_any<T, VEC, 8, BF16>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
+            case 1: dequantize_any<T, VEC, 1, HDR>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
+            case 2: dequantize_any<T, VEC, 2, HDR>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
+            case 3: dequantize_any<T, VEC, 3, HDR>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
+            case 4: dequantize_any<T, VEC, 4, HDR>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
+            case 5: dequantize_any<T, VEC, 5, HDR>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
+            case 6: dequantize_any<T, VEC, 6, HDR>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
+            case 7: dequantize_any<T, VEC, 7, HDR>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
+            case 8: dequantize_any<T, VEC, 8, HDR>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
             default: return;
         }
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// One range and zero point for the whole tensor (the per-tensor baseline of Sec. 4.1 and
+// Sec. 6.1): Z = min, R = max - min over all elements.  Three tiny launches on the caller's
+// stream: set the two result words to the identity, reduce (a fixed number of wavefronts
+// stride over the tensor; each block folds its minimum and maximum and issues two atomics),
+// and convert.  Minimum and maximum do not depend on the order of the operations, so the
+// atomics do not make the result vary.  While the reduction runs the two words hold order-
+// preserving integer images of the floats (sign bit flipped for non-negative values, all
+// bits flipped for negative ones), on which unsigned min / max order like the floats.
+
+__device__ __forceinline__ uint32_t float_to_ordered(float f)
+{
+    const uint32_t u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ __forceinline__ float ordered_to_float(uint32_t k)
+{
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+
+__global__ void tensor_stats_init_kernel(uint32_t* zr)
+{
+    if (threadIdx.x == 0) {
+        zr[0] = 0xffffffffu;  // above every value's image
+        zr[1] = 0u;           // below every value's image
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kBlock) void tensor_stats_reduce_kernel(const T* __restrict__ x, int64_t n, uint32_t* zr)
+{
+    __shared__ float part_lo[kWavesPerBlock], part_hi[kWavesPerBlock];
+    constexpr int kE = 16 / sizeof(T);  // elements per 128-bit load
+    const int64_t chunks = n / kE;      // whole 128-bit chunks; x is 16-byte aligned
+    float lo = __builtin_inff(), hi = -__builtin_inff();
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    for (int64_t c = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; c < chunks; c += stride) {
+        if constexpr (sizeof(T) == 4) {
+            const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(x) + c);
+            lo = fminf(fminf(lo, v.x), fminf(fminf(v.y, v.z), v.w));
+            hi = fmaxf(fmaxf(hi, v.x), fmaxf(fmaxf(v.y, v.z), v.w));
+        } else {
+            typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+            const f16x8 v = __builtin_nontemporal_load(reinterpret_cast<const f16x8*>(x) + c);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                lo = fminf(lo, static_cast<float>(v[k]));
+                hi = fmaxf(hi, static_cast<float>(v[k]));
+            }
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x < n - chunks * kE) {  // the last, partial chunk
+        const float v = static_cast<float>(x[chunks * kE + threadIdx.x]);
+        lo = fminf(lo, v);
+        hi = fmaxf(hi, v);
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        lo = fminf(lo, __shfl_xor(lo, d));
+        hi = fmaxf(hi, __shfl_xor(hi, d));
+    }
+    if ((threadIdx.x & (kWave - 1)) == 0) {
+        part_lo[threadIdx.x >> 6] = lo;
+        part_hi[threadIdx.x >> 6] = hi;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int w = 1; w < kWavesPerBlock; ++w) {
+            lo = fminf(lo, part_lo[w]);
+            hi = fmaxf(hi, part_hi[w]);
+        }
+        atomicMin(zr, float_to_ordered(lo));
+        atomicMax(zr + 1, float_to_ordered(hi));
+    }
+}
+
+__global__ void tensor_stats_finish_kernel(uint32_t* zr)
+{
+    if (threadIdx.x == 0) {
+        const float mn = ordered_to_float(zr[0]) + 0.0f;  // -0.0 -> +0.0
+        const float mx = ordered_to_float(zr[1]);
+        zr[0] = __float_as_uint(mn);
+        zr[1] = __float_as_uint((mx - mn) + 0.0f);  // a zero range is +0.0
     }
 }
 
@@ -1107,7 +1211,7 @@ int make_geometry(const char* who, int64_t N, int64_t D, uint32_t tiles_per_wave
     geo->ng = static_cast<uint32_t>(ng);
     geo->tiles_per_sample = static_cast<uint32_t>(tps);
     geo->tiles_per_wave = tiles_per_wave;
-    geo->hdr_bf16 = 0;
+    geo->hdr_mode = 0;
     const int64_t waves = (tps + tiles_per_wave - 1) / tiles_per_wave;
     const int64_t gx = (waves + kWavesPerBlock - 1) / kWavesPerBlock;
     const int64_t gy = N < 65535 ? N : 65535;
@@ -1237,7 +1341,7 @@ int launch_quantize_pack(const void* x, int dtype, int64_t N, int64_t D, const u
     geo.tiles_per_sample = static_cast<uint32_t>(tps);
     geo.total_tiles = static_cast<uint32_t>(N * tps);
     geo.step_n = geo.step_t = 0;
-    geo.hdr_bf16 = hdr == ACTQ_HDR_BF16 ? 1u : 0u;
+    geo.hdr_mode = static_cast<uint32_t>(hdr);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool vec = vector_ok(D);
     int rc;
@@ -1256,19 +1360,23 @@ int launch_unpack_dequantize(const void* packed, uint64_t capacity, const void* 
     Geometry geo;
     dim3 grid;
     if (int rc = make_geometry("actq_unpack_dequantize", N, D, kTilesPerWaveWrite, &geo, &grid)) return rc;
-    geo.hdr_bf16 = hdr == ACTQ_HDR_BF16 ? 1u : 0u;
+    geo.hdr_mode = static_cast<uint32_t>(hdr);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool vec = vector_ok(D);
     auto* pk = static_cast<const uint8_t*>(packed);
-    const bool bf = hdr == ACTQ_HDR_BF16;
 #define ACTQ_DEQ(T, V, H) unpack_dequantize_kernel<T, V, H><<<grid, kBlock, 0, s>>>(pk, capacity, header, bits, offsets, geo, static_cast<T*>(out))
+#define ACTQ_DEQ_H(T, V)                                   \
+    do {                                                   \
+        if (hdr == ACTQ_HDR_F32) ACTQ_DEQ(T, V, 0);        \
+        else if (hdr == ACTQ_HDR_BF16) ACTQ_DEQ(T, V, 1);  \
+        else ACTQ_DEQ(T, V, 2);                            \
+    } while (0)
     if (out_dtype == ACTQ_F32) {
-        if (vec) { if (bf) ACTQ_DEQ(float, true, true); else ACTQ_DEQ(float, true, false); }
-        else { if (bf) ACTQ_DEQ(float, false, true); else ACTQ_DEQ(float, false, false); }
+        if (vec) ACTQ_DEQ_H(float, true); else ACTQ_DEQ_H(float, false);
     } else {
-        if (vec) { if (bf) ACTQ_DEQ(_Float16, true, true); else ACTQ_DEQ(_Float16, true, false); }
-        else { if (bf) ACTQ_DEQ(_Float16, false, true); else ACTQ_DEQ(_Float16, false, false); }
+        if (vec) ACTQ_DEQ_H(_Float16, true); else ACTQ_DEQ_H(_Float16, false);
     }
+#undef ACTQ_DEQ_H
 #undef ACTQ_DEQ
     return check_launch("actq_unpack_dequantize");
 }
@@ -1287,6 +1395,23 @@ int launch_allocate_bits(const float* w, const int64_t* D_items, int64_t D, int6
     const int block = static_cast<int>(lanes < kAllocBlock ? lanes : kAllocBlock);
     allocate_bits_kernel<<<1, block, 0, static_cast<hipStream_t>(stream)>>>(w, a, bits, offsets, result);
     return check_launch("actq_allocate_bits_device");
+}
+
+int launch_tensor_stats(const void* x, int dtype, int64_t n, float* zr, void* stream)
+{
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint32_t* words = reinterpret_cast<uint32_t*>(zr);
+    const int64_t chunks = n / (dtype == ACTQ_F32 ? 4 : 8);
+    int64_t blocks = (chunks + kBlock - 1) / kBlock;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 2048) blocks = 2048;  // eight resident blocks per compute unit: 4096 atomics in all
+    tensor_stats_init_kernel<<<1, kWave, 0, s>>>(words);
+    if (dtype == ACTQ_F32)
+        tensor_stats_reduce_kernel<float><<<static_cast<unsigned>(blocks), kBlock, 0, s>>>(static_cast<const float*>(x), n, words);
+    else
+        tensor_stats_reduce_kernel<_Float16><<<static_cast<unsigned>(blocks), kBlock, 0, s>>>(static_cast<const _Float16*>(x), n, words);
+    tensor_stats_finish_kernel<<<1, kWave, 0, s>>>(words);
+    return check_launch("actq_tensor_stats");
 }
 
 int launch_sample_sensitivity(const float* grange, int64_t N, int64_t ng, int32_t G, const float* grad2,

@@ -27,11 +27,12 @@ class GpuRun:
         self.offsets = torch.from_numpy(self.offsets_np.view(np.int64)).to(dev)
         self.packed_buf = torch.full((self.total + pad,), CANARY, dtype=torch.uint8, device=dev)
         self.packed = self.packed_buf[: self.total]
-        if hf == B.ACTQ_HDR_F32:
-            self.header_buf = torch.full((self.N * self.ng * 2 + pad,), float("nan"), dtype=torch.float32, device=dev)
+        self.header_len = 2 if hf == B.ACTQ_HDR_TENSOR else self.N * self.ng * 2
+        if hf == B.ACTQ_HDR_BF16:
+            self.header_buf = torch.full((self.header_len + pad,), 0x7A5A, dtype=torch.int16, device=dev)
         else:
-            self.header_buf = torch.full((self.N * self.ng * 2 + pad,), 0x7A5A, dtype=torch.int16, device=dev)
-        self.header = self.header_buf[: self.N * self.ng * 2]
+            self.header_buf = torch.full((self.header_len + pad,), float("nan"), dtype=torch.float32, device=dev)
+        self.header = self.header_buf[: self.header_len]
 
     def stats(self):
         n = self.N * self.ng
@@ -46,9 +47,11 @@ class GpuRun:
         B.quantize_pack(self.x, self.bits, self.offsets, self.packed, self.header, seed, tag, noise_bits, self.G, hf=self.hf)
         torch.cuda.synchronize()
         assert (self.packed_buf[self.total:] == CANARY).all(), "quantize_pack wrote past the bit stream"
-        tail = self.header_buf[self.N * self.ng * 2:]
-        intact = torch.isnan(tail).all() if self.hf == B.ACTQ_HDR_F32 else (tail == 0x7A5A).all()
+        tail = self.header_buf[self.header_len:]
+        intact = (tail == 0x7A5A).all() if self.hf == B.ACTQ_HDR_BF16 else torch.isnan(tail).all()
         assert intact, "quantize_pack wrote past the header"
+        if self.hf == B.ACTQ_HDR_TENSOR:
+            return self.packed.cpu().numpy(), self.header.cpu().numpy()
         hd = self.header.cpu().numpy().reshape(self.N, self.ng, 2)
         return (self.packed.cpu().numpy(), hd if self.hf == B.ACTQ_HDR_F32 else hd.view(np.uint16))
 

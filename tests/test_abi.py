@@ -57,7 +57,7 @@ def test_device_calls_validate_before_launching():
     assert L.actq_quantize_pack(*(ok[:2] + [2, 512, 128] + ok[5:])) == E      # sanity: list is well-formed
     for idx, bad in [(0, None), (5, None), (6, None), (10, None), (12, None), (2, -1), (3, 0), (4, 512),
                      (1, 3), (9, 12), (0, FAKE + 2), (10, FAKE + 8), (12, FAKE + 4), (11, 10), (2, 1 << 32),
-                     (3, 1 << 34), (13, 2), (5, FAKE + 1)]:
+                     (3, 1 << 34), (13, 3), (5, FAKE + 1)]:
         args = list(ok)
         args[idx] = bad
         assert L.actq_quantize_pack(*args) == E, (idx, bad)
@@ -79,7 +79,14 @@ def test_device_calls_validate_before_launching():
     out = ctypes.c_uint64()
     assert L.actq_header_bytes(3, 1000, 256, 0, ctypes.addressof(out)) == 0 and out.value == 3 * 4 * 8
     assert L.actq_header_bytes(3, 1000, 256, 1, ctypes.addressof(out)) == 0 and out.value == 3 * 4 * 4
+    assert L.actq_header_bytes(3, 1000, 256, 2, ctypes.addressof(out)) == 0 and out.value == 8
     assert L.actq_header_bytes(3, 1000, 256, 5, ctypes.addressof(out)) == E
+    # tensor_stats: x, dt, n, zr, stream
+    ok = [FAKE, 0, 1000, FAKE, None]
+    for idx, bad in [(0, None), (3, None), (1, 4), (2, 0), (2, 1 << 40), (0, FAKE + 4), (3, FAKE + 4)]:
+        args = list(ok)
+        args[idx] = bad
+        assert L.actq_tensor_stats(*args) == E, (idx, bad)
     assert L.actq_header_bytes(3, 1000, 256, 0, None) == E
 
 

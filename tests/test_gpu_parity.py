@@ -95,6 +95,8 @@ def test_degenerate_groups_negative_zero_and_subnormals():
     x[0, :256] = 3.25                                   # constant group
     x[0, 256:512] = 0.0
     x[0, 300] = -0.0                                    # min is -0.0
+    x[3, 512:768] = 0.0
+    x[3, 512:768:2] = -0.0                              # zeros of both signs, -0.0 first: range is +0.0
     x[1, :256] = np.float32(1e-45) * rng.integers(0, 2, 256)      # range = smallest subnormal
     x[1, 256:512] = (rng.integers(0, 1000, 256) * np.float32(1e-42)).astype(np.float32)  # subnormal data
     x[2, :256] = -np.abs(x[2, :256])
@@ -263,6 +265,60 @@ def test_unaligned_device_arrays_are_rejected():
     assert e.value.code == B.ACTQ_EINVAL and "bits" in str(e.value)
     with pytest.raises(B.ActqError):
         B.quantize_pack(x.view(-1)[1:257 + 256 * 6].view(7, 256), bits[:7], offs[:7], packed, header[:14], 1)
+
+
+# ----------------------------------------------------------------------------- per-tensor baseline
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+@pytest.mark.parametrize("n", [1, 3, 4, 7, 255, 4096, 4096 * 33 + 5, 3_000_001])
+def test_tensor_stats(n, dtype):
+    rng = np.random.default_rng(n)
+    x = (rng.standard_normal(n) * 3 + 1).astype(dtype)
+    buf = torch.full((4,), float("nan"), dtype=torch.float32, device="cuda:0")
+    B.tensor_stats(torch.from_numpy(x).cuda(), buf[:2])
+    torch.cuda.synchronize()
+    assert torch.isnan(buf[2:]).all()
+    assert np.array_equal(buf[:2].cpu().numpy().view(np.uint32), oracle.tensor_stats(x).view(np.uint32))
+
+
+def test_tensor_stats_negative_zero_and_signs():
+    for vals in ([-0.0, 0.0, -0.0, 0.0], [-3.0, -1.0, -2.0, -5.0], [4.0, 2.0, 9.0, 2.5], [-1e-45, 1e-45, 0.0, -0.0]):
+        x = np.array(vals * 3, dtype=np.float32)
+        zr = B.tensor_stats(torch.from_numpy(x).cuda()).cpu().numpy()
+        assert np.array_equal(zr.view(np.uint32), oracle.tensor_stats(x).view(np.uint32)), vals
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+@pytest.mark.parametrize("noise_bits", [24, 16])
+@pytest.mark.parametrize("N,D", [(5, 256 * 7), (3, 256 * 13 + 100), (2, 257), (6, 256 * 40)])
+def test_per_tensor_mode(N, D, noise_bits, dtype):
+    rng = np.random.default_rng(N * 13 + D)
+    x = (rng.standard_normal((N, D)) * np.exp(rng.uniform(-3, 3, (N, 1))) + 0.5).astype(dtype)
+    bits = rng.integers(1, 9, N).astype(np.uint8)
+    run = GpuRun(x, bits, hf=B.ACTQ_HDR_TENSOR)
+    zr = oracle.tensor_stats(x)
+    B.tensor_stats(run.x, run.header)
+    torch.cuda.synchronize()
+    assert np.array_equal(run.header.cpu().numpy().view(np.uint32), zr.view(np.uint32))
+    packed, header = run.quantize(77, 5, noise_bits)
+    assert np.array_equal(header.reshape(-1).view(np.uint32), zr.view(np.uint32)), "the given header must not be written"
+    opacked, ooff = oracle.quantize_pack_tensor(x, bits, zr, 77, 5, noise_bits=noise_bits)
+    assert np.array_equal(packed, opacked)
+    for dt in (torch.float32, torch.float16):
+        npdt = np.float32 if dt == torch.float32 else np.float16
+        out = run.dequantize(dt)
+        want = oracle.unpack_dequantize_tensor(opacked, zr, bits, ooff, N, D, out_dtype=npdt)
+        assert np.array_equal(out.view(np.uint8), want.view(np.uint8))
+
+
+def test_per_tensor_mode_constant_tensor():
+    x = np.full((3, 512), -2.5, dtype=np.float32)
+    bits = np.array([1, 4, 8], dtype=np.uint8)
+    run = GpuRun(x, bits, hf=B.ACTQ_HDR_TENSOR)
+    B.tensor_stats(run.x, run.header)
+    packed, _ = run.quantize(1)
+    assert not packed.any()
+    assert np.all(run.dequantize() == -2.5)
 
 
 # ----------------------------------------------------------------------------- device allocator

@@ -39,6 +39,19 @@ def test_group_stats_ragged_tail_and_f16():
         assert np.array_equal(grange[:, g], x32[:, a:b].max(-1) - x32[:, a:b].min(-1))
 
 
+def test_zero_range_is_positive_zero_whatever_the_signs_of_the_zeros():
+    for first in (-0.0, 0.0):
+        x = np.zeros((1, 256), dtype=np.float32)
+        x[0, 0::2] = first
+        x[0, 1::2] = -first
+        gmin, grange = oracle.group_stats(x)
+        assert gmin[0, 0] == 0 and grange[0, 0] == 0
+        assert not np.signbit(gmin[0, 0]) and not np.signbit(grange[0, 0])
+    x = np.full((1, 256), -0.0, dtype=np.float32)
+    gmin, grange = oracle.group_stats(x)
+    assert not np.signbit(gmin[0, 0]) and not np.signbit(grange[0, 0])
+
+
 def test_negative_zero_minimum_is_stored_as_positive_zero():
     x = np.zeros((1, 256), dtype=np.float32)
     x[0, 3] = -0.0
