@@ -321,6 +321,43 @@ def test_per_tensor_mode_constant_tensor():
     assert np.all(run.dequantize() == -2.5)
 
 
+def test_variance_sweep_per_group_against_per_tensor():
+    """Sec. 4.1's argument measured on the GPU: squared error of one quantization pass per width,
+    per-group against per-tensor headers, on group ranges spread over orders of magnitude.  The
+    sums over 2^18 elements concentrate, so one pass is compared with the closed-form expectation
+    sum scale^2 p (1 - p)."""
+    rng = np.random.default_rng(21)
+    N, ng, G = 32, 32, 256
+    sigma = np.exp(rng.normal(0, 1.5, (N, ng, 1)))
+    x = (rng.standard_normal((N, ng, G)) * sigma).astype(np.float32).reshape(N, ng * G)
+    gmin, grange = oracle.group_stats(x)
+    zr = oracle.tensor_stats(x)
+    x64 = x.astype(np.float64)
+
+    def expected(z, scale):
+        u = (x64 - z) / np.where(scale > 0, scale, 1.0)
+        p = u - np.floor(u)
+        return float((scale.astype(np.float64) ** 2 * p * (1 - p)).sum())
+
+    print()
+    print("  b   per-group MSE   per-tensor MSE   ratio")
+    for b in range(1, 9):
+        Bq = np.float32((1 << b) - 1)
+        bits = np.full(N, b, dtype=np.uint8)
+        pg = GpuRun(x, bits)
+        pg.quantize(100 + b, 0, 16)
+        se_pg = float(((pg.dequantize().astype(np.float64) - x64) ** 2).sum())
+        pt = GpuRun(x, bits, hf=B.ACTQ_HDR_TENSOR)
+        B.tensor_stats(pt.x, pt.header)
+        pt.quantize(100 + b, 0, 16)
+        se_pt = float(((pt.dequantize().astype(np.float64) - x64) ** 2).sum())
+        want_pg = expected(np.repeat(gmin, G, axis=1), np.repeat(grange / Bq, G, axis=1))
+        want_pt = expected(zr[0], np.full(x.shape, zr[1] / Bq, dtype=np.float32))
+        print(f"  {b}   {se_pg / x.size:13.4e}   {se_pt / x.size:14.4e}   {se_pt / se_pg:7.1f}")
+        assert abs(se_pg / want_pg - 1) < 0.05 and abs(se_pt / want_pt - 1) < 0.05
+        assert se_pt > 10 * se_pg
+
+
 # ----------------------------------------------------------------------------- device allocator
 
 def _oracle_alloc(w, D, budget, widths):
