@@ -379,6 +379,48 @@ def main():
                 raise RuntimeError(f"device allocator reported status {status}")
             state["bits"], state["total"] = bits_dev.cpu().numpy(), total
 
+    # The timed steps of the device-allocator path call the C ABI with pointers and sizes worked out
+    # once and with events created beforehand, so that the host stays ahead of the GPU (five launches
+    # of 5-70 us each); the Python binding, with its checks, runs the first warm-up step and every test.
+    if args.allocator == "device":
+        binding_step = step
+        binding_step()
+        lib = B.lib()
+        sp = stream.cuda_stream
+        dt = B.ACTQ_F16 if wl.dtype == "f16" else B.ACTQ_F32
+        xp, gminp, grp, g2p, wp = x.data_ptr(), gmin.data_ptr(), grange.data_ptr(), grad2.data_ptr(), w_dev.data_ptr()
+        bp, op, rp = bits_dev.data_ptr(), offs_dev.data_ptr(), result_dev.data_ptr()
+        pkp, cap, hp, outp = packed_buf.data_ptr(), packed_buf.numel(), header.data_ptr(), out.data_ptr()
+        seed, tag, nb = wl.philox_seed, wl.tag, args.noise_bits
+        names = ("group_stats", "sensitivity+allocate", "quantize_pack", "unpack_dequantize")
+        # five boundary events per step: the end of one launch is the start of the next
+        pool = [[torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)] for _ in range(args.steps)]
+        cursor = [0]
+
+        def step(events=None):
+            ev = None
+            if events is not None:
+                ev = pool[cursor[0]]
+                cursor[0] += 1
+                for i, name in enumerate(names):
+                    events.setdefault(name, []).extend([(0, ev[i]), (1, ev[i + 1])])
+                ev[0].record(stream)
+            rc = lib.actq_group_stats(xp, dt, N, D, G, gminp, grp, sp)
+            if ev:
+                ev[1].record(stream)
+            rc |= lib.actq_sample_sensitivity(grp, N, ng, G, g2p, wp, sp)
+            rc |= lib.actq_allocate_bits_device(wp, None, D, N, G, budget, widths, bp, op, rp, sp)
+            if ev:
+                ev[2].record(stream)
+            rc |= lib.actq_quantize_pack(xp, dt, N, D, G, bp, op, seed, tag, nb, pkp, cap, hp, hf, sp)
+            if ev:
+                ev[3].record(stream)
+            rc |= lib.actq_unpack_dequantize(pkp, cap, hp, hf, bp, op, N, D, G, outp, dt, sp)
+            if ev:
+                ev[4].record(stream)
+            if rc:
+                raise RuntimeError(B.last_error())
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
