@@ -35,7 +35,7 @@ def parse():
     p.add_argument("--gpus", type=int, default=1)
     p.add_argument("--steps", type=int, default=30)
     p.add_argument("--warmup", type=int, default=5)
-    p.add_argument("--workload", default="r50_stage1", choices=["r50_stage1", "tiny", "r50_stem_f16", "fpn", "r50_sweep", "contexts"])
+    p.add_argument("--workload", default="r50_stage1", choices=["r50_stage1", "tiny", "r50_stem_f16", "fpn", "r50_sweep", "contexts", "block"])
     p.add_argument("--noise-bits", type=int, default=16, choices=[24, 16])
     p.add_argument("--header", default="f32", choices=["f32", "bf16"],
                    help="group header format: (Z, R/B) binary32, 8 B/group, or (Z, R) bfloat16, 4 B/group")
@@ -278,6 +278,64 @@ def contexts(args, torch, B, dev):
         "cpu_baseline": cpu_baseline}))
 
 
+def block(args, torch, dev):
+    """Layer integration: one ResNet-50 stage-1 bottleneck (1x1-3x3-1x1 convolutions with batch
+    norm, ReLU and the residual) at batch 64, fp32, forward + backward, stock layers against their
+    activation-compressed versions at a 2.0-bit average: time per iteration and the memory held for
+    the backward pass (allocated after the forward pass, minus what was allocated before it and the output).  The convolutions and batch norms themselves are torch's in both runs."""
+    import torch.nn as nn
+    from paper_2104_14129_amd import layers as L
+
+    class Bottleneck(nn.Module):
+        def __init__(self):
+            super().__init__()
+            self.a = nn.Sequential(nn.Conv2d(256, 64, 1, bias=False), nn.BatchNorm2d(64), nn.ReLU(),
+                                   nn.Conv2d(64, 64, 3, padding=1, bias=False), nn.BatchNorm2d(64), nn.ReLU(),
+                                   nn.Conv2d(64, 256, 1, bias=False), nn.BatchNorm2d(256))
+            self.out = nn.ReLU()
+
+        def forward(self, x):
+            return self.out(self.a(x) + x)
+
+    torch.manual_seed(0)
+    x = torch.randn(64, 256, 56, 56, device=dev).clamp_min_(0)
+    gy = torch.randn(64, 256, 56, 56, device=dev)
+
+    def run(model):
+        xin = x.clone().requires_grad_(True)
+
+        def it():
+            y = model(xin)
+            held = torch.cuda.memory_allocated() - y.numel() * y.element_size()   # contexts only, not the output
+            y.backward(gy)
+            return held
+        for _ in range(args.warmup):
+            it()
+        torch.cuda.synchronize()
+        base = torch.cuda.memory_allocated()
+        t0 = time.perf_counter()
+        held = 0
+        for _ in range(args.steps):
+            held = it()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / args.steps, held - base
+
+    stock_ms, stock_held = run(Bottleneck().to(dev))
+    L.set_optimization_level("L3", bits=2.0)
+    q_ms, q_held = run(L.convert(Bottleneck().to(dev)))
+    in_bytes = x.numel() * 4
+    print(json.dumps({
+        "metric": "activation-compressed ResNet-50 bottleneck, forward + backward: GB/s of block input; memory held for backward",
+        "value": in_bytes / (q_ms * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": q_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "block_r50_bottleneck_f32_64x256x56x56", "level": "L3", "mean_bits": 2.0},
+        "stock": {"ms_per_step": stock_ms, "context_bytes": stock_held},
+        "compressed": {"ms_per_step": q_ms, "context_bytes": q_held},
+        "memory_ratio": stock_held / max(q_held, 1), "time_ratio": q_ms / stock_ms,
+        "roofline": None, "cpu_baseline": None}))
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -298,6 +356,8 @@ def main():
         return sweep(args, torch, B, synth, dev)
     if args.workload == "contexts":
         return contexts(args, torch, B, dev)
+    if args.workload == "block":
+        return block(args, torch, dev)
 
     wl = {"r50_stage1": synth.r50_stage1, "tiny": synth.tiny, "r50_stem_f16": synth.r50_stem_f16,
           "fpn": synth.fpn}[args.workload]()
