@@ -480,6 +480,55 @@ def test_device_allocator_full_sweep_size():
         _check_alloc(w, D, 2 * int(D.sum()), widths, False)
 
 
+# ----------------------------------------------------------------------------- beyond 32-bit indices
+
+def test_element_indices_and_byte_offsets_beyond_32_bits():
+    """fp16 [3, 2^30]: element indices run past 2^32 and the bit stream past 2^31 bytes.  The tensor
+    is generated on the GPU; groups sampled at the ends and in the middle of every sample are pulled
+    back and compared, bit for bit, with the oracle's single-group routines."""
+    N, D = 3, 1 << 30
+    ng = D // 256
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev).manual_seed(123)
+    x = torch.empty((N, D), dtype=torch.float16, device=dev)
+    for n in range(N):
+        x[n].normal_(0, 1.5, generator=gen)
+    bits_np = np.array([8, 8, 4], dtype=np.uint8)
+    offsets_np, total = B.packed_bytes(N, D, bits_np)
+    assert int(offsets_np[2]) == 1 << 31 and total == (1 << 31) + (1 << 29)
+    bits = torch.from_numpy(bits_np).to(dev)
+    offsets = torch.from_numpy(offsets_np.view(np.int64)).to(dev)
+    packed = torch.full((total + 256,), 0xA5, dtype=torch.uint8, device=dev)
+    header = torch.full((N * ng * 2 + 64,), float("nan"), dtype=torch.float32, device=dev)
+    gmin = torch.empty((N, ng), dtype=torch.float32, device=dev)
+    grange = torch.empty((N, ng), dtype=torch.float32, device=dev)
+    out = torch.full((N * D + 64,), float("nan"), dtype=torch.float16, device=dev)
+    seed, tag = 0x1234567890, 17
+    print("[2^30 features] launching", flush=True)
+    B.group_stats(x, gmin, grange)
+    B.quantize_pack(x, bits, offsets, packed[:total], header[:N * ng * 2], seed, tag, 16)
+    B.unpack_dequantize(packed[:total], header[:N * ng * 2], bits, offsets, out[:N * D].view(N, D))
+    torch.cuda.synchronize()
+    assert (packed[total:] == 0xA5).all() and torch.isnan(header[N * ng * 2:]).all() and torch.isnan(out[N * D:]).all()
+    rng = np.random.default_rng(0)
+    picks = [0, 1, 2, 3, 4, ng // 2 - 1, ng // 2, ng - 5, ng - 4, ng - 3, ng - 2, ng - 1] + list(rng.integers(0, ng, 12))
+    hd = header[:N * ng * 2].view(N, ng, 2)
+    outv = out[:N * D].view(N, D)
+    for n in range(N):
+        b = int(bits_np[n])
+        for g in picks:
+            g = int(g)
+            xg = x[n, g * 256:(g + 1) * 256].cpu().numpy()
+            want_bytes, want_hd = oracle.quantize_group(xg, b, seed, tag, n, g * 256, noise_bits=16)
+            lo = int(offsets_np[n]) + g * 32 * b
+            assert np.array_equal(packed[lo:lo + 32 * b].cpu().numpy(), want_bytes), (n, g)
+            assert np.array_equal(hd[n, g].cpu().numpy().view(np.uint32), want_hd.view(np.uint32)), (n, g)
+            omin, orange = oracle.group_stats(xg.reshape(1, 256))
+            assert gmin[n, g].item() == omin[0, 0] and grange[n, g].item() == orange[0, 0]
+            want_out = oracle.dequantize_group(want_bytes, want_hd, b, 256, out_dtype=np.float16)
+            assert np.array_equal(outv[n, g * 256:(g + 1) * 256].cpu().numpy().view(np.uint16), want_out.view(np.uint16)), (n, g)
+
+
 # ----------------------------------------------------------------------------- full sizes
 
 def _full_size(wl, noise_bits, out_dtype):
