@@ -81,7 +81,7 @@ bool make_ladder(uint32_t widths, Ladder* out)
 
 extern "C" {
 
-int actq_version(void) { return 200; }
+int actq_version(void) { return 300; }
 
 int actq_header_bytes(int64_t N, int64_t D, int32_t G, actq_header_format hf, uint64_t* bytes_host)
 {
