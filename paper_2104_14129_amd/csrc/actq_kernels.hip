@@ -937,18 +937,33 @@ __global__ void tensor_stats_finish_kernel(uint32_t* zr)
 
 // ------------------------------------------------------------------------------------
 // Sec. 4.2, Eq. (8): w_n = (G / 6) * ||grad_n||^2 * sum_g R_ng^2.  One block per sample over the
-// group ranges (1/256 of the tensor's size); fixed summation order, so results are reproducible.
-__global__ __launch_bounds__(kBlock) void sample_sensitivity_kernel(const float* __restrict__ grange,
-                                                                    uint32_t N, uint32_t ng, uint32_t grid_x,
-                                                                    float coeff, const float* __restrict__ grad2,
-                                                                    float* __restrict__ w)
+// group ranges (1/256 of the tensor's size).  The block is as wide as the sample needs (up to
+// 1024 lanes) and every lane keeps four independent partial sums, so that a sample with many
+// groups has enough loads in flight; the partial sums are combined in a fixed order, so the
+// result is reproducible.
+constexpr int kSensMaxBlock = 1024;
+
+__global__ __launch_bounds__(kSensMaxBlock) void sample_sensitivity_kernel(const float* __restrict__ grange,
+                                                                           uint32_t N, uint32_t ng, uint32_t grid_x,
+                                                                           float coeff, const float* __restrict__ grad2,
+                                                                           float* __restrict__ w)
 {
-    __shared__ float partial[kWavesPerBlock];
+    __shared__ float partial[kSensMaxBlock / kWave];
     const uint32_t n = blockIdx.y * grid_x + blockIdx.x;
     if (n >= N) return;
     const float* r = grange + static_cast<int64_t>(n) * ng;
-    float acc = 0.0f;
-    for (uint32_t g = threadIdx.x; g < ng; g += kBlock) acc = __builtin_fmaf(r[g], r[g], acc);
+    const uint32_t threads = blockDim.x;
+    float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
+    uint32_t g = threadIdx.x;
+    for (; g + 3 * threads < ng; g += 4 * threads) {
+        const float r0 = r[g], r1 = r[g + threads], r2 = r[g + 2 * threads], r3 = r[g + 3 * threads];
+        a0 = __builtin_fmaf(r0, r0, a0);
+        a1 = __builtin_fmaf(r1, r1, a1);
+        a2 = __builtin_fmaf(r2, r2, a2);
+        a3 = __builtin_fmaf(r3, r3, a3);
+    }
+    for (; g < ng; g += threads) a0 = __builtin_fmaf(r[g], r[g], a0);
+    float acc = (a0 + a1) + (a2 + a3);
     // lanes, then wavefronts, in a fixed order
     acc += dpp_f32<kDppXor1>(acc);
     acc += dpp_f32<kDppXor2>(acc);
@@ -959,7 +974,8 @@ __global__ __launch_bounds__(kBlock) void sample_sensitivity_kernel(const float*
     if ((threadIdx.x & (kWave - 1)) == 0) partial[threadIdx.x >> 6] = acc;
     __syncthreads();
     if (threadIdx.x == 0) {
-        const float total = (partial[0] + partial[1]) + (partial[2] + partial[3]);
+        float total = 0.0f;
+        for (uint32_t k = 0; k < threads / kWave; ++k) total += partial[k];
         w[n] = coeff * total * (grad2 ? grad2[n] : 1.0f);
     }
 }
@@ -1420,7 +1436,10 @@ int launch_sample_sensitivity(const float* grange, int64_t N, int64_t ng, int32_
     const uint32_t gx = N < 65535 ? static_cast<uint32_t>(N) : 65535u;
     const uint32_t gy = static_cast<uint32_t>((N + gx - 1) / gx);
     if (gy > 65535u) return fail(ACTQ_EINVAL, "actq_sample_sensitivity: too many samples for one launch");
-    sample_sensitivity_kernel<<<dim3(gx, gy), kBlock, 0, static_cast<hipStream_t>(stream)>>>(
+    // one lane per group up to 1024 lanes, whole wavefronts
+    const int64_t lanes = (ng + kWave - 1) / kWave * kWave;
+    const unsigned block = static_cast<unsigned>(lanes < kSensMaxBlock ? lanes : kSensMaxBlock);
+    sample_sensitivity_kernel<<<dim3(gx, gy), block, 0, static_cast<hipStream_t>(stream)>>>(
         grange, static_cast<uint32_t>(N), static_cast<uint32_t>(ng), gx, static_cast<float>(G) / 6.0f, grad2, w);
     return check_launch("actq_sample_sensitivity");
 }
