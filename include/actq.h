@@ -245,6 +245,43 @@ int actq_allocate_bits_device(const float* w, const int64_t* D_items, int64_t D,
                               uint8_t* bits, uint64_t* offsets, int64_t* result, void* stream);
 
 /*
+ * Several tensors per launch.  A network saves dozens of activations of very
+ * different sizes per step (Sec. 5.1: every layer keeps a compressed context);
+ * these calls do the work of the single-tensor calls for up to
+ * ACTQ_MAX_TENSORS_PER_CALL tensors in one launch, with identical results.
+ * All tensors of a call share N, the dtype, the header format, the seed and the
+ * bit stream buffer (`packed`, with each tensor's own offsets array addressing
+ * it); tensor i draws its noise with tag + i.  Every D must be a multiple of
+ * G = 256 (tensors with ragged groups go through the single-tensor calls).
+ *
+ * The descriptor array lives in HOST memory and is copied into the launch; the
+ * pointers inside are device pointers with the alignment rules of the
+ * single-tensor calls.  Fields a call does not use may be NULL.
+ */
+#define ACTQ_MAX_TENSORS_PER_CALL 48
+typedef struct actq_tensor {
+    const void* x;           /* in : N*D elements (group_stats_multi, quantize_pack_multi)   */
+    void* out;               /* out: N*D elements (unpack_dequantize_multi)                  */
+    float* gmin;             /* out: [N*ng] (group_stats_multi)                              */
+    float* grange;           /* out: [N*ng] (group_stats_multi)                              */
+    void* header;            /* out of quantize_pack_multi, in of unpack_dequantize_multi    */
+    const uint8_t* bits;     /* in : [N] widths (quantize, dequantize)                       */
+    const uint64_t* offsets; /* in : [N] byte offsets into `packed` (quantize, dequantize)   */
+    int64_t D;               /* features per sample, a multiple of 256                       */
+} actq_tensor;
+
+int actq_group_stats_multi(const actq_tensor* tensors_host, int32_t count, actq_dtype dt,
+                           int64_t N, int32_t G, void* stream);
+int actq_quantize_pack_multi(const actq_tensor* tensors_host, int32_t count, actq_dtype dt,
+                             int64_t N, int32_t G, uint64_t seed, uint64_t tag, int32_t noise_bits,
+                             void* packed, uint64_t packed_capacity, actq_header_format hf,
+                             void* stream);
+int actq_unpack_dequantize_multi(const actq_tensor* tensors_host, int32_t count,
+                                 const void* packed, uint64_t packed_capacity,
+                                 actq_header_format hf, int64_t N, int32_t G, actq_dtype out_dt,
+                                 void* stream);
+
+/*
  * Exact context of a ReLU layer (appendix, "Activation Layers"): one bit per
  * element, f'(x) = [x > 0], nothing approximated.
  *

@@ -25,7 +25,8 @@ ACTQ_WIDTHS_POW2, ACTQ_WIDTHS_ALL = 0x116, 0x1FE  # allowed-width sets of the al
 EXPORTS = ("actq_version", "actq_last_error", "actq_packed_bytes", "actq_header_bytes", "actq_group_stats",
            "actq_quantize_pack", "actq_unpack_dequantize", "actq_sample_sensitivity", "actq_allocate_bits",
            "actq_allocate_bits_device", "actq_relu_mask_bytes", "actq_relu_forward", "actq_relu_backward",
-           "actq_pool2d_output_size", "actq_maxpool2d_forward", "actq_maxpool2d_backward", "actq_tensor_stats")
+           "actq_pool2d_output_size", "actq_maxpool2d_forward", "actq_maxpool2d_backward", "actq_tensor_stats",
+           "actq_group_stats_multi", "actq_quantize_pack_multi", "actq_unpack_dequantize_multi")
 
 
 class ActqError(RuntimeError):
@@ -66,6 +67,12 @@ def lib() -> ctypes.CDLL:
     L.actq_sample_sensitivity.argtypes = [vp, i64, i64, i32, vp, vp, vp]
     L.actq_allocate_bits.restype = c.c_int
     L.actq_allocate_bits.argtypes = [vp, vp, i64, i64, c.c_uint32, vp]
+    L.actq_group_stats_multi.restype = c.c_int
+    L.actq_group_stats_multi.argtypes = [vp, i32, c.c_int, i64, i32, vp]
+    L.actq_quantize_pack_multi.restype = c.c_int
+    L.actq_quantize_pack_multi.argtypes = [vp, i32, c.c_int, i64, i32, u64, u64, i32, vp, u64, c.c_int, vp]
+    L.actq_unpack_dequantize_multi.restype = c.c_int
+    L.actq_unpack_dequantize_multi.argtypes = [vp, i32, vp, u64, c.c_int, i64, i32, c.c_int, vp]
     L.actq_tensor_stats.restype = c.c_int
     L.actq_tensor_stats.argtypes = [vp, c.c_int, i64, vp, vp]
     L.actq_relu_mask_bytes.restype = c.c_int
@@ -362,3 +369,47 @@ def tensor_stats(x, zr=None, stream=None):
     _check(lib().actq_tensor_stats(_dev(x, None, "x"), _dtype_code(x), int(x.numel()), _dev(zr, torch.float32, "zr"),
                                    _stream(stream)))
     return zr
+
+
+# ----------------------------------------------------------------------------- several tensors per launch
+
+MAX_TENSORS_PER_CALL = 48
+
+
+class TensorDesc(ctypes.Structure):
+    """Mirror of `actq_tensor` (include/actq.h)."""
+    _fields_ = [("x", ctypes.c_void_p), ("out", ctypes.c_void_p), ("gmin", ctypes.c_void_p),
+                ("grange", ctypes.c_void_p), ("header", ctypes.c_void_p), ("bits", ctypes.c_void_p),
+                ("offsets", ctypes.c_void_p), ("D", ctypes.c_int64)]
+
+
+def tensor_table(entries):
+    """Host-side descriptor array from dicts with any of the keys x, out, gmin, grange, header, bits,
+    offsets (device tensors) and D.  All tensors must be [N, D] views with the same N."""
+    torch = _torch()
+    table = (TensorDesc * len(entries))()
+    for slot, e in zip(table, entries):
+        for key in ("x", "out", "gmin", "grange", "header", "bits", "offsets"):
+            t = e.get(key)
+            setattr(slot, key, None if t is None else _dev(t, None, key))
+        slot.D = int(e["D"])
+    return table
+
+
+def group_stats_multi(table, dtype_code: int, N: int, G: int = G_DEFAULT, stream=None):
+    _check(lib().actq_group_stats_multi(ctypes.addressof(table), len(table), dtype_code, N, G, _stream(stream)))
+
+
+def quantize_pack_multi(table, dtype_code: int, N: int, packed, seed: int, tag: int = 0, noise_bits: int = 24,
+                        G: int = G_DEFAULT, stream=None, hf: int = ACTQ_HDR_F32):
+    torch = _torch()
+    _check(lib().actq_quantize_pack_multi(ctypes.addressof(table), len(table), dtype_code, N, G, seed, tag, noise_bits,
+                                          _dev(packed, torch.uint8, "packed"), int(packed.numel()), hf,
+                                          _stream(stream)))
+
+
+def unpack_dequantize_multi(table, dtype_code: int, N: int, packed, G: int = G_DEFAULT, stream=None,
+                            hf: int = ACTQ_HDR_F32):
+    torch = _torch()
+    _check(lib().actq_unpack_dequantize_multi(ctypes.addressof(table), len(table), _dev(packed, torch.uint8, "packed"),
+                                              int(packed.numel()), hf, N, G, dtype_code, _stream(stream)))

@@ -252,6 +252,60 @@ int actq_allocate_bits_device(const float* w, const int64_t* D_items, int64_t D,
     return launch_allocate_bits(w, D_items, D, M, budget_bits, lad, bits, offsets, result, stream);
 }
 
+// Checks shared by the multi-tensor calls: which == 0 stats, 1 quantize, 2 dequantize.
+static int check_multi(const char* who, const actq_tensor* t, int32_t count, int dt, int64_t N, int32_t G, int which,
+                       const void* packed, int hf)
+{
+    if (int rc = check_dtype(who, dt)) return rc;
+    if (!t) return fail(ACTQ_EINVAL, "%s: tensors_host is null", who);
+    if (count < 1 || count > ACTQ_MAX_TENSORS_PER_CALL)
+        return fail(ACTQ_EINVAL, "%s: count must be in [1, %d]", who, ACTQ_MAX_TENSORS_PER_CALL);
+    if (which != 0) {
+        if (int rc = check_header(who, hf)) return rc;
+        if (!packed || !aligned(packed, 16)) return fail(ACTQ_EINVAL, "%s: packed must be non-null and 16-byte aligned", who);
+    }
+    for (int32_t i = 0; i < count; ++i) {
+        if (int rc = check_view(who, N, t[i].D, G)) return rc;
+        if (t[i].D % G != 0) return fail(ACTQ_EINVAL, "%s: tensor %d: D must be a multiple of %d", who, i, G);
+        const void* data = which == 2 ? t[i].out : t[i].x;
+        if (!data || !aligned(data, 16)) return fail(ACTQ_EINVAL, "%s: tensor %d: data pointer must be non-null and 16-byte aligned", who, i);
+        if (which == 0) {
+            if (!t[i].gmin || !t[i].grange || !aligned(t[i].gmin, 4) || !aligned(t[i].grange, 4))
+                return fail(ACTQ_EINVAL, "%s: tensor %d: gmin and grange must be non-null and 4-byte aligned", who, i);
+        } else {
+            if (!t[i].header || !aligned(t[i].header, 8)) return fail(ACTQ_EINVAL, "%s: tensor %d: header must be non-null and 8-byte aligned", who, i);
+            if (!t[i].bits || !aligned(t[i].bits, 4)) return fail(ACTQ_EINVAL, "%s: tensor %d: bits must be non-null and 4-byte aligned", who, i);
+            if (!t[i].offsets || !aligned(t[i].offsets, 8)) return fail(ACTQ_EINVAL, "%s: tensor %d: offsets must be non-null and 8-byte aligned", who, i);
+        }
+    }
+    return ACTQ_OK;
+}
+
+int actq_group_stats_multi(const actq_tensor* tensors_host, int32_t count, actq_dtype dt, int64_t N, int32_t G,
+                           void* stream)
+{
+    if (int rc = check_multi("actq_group_stats_multi", tensors_host, count, dt, N, G, 0, nullptr, 0)) return rc;
+    return launch_group_stats_multi(tensors_host, count, dt, N, stream);
+}
+
+int actq_quantize_pack_multi(const actq_tensor* tensors_host, int32_t count, actq_dtype dt, int64_t N, int32_t G,
+                             uint64_t seed, uint64_t tag, int32_t noise_bits, void* packed,
+                             uint64_t packed_capacity, actq_header_format hf, void* stream)
+{
+    if (int rc = check_multi("actq_quantize_pack_multi", tensors_host, count, dt, N, G, 1, packed, hf)) return rc;
+    if (noise_bits != 24 && noise_bits != 16)
+        return fail(ACTQ_EINVAL, "actq_quantize_pack_multi: noise_bits must be 24 or 16, got %d", noise_bits);
+    return launch_quantize_pack_multi(tensors_host, count, dt, N, seed, tag, noise_bits, packed, packed_capacity, hf, stream);
+}
+
+int actq_unpack_dequantize_multi(const actq_tensor* tensors_host, int32_t count, const void* packed,
+                                 uint64_t packed_capacity, actq_header_format hf, int64_t N, int32_t G,
+                                 actq_dtype out_dt, void* stream)
+{
+    if (int rc = check_multi("actq_unpack_dequantize_multi", tensors_host, count, out_dt, N, G, 2, packed, hf)) return rc;
+    return launch_unpack_dequantize_multi(tensors_host, count, packed, packed_capacity, hf, N, out_dt, stream);
+}
+
 int actq_tensor_stats(const void* x, actq_dtype dt, int64_t n, float* zr, void* stream)
 {
     if (int rc = check_dtype("actq_tensor_stats", dt)) return rc;

@@ -31,6 +31,11 @@ int launch_quantize_pack(const void* x, int dtype, int64_t N, int64_t D, const u
 int launch_unpack_dequantize(const void* packed, uint64_t capacity, const void* header, int hdr,
                              const uint8_t* bits, const uint64_t* offsets, int64_t N,
                              int64_t D, void* out, int out_dtype, void* stream);
+int launch_group_stats_multi(const actq_tensor* tensors, int32_t count, int dtype, int64_t N, void* stream);
+int launch_quantize_pack_multi(const actq_tensor* tensors, int32_t count, int dtype, int64_t N, uint64_t seed,
+                               uint64_t tag, int noise_bits, void* packed, uint64_t capacity, int hdr, void* stream);
+int launch_unpack_dequantize_multi(const actq_tensor* tensors, int32_t count, const void* packed, uint64_t capacity,
+                                   int hdr, int64_t N, int out_dtype, void* stream);
 int launch_tensor_stats(const void* x, int dtype, int64_t n, float* zr, void* stream);
 int launch_sample_sensitivity(const float* grange, int64_t N, int64_t ng, int32_t G,
                               const float* grad2, float* w, void* stream);

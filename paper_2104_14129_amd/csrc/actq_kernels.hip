@@ -38,6 +38,7 @@ constexpr int kWave = 64;
 constexpr int kWavesPerBlock = 4;
 constexpr int kBlock = kWave * kWavesPerBlock;
 constexpr int kTileGroups = 4;
+constexpr int kMaxMulti = ACTQ_MAX_TENSORS_PER_CALL;  // tensors of one multi-tensor launch
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
@@ -848,6 +849,136 @@ __global__ __launch_bounds__(kBlock) void unpack_dequantize_kernel(
 }
 
 // ------------------------------------------------------------------------------------
+// Several tensors in one launch.  A network saves dozens of activations of very different
+// sizes (a ResNet-50 step: 53, from 26 MB to 822 MB at batch 256); one launch per tensor leaves
+// the chip draining and refilling 53 times per pass, and the small tensors cannot fill it at
+// all.  Here the tiles of all tensors form one grid: grid.x runs over the tiles of one sample
+// of every tensor in turn (tile_start[] are the prefix sums), grid.y * grid.z over the samples.
+// A wavefront finds its tensor with one ballot over the prefix sums, loads that tensor's
+// pointers from the kernel arguments (uniform loads) and runs the single-tensor tile code.
+// Every tensor has full groups (D a multiple of 256) and the same N, dtype and header format.
+
+struct MultiItem {
+    const void* x;            // input of group_stats / quantize_pack
+    void* out;                // output of unpack_dequantize
+    float* gmin;              // outputs of group_stats
+    float* grange;
+    void* header;
+    const uint8_t* bits;
+    const uint64_t* offsets;
+    int64_t D;
+};
+
+struct MultiTable {
+    uint32_t count, N, grid_y, hdr_mode;
+    uint32_t tile_start[kMaxMulti + 1];  // tile_start[count] = tiles per sample over all tensors
+    MultiItem item[kMaxMulti];
+};
+
+// Tensor index and tile inside the tensor's sample for linear tile `lin` (wavefront-uniform).
+__device__ __forceinline__ uint32_t multi_locate(const MultiTable& t, uint32_t lin, int lane, uint32_t& tile)
+{
+    const uint32_t start = static_cast<uint32_t>(lane) < t.count ? t.tile_start[lane] : 0xffffffffu;
+    const uint64_t at_or_before = __ballot(start <= lin);
+    const uint32_t l = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(__builtin_popcountll(at_or_before) - 1));
+    tile = lin - static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(t.tile_start[l])));
+    return l;
+}
+
+template <typename T>
+__global__ __launch_bounds__(kBlock) void group_stats_multi_kernel(MultiTable t)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint32_t wave = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6)));
+    const uint32_t n = blockIdx.z * t.grid_y + blockIdx.y;
+    const uint32_t lin = blockIdx.x * kWavesPerBlock + wave;
+    if (n >= t.N || lin >= t.tile_start[t.count]) return;
+    uint32_t tile;
+    const MultiItem& it = t.item[multi_locate(t, lin, lane, tile)];
+    const uint32_t ng = static_cast<uint32_t>(it.D >> 8);
+    const T* xs = static_cast<const T*>(it.x) + static_cast<int64_t>(n) * it.D;
+    const uint32_t g0 = tile * kTileGroups;
+    const int groups = static_cast<int>(min(static_cast<uint32_t>(kTileGroups), ng - g0));
+    float v[kTileGroups][4];
+    bool ok[kTileGroups][4];
+    load_tile<T, true>(xs, g0, groups, lane, it.D, v, ok);
+    float lo[kTileGroups], hi[kTileGroups];
+    lane_min_max<true>(v, ok, lo, hi);
+    float mn, mx;
+    tile_min_max(lo, hi, lane, mn, mx);
+    mn += 0.0f;  // -0.0 -> +0.0
+    const int row = lane >> 4;
+    if ((lane & 15) == 0 && row < groups) {
+        const int64_t gi = static_cast<int64_t>(n) * ng + g0 + row;
+        it.gmin[gi] = mn;
+        it.grange[gi] = (mx - mn) + 0.0f;
+    }
+}
+
+template <typename T, int NOISE_BITS>
+__global__ __launch_bounds__(kBlock) void quantize_pack_multi_kernel(MultiTable t, uint32_t k0, uint32_t k1, uint64_t tag,
+                                                                     uint8_t* __restrict__ packed, uint64_t capacity)
+{
+    __shared__ uint32_t stage_all[kWavesPerBlock][256];
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint32_t wave = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6)));
+    const uint32_t lin = blockIdx.x * kWavesPerBlock + wave;
+    Cursor c;
+    c.n = blockIdx.z * t.grid_y + blockIdx.y;
+    if (c.n >= t.N || lin >= t.tile_start[t.count]) return;
+    const uint32_t l = multi_locate(t, lin, lane, c.t);
+    const MultiItem& it = t.item[l];
+    StreamGeometry geo;
+    geo.D = it.D;
+    geo.N = t.N;
+    geo.ng = static_cast<uint32_t>(it.D >> 8);
+    geo.tiles_per_sample = (geo.ng + kTileGroups - 1) / kTileGroups;
+    geo.total_tiles = 0;
+    geo.step_n = geo.step_t = 0;
+    geo.hdr_mode = t.hdr_mode;
+    const uint64_t tensor_tag = tag + l;  // every tensor of the launch draws its own noise
+    TileRegs r;
+    fetch<T, true>(static_cast<const T*>(it.x), geo, it.bits, it.offsets, lane, c, r);
+    quantize_one<NOISE_BITS, true>(r, c, geo, lane, k0, k1, static_cast<uint32_t>(tensor_tag),
+                                   static_cast<uint32_t>(tensor_tag >> 32), packed, capacity, it.header, stage_all[wave]);
+}
+
+template <typename T, int HDR>
+__global__ __launch_bounds__(kBlock) void unpack_dequantize_multi_kernel(MultiTable t, const uint8_t* __restrict__ packed,
+                                                                         uint64_t capacity)
+{
+    __shared__ uint32_t stage_all[kWavesPerBlock][256];
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint32_t wave = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6)));
+    uint32_t* stage = stage_all[wave];
+    const uint32_t n = blockIdx.z * t.grid_y + blockIdx.y;
+    const uint32_t lin = blockIdx.x * kWavesPerBlock + wave;
+    if (n >= t.N || lin >= t.tile_start[t.count]) return;
+    uint32_t tile;
+    const MultiItem& it = t.item[multi_locate(t, lin, lane, tile)];
+    const uint32_t ng = static_cast<uint32_t>(it.D >> 8);
+    T* os = static_cast<T*>(it.out) + static_cast<int64_t>(n) * it.D;
+    const uint32_t b = load_width(it.bits, n);
+    const uint64_t off = it.offsets[n];
+    const uint64_t bytes = static_cast<uint64_t>(ng) * 32u * b;
+    if ((off & 31u) != 0 || off > capacity || bytes > capacity - off) return;
+    const uint8_t* src = packed + off;
+    const uint32_t g0 = tile * kTileGroups;
+    const int groups = static_cast<int>(min(static_cast<uint32_t>(kTileGroups), ng - g0));
+    switch (b) {
+        case 1: dequantize_any<T, true, 1, HDR>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
+        case 2: dequantize_any<T, true, 2, HDR>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
+        case 3: dequantize_any<T, true, 3, HDR>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
+        case 4: dequantize_any<T, true, 4, HDR>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
+        case 5: dequantize_any<T, true, 5, HDR>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
+        case 6: dequantize_any<T, true, 6, HDR>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
+        case 7: dequantize_any<T, true, 7, HDR>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
+        case 8: dequantize_any<T, true, 8, HDR>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
+        default: return;
+    }
+}
+
+// ------------------------------------------------------------------------------------
 // One range and zero point for the whole tensor (the per-tensor baseline of Sec. 4.1 and
 // Sec. 6.1): Z = min, R = max - min over all elements.  Three tiny launches on the caller's
 // stream: set the two result words to the identity, reduce (a fixed number of wavefronts
@@ -1411,6 +1542,88 @@ int launch_allocate_bits(const float* w, const int64_t* D_items, int64_t D, int6
     const int block = static_cast<int>(lanes < kAllocBlock ? lanes : kAllocBlock);
     allocate_bits_kernel<<<1, block, 0, static_cast<hipStream_t>(stream)>>>(w, a, bits, offsets, result);
     return check_launch("actq_allocate_bits_device");
+}
+
+static int make_multi_table(const char* who, const actq_tensor* tensors, int32_t count, int64_t N, int hdr,
+                            MultiTable* t, dim3* grid)
+{
+    t->count = static_cast<uint32_t>(count);
+    t->N = static_cast<uint32_t>(N);
+    t->hdr_mode = static_cast<uint32_t>(hdr);
+    uint64_t tiles = 0;
+    for (int32_t i = 0; i < count; ++i) {
+        const int64_t ng = tensors[i].D / kGroup;
+        t->tile_start[i] = static_cast<uint32_t>(tiles);
+        tiles += static_cast<uint64_t>((ng + kTileGroups - 1) / kTileGroups);
+        if (tiles >= (uint64_t(1) << 31)) return fail(ACTQ_EINVAL, "%s: too many tiles for one launch", who);
+        MultiItem& it = t->item[i];
+        it.x = tensors[i].x;
+        it.out = tensors[i].out;
+        it.gmin = tensors[i].gmin;
+        it.grange = tensors[i].grange;
+        it.header = tensors[i].header;
+        it.bits = tensors[i].bits;
+        it.offsets = tensors[i].offsets;
+        it.D = tensors[i].D;
+    }
+    for (int32_t i = count; i <= kMaxMulti; ++i) t->tile_start[i] = static_cast<uint32_t>(tiles);
+    t->tile_start[count] = static_cast<uint32_t>(tiles);
+    const int64_t gy = N < 65535 ? N : 65535;
+    const int64_t gz = (N + gy - 1) / gy;
+    if (gz > 65535) return fail(ACTQ_EINVAL, "%s: too many samples for one launch", who);
+    t->grid_y = static_cast<uint32_t>(gy);
+    *grid = dim3(static_cast<unsigned>((tiles + kWavesPerBlock - 1) / kWavesPerBlock), static_cast<unsigned>(gy),
+                 static_cast<unsigned>(gz));
+    return ACTQ_OK;
+}
+
+int launch_group_stats_multi(const actq_tensor* tensors, int32_t count, int dtype, int64_t N, void* stream)
+{
+    MultiTable t;
+    dim3 grid;
+    if (int rc = make_multi_table("actq_group_stats_multi", tensors, count, N, 0, &t, &grid)) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (dtype == ACTQ_F32) group_stats_multi_kernel<float><<<grid, kBlock, 0, s>>>(t);
+    else group_stats_multi_kernel<_Float16><<<grid, kBlock, 0, s>>>(t);
+    return check_launch("actq_group_stats_multi");
+}
+
+int launch_quantize_pack_multi(const actq_tensor* tensors, int32_t count, int dtype, int64_t N, uint64_t seed,
+                               uint64_t tag, int noise_bits, void* packed, uint64_t capacity, int hdr, void* stream)
+{
+    MultiTable t;
+    dim3 grid;
+    if (int rc = make_multi_table("actq_quantize_pack_multi", tensors, count, N, hdr, &t, &grid)) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint32_t k0 = static_cast<uint32_t>(seed), k1 = static_cast<uint32_t>(seed >> 32);
+    uint8_t* pk = static_cast<uint8_t*>(packed);
+    if (dtype == ACTQ_F32) {
+        if (noise_bits == 16) quantize_pack_multi_kernel<float, 16><<<grid, kBlock, 0, s>>>(t, k0, k1, tag, pk, capacity);
+        else quantize_pack_multi_kernel<float, 24><<<grid, kBlock, 0, s>>>(t, k0, k1, tag, pk, capacity);
+    } else {
+        if (noise_bits == 16) quantize_pack_multi_kernel<_Float16, 16><<<grid, kBlock, 0, s>>>(t, k0, k1, tag, pk, capacity);
+        else quantize_pack_multi_kernel<_Float16, 24><<<grid, kBlock, 0, s>>>(t, k0, k1, tag, pk, capacity);
+    }
+    return check_launch("actq_quantize_pack_multi");
+}
+
+int launch_unpack_dequantize_multi(const actq_tensor* tensors, int32_t count, const void* packed, uint64_t capacity,
+                                   int hdr, int64_t N, int out_dtype, void* stream)
+{
+    MultiTable t;
+    dim3 grid;
+    if (int rc = make_multi_table("actq_unpack_dequantize_multi", tensors, count, N, hdr, &t, &grid)) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint8_t* pk = static_cast<const uint8_t*>(packed);
+#define ACTQ_DEQM(T)                                                                                     \
+    do {                                                                                                 \
+        if (hdr == ACTQ_HDR_F32) unpack_dequantize_multi_kernel<T, 0><<<grid, kBlock, 0, s>>>(t, pk, capacity);       \
+        else if (hdr == ACTQ_HDR_BF16) unpack_dequantize_multi_kernel<T, 1><<<grid, kBlock, 0, s>>>(t, pk, capacity); \
+        else unpack_dequantize_multi_kernel<T, 2><<<grid, kBlock, 0, s>>>(t, pk, capacity);                           \
+    } while (0)
+    if (out_dtype == ACTQ_F32) ACTQ_DEQM(float); else ACTQ_DEQM(_Float16);
+#undef ACTQ_DEQM
+    return check_launch("actq_unpack_dequantize_multi");
 }
 
 int launch_tensor_stats(const void* x, int dtype, int64_t n, float* zr, void* stream)

@@ -209,3 +209,41 @@ def test_context_calls_validate_before_launching():
         args = list(ok)
         args[idx] = bad
         assert L.actq_maxpool2d_backward(*args) == E, (idx, bad)
+
+
+def test_multi_tensor_calls_validate_before_launching():
+    L = B.lib()
+    E = B.ACTQ_EINVAL
+
+    def table(n=2, **over):
+        t = (B.TensorDesc * n)()
+        for slot in t:
+            slot.x = slot.out = slot.gmin = slot.grange = slot.header = slot.bits = slot.offsets = FAKE
+            slot.D = 512
+        for k, v in over.items():
+            setattr(t[1 if n > 1 else 0], k, v)
+        return t
+
+    def stats(t, count=None, dt=0, N=4, G=256):
+        return L.actq_group_stats_multi(ctypes.addressof(t), len(t) if count is None else count, dt, N, G, None)
+
+    def quant(t, dt=0, N=4, G=256, nb=16, packed=FAKE, hf=0):
+        return L.actq_quantize_pack_multi(ctypes.addressof(t), len(t), dt, N, G, 1, 0, nb, packed, 1 << 20, hf, None)
+
+    def deq(t, dt=0, N=4, G=256, packed=FAKE, hf=0):
+        return L.actq_unpack_dequantize_multi(ctypes.addressof(t), len(t), packed, 1 << 20, hf, N, G, dt, None)
+
+    assert L.actq_group_stats_multi(None, 1, 0, 4, 256, None) == E
+    assert stats(table(), count=0) == E and stats(table(49)) == E
+    assert stats(table(), dt=3) == E and stats(table(), N=0) == E and stats(table(), G=64) == E
+    for k, v in [("D", 500), ("D", 0), ("x", None), ("x", FAKE + 4), ("gmin", None), ("grange", FAKE + 2)]:
+        assert stats(table(**{k: v})) == E, (k, v)
+        assert "tensor 1" in B.last_error() or "D" in B.last_error() or "positive" in B.last_error()
+    assert quant(table(), nb=8) == E and quant(table(), packed=None) == E and quant(table(), packed=FAKE + 8) == E
+    assert quant(table(), hf=9) == E
+    for k, v in [("D", 300), ("x", None), ("header", None), ("header", FAKE + 4), ("bits", None), ("bits", FAKE + 1),
+                 ("offsets", None), ("offsets", FAKE + 4)]:
+        assert quant(table(**{k: v})) == E, (k, v)
+    assert deq(table(), dt=2) == E and deq(table(), packed=None) == E
+    for k, v in [("out", None), ("out", FAKE + 8), ("header", None), ("bits", None), ("offsets", None), ("D", 257)]:
+        assert deq(table(**{k: v})) == E, (k, v)

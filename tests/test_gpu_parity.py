@@ -480,6 +480,88 @@ def test_device_allocator_full_sweep_size():
         _check_alloc(w, D, 2 * int(D.sum()), widths, False)
 
 
+# ----------------------------------------------------------------------------- several tensors per launch
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+@pytest.mark.parametrize("noise_bits,hf", [(16, 0), (24, 0), (16, 1)])
+def test_multi_tensor_calls_equal_the_single_tensor_calls(noise_bits, hf, dtype):
+    """Five tensors of very different sizes in one launch per kernel: statistics, bit stream,
+    headers and dequantized values equal the oracle's (hence the single-tensor calls'), with one
+    shared bit stream buffer and tag + i as the tag of tensor i."""
+    rng = np.random.default_rng(31 + noise_bits + hf)
+    N = 6
+    Ds = [256, 256 * 5, 256 * 64, 256 * 3, 256 * 21]
+    dev = torch.device("cuda:0")
+    tdt = torch.float32 if dtype == np.float32 else torch.float16
+    xs_np = [(rng.standard_normal((N, D)) * np.exp(rng.uniform(-2, 2, (N, 1)))).astype(dtype) for D in Ds]
+    bits_np = [rng.integers(1, 9, N).astype(np.uint8) for _ in Ds]
+    # one bit stream for all tensors: offsets continue from tensor to tensor
+    offs_np, base = [], 0
+    for D, b in zip(Ds, bits_np):
+        o, total = B.packed_bytes(N, D, b)
+        offs_np.append(o + np.uint64(base))
+        base += total
+    packed = torch.full((base + 256,), 0xA5, dtype=torch.uint8, device=dev)
+    entries, keep = [], []
+    for D, x_np, b, o in zip(Ds, xs_np, bits_np, offs_np):
+        ng = D // 256
+        e = {"x": torch.from_numpy(x_np).to(dev), "out": torch.full((N, D), float("nan"), dtype=tdt, device=dev),
+             "gmin": torch.full((N, ng), float("nan"), dtype=torch.float32, device=dev),
+             "grange": torch.full((N, ng), float("nan"), dtype=torch.float32, device=dev),
+             "header": (torch.zeros(N * ng * 2, dtype=torch.int16, device=dev) if hf == 1
+                        else torch.full((N * ng * 2,), float("nan"), dtype=torch.float32, device=dev)),
+             "bits": torch.from_numpy(b).to(dev), "offsets": torch.from_numpy(o.view(np.int64)).to(dev), "D": D}
+        entries.append(e)
+    table = B.tensor_table(entries)
+    code = B.ACTQ_F32 if dtype == np.float32 else B.ACTQ_F16
+    B.group_stats_multi(table, code, N)
+    B.quantize_pack_multi(table, code, N, packed[:base], seed=77, tag=1000, noise_bits=noise_bits, hf=hf)
+    B.unpack_dequantize_multi(table, code, N, packed[:base], hf=hf)
+    torch.cuda.synchronize()
+    assert (packed[base:] == 0xA5).all()
+    pk = packed[:base].cpu().numpy()
+    for i, (e, x_np, b, o, D) in enumerate(zip(entries, xs_np, bits_np, offs_np, Ds)):
+        omin, orange = oracle.group_stats(x_np)
+        assert np.array_equal(e["gmin"].cpu().numpy().view(np.uint32), omin.view(np.uint32)), i
+        assert np.array_equal(e["grange"].cpu().numpy().view(np.uint32), orange.view(np.uint32)), i
+        if hf == 1:
+            opacked, oheader, ooff = oracle.quantize_pack_bf16(x_np, b, 77, 1000 + i, noise_bits=noise_bits)
+            want = oracle.unpack_dequantize_bf16(opacked, oheader, b, ooff, N, D, out_dtype=dtype)
+            assert np.array_equal(e["header"].cpu().numpy().view(np.uint16), oheader.reshape(-1)), i
+        else:
+            opacked, oheader, ooff = oracle.quantize_pack(x_np, b, 77, 1000 + i, noise_bits=noise_bits)
+            want = oracle.unpack_dequantize(opacked, oheader, b, ooff, N, D, out_dtype=dtype)
+            assert np.array_equal(e["header"].cpu().numpy().view(np.uint32), oheader.reshape(-1).view(np.uint32)), i
+        lo = int(o[0])
+        assert np.array_equal(pk[lo:lo + opacked.size], opacked), i
+        assert np.array_equal(e["out"].cpu().numpy().view(np.uint8), want.view(np.uint8)), i
+
+
+def test_multi_tensor_call_with_the_maximum_number_of_tensors():
+    N, D = 3, 512
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(8)
+    count = B.MAX_TENSORS_PER_CALL
+    xs = [rng.standard_normal((N, D)).astype(np.float32) for _ in range(count)]
+    bits = np.full(N, 2, dtype=np.uint8)
+    o, total = B.packed_bytes(N, D, bits)
+    packed = torch.zeros(total * count, dtype=torch.uint8, device=dev)
+    entries = [{"x": torch.from_numpy(x).to(dev), "out": torch.empty((N, D), device=dev),
+                "header": torch.empty(N * 2 * 2, device=dev), "bits": torch.from_numpy(bits).to(dev),
+                "offsets": torch.from_numpy((o + np.uint64(total * i)).view(np.int64)).to(dev), "D": D}
+               for i, x in enumerate(xs)]
+    table = B.tensor_table(entries)
+    B.quantize_pack_multi(table, B.ACTQ_F32, N, packed, seed=5, tag=0, noise_bits=16)
+    B.unpack_dequantize_multi(table, B.ACTQ_F32, N, packed)
+    torch.cuda.synchronize()
+    pk = packed.cpu().numpy()
+    for i in (0, 1, count // 2, count - 2, count - 1):
+        opacked, oheader, ooff = oracle.quantize_pack(xs[i], bits, 5, i, noise_bits=16)
+        assert np.array_equal(pk[total * i: total * (i + 1)], opacked), i
+        want = oracle.unpack_dequantize(opacked, oheader, bits, ooff, N, D)
+        assert np.array_equal(entries[i]["out"].cpu().numpy().view(np.uint32), want.view(np.uint32)), i
+
+
 # ----------------------------------------------------------------------------- beyond 32-bit indices
 
 def test_element_indices_and_byte_offsets_beyond_32_bits():
