@@ -41,6 +41,8 @@ def parse():
                    help="group header format: (Z, R/B) binary32, 8 B/group, or (Z, R) bfloat16, 4 B/group")
     p.add_argument("--allocator", default="device", choices=["device", "host"],
                    help="where the greedy bit allocation of each step runs")
+    p.add_argument("--launches", default="multi", choices=["multi", "single"],
+                   help="r50_sweep: all tensors in a few multi-tensor launches, or one launch per tensor and kernel")
     p.add_argument("--uniform-bits", type=int, default=0, choices=range(0, 9), metavar="B",
                    help="give every sample the width B (1..8) instead of the workload's mixed widths")
     p.add_argument("--no-cpu-baseline", action="store_true")
@@ -76,12 +78,17 @@ def measured_traffic(workload: str, noise_bits: int, kernel: str):
 
 def sweep(args, torch, B, synth, dev):
     """The 53 conv-input tensors of ResNet-50 at batch 256 (fp32, 10.9 GB): one step allocates
-    widths for all 53 x 256 (layer, sample) items under a 2.0-bit average budget on the host, then
-    runs group_stats, quantize_pack and unpack_dequantize on every layer."""
+    widths for all 53 x 256 (layer, sample) items under a 2.0-bit average budget, then runs
+    group_stats, quantize_pack and unpack_dequantize on every layer -- by default as multi-tensor
+    launches (one call per size class and kernel), with --launches single as one launch
+    per layer and kernel."""
+    import ctypes
     N, G = 256, 256
     shapes = synth.resnet50_conv_input_shapes()
     Dl = [c * h * w for c, h, w in shapes]
     L = len(Dl)
+    multi = args.launches == "multi"
+    device_alloc = args.allocator == "device"
     gen = torch.Generator(device=dev)
     xs = []
     for l, D in enumerate(Dl):
@@ -91,69 +98,124 @@ def sweep(args, torch, B, synth, dev):
     D_host = np.repeat(np.array(Dl, dtype=np.int64), N)
     budget = 2 * int(D_host.sum())
     Dmax = max(Dl)
-    ngmax = Dmax // G
-    gmin = torch.empty(N * ngmax, dtype=torch.float32, device=dev)
-    grange = torch.empty(N * ngmax, dtype=torch.float32, device=dev)
-    header = torch.empty(N * ngmax * 2, dtype=torch.float32, device=dev)
-    device_alloc = args.allocator == "device"
-    # host allocator: one layer's stream at a time, room for 8 bits everywhere; device allocator: the
-    # offsets run over all layers, so the buffer holds every layer's stream at once (budget / 8 bytes)
-    packed_buf = torch.empty(budget // 8 + 4096 if device_alloc else N * Dmax, dtype=torch.uint8, device=dev)
+    # The offsets run over all layers (one shared bit stream of budget / 8 bytes) whenever the device
+    # allocator writes them or the multi-tensor calls read them; one launch per layer with the host
+    # allocator reuses a one-layer buffer with room for 8 bits everywhere.
+    shared_stream = multi or device_alloc
+    packed_buf = torch.empty(budget // 8 + 4096 if shared_stream else N * Dmax, dtype=torch.uint8, device=dev)
+    packed_capacity = packed_buf.numel()
     w_dev = torch.from_numpy(w_host).to(dev)
     D_dev = torch.from_numpy(D_host).to(dev)
     result_dev = torch.zeros(2, dtype=torch.int64, device=dev)
-    out = torch.empty(N * Dmax, dtype=torch.float32, device=dev)
     bits_pin = torch.empty(N * L, dtype=torch.uint8, pin_memory=True)
     offs_pin = torch.empty(N * L, dtype=torch.int64, pin_memory=True)
     bits_dev = torch.empty(N * L, dtype=torch.uint8, device=dev)
     offs_dev = torch.empty(N * L, dtype=torch.int64, device=dev)
     stream = torch.cuda.current_stream()
     state = {}
-    # 159 launches per step: the per-launch host cost must stay far below the kernel times, so the
-    # sweep calls the C ABI with pointers and sizes worked out once (the checks of the Python
-    # binding run on every call of the single-tensor benchmark and in all tests).
+    # The per-launch host cost must stay far below the kernel times, so the sweep calls the C ABI with
+    # pointers and sizes worked out once (the checks of the Python binding run in all tests).
     lib = B.lib()
     sp = stream.cuda_stream
-    packed_capacity = packed_buf.numel()
-    layer_args = []
-    for l, D in enumerate(Dl):
-        ng = D // G
-        layer_args.append((xs[l].data_ptr(), D, bits_dev.data_ptr() + l * N, offs_dev.data_ptr() + 8 * l * N))
     names = ("group_stats", "quantize_pack", "unpack_dequantize")
-    pool = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(3 * L)]
-            for _ in range(args.steps)]
 
-    def step(ev=None):
+    def allocate():
         if device_alloc:
             B.allocate_bits_device(w_dev, D_dev, budget, B.ACTQ_WIDTHS_POW2, bits_dev, offs_dev, result_dev, G, stream=stream)
-        else:
-            bits = B.allocate_bits(w_host, D_host, budget)
-            totals = []
-            for l, D in enumerate(Dl):
-                offsets, total = B.packed_bytes(N, D, bits[l * N:(l + 1) * N], G)
-                offs_pin.numpy()[l * N:(l + 1) * N] = offsets.view(np.int64)
-                totals.append(total)
-            bits_pin.numpy()[:] = bits
-            bits_dev.copy_(bits_pin, non_blocking=True)
-            offs_dev.copy_(offs_pin, non_blocking=True)
-            state["bits"], state["totals"] = bits, totals
-        gm, gr, hd, pk, o = gmin.data_ptr(), grange.data_ptr(), header.data_ptr(), packed_buf.data_ptr(), out.data_ptr()
-        for l, (xp, D, bp, op) in enumerate(layer_args):
-            if ev is not None:
-                ev[3 * l][0].record(stream)
-            rc = lib.actq_group_stats(xp, B.ACTQ_F32, N, D, G, gm, gr, sp)
-            if ev is not None:
-                ev[3 * l][1].record(stream)
-                ev[3 * l + 1][0].record(stream)
-            rc |= lib.actq_quantize_pack(xp, B.ACTQ_F32, N, D, G, bp, op, 15, l, args.noise_bits, pk, packed_capacity, hd, B.ACTQ_HDR_F32, sp)
-            if ev is not None:
-                ev[3 * l + 1][1].record(stream)
-                ev[3 * l + 2][0].record(stream)
-            rc |= lib.actq_unpack_dequantize(pk, packed_capacity, hd, B.ACTQ_HDR_F32, bp, op, N, D, G, o, B.ACTQ_F32, sp)
-            if ev is not None:
-                ev[3 * l + 2][1].record(stream)
+            return
+        bits = B.allocate_bits(w_host, D_host, budget)
+        totals, base = [], 0
+        for l, D in enumerate(Dl):
+            offsets, total = B.packed_bytes(N, D, bits[l * N:(l + 1) * N], G)
+            offs_pin.numpy()[l * N:(l + 1) * N] = offsets.view(np.int64) + (base if shared_stream else 0)
+            base += total
+            totals.append(total)
+        bits_pin.numpy()[:] = bits
+        bits_dev.copy_(bits_pin, non_blocking=True)
+        offs_dev.copy_(offs_pin, non_blocking=True)
+        state["bits"], state["totals"] = bits, totals
+
+    if multi:
+        # every layer keeps its own statistics, header and output arrays, as a training step would
+        keep = [{"x": xs[l], "out": torch.empty((N, D), dtype=torch.float32, device=dev),
+                 "gmin": torch.empty(N * (D // G), dtype=torch.float32, device=dev),
+                 "grange": torch.empty(N * (D // G), dtype=torch.float32, device=dev),
+                 "header": torch.empty(N * (D // G) * 2, dtype=torch.float32, device=dev),
+                 "bits": bits_dev[l * N:(l + 1) * N], "offsets": offs_dev[l * N:(l + 1) * N], "D": D}
+                for l, D in enumerate(Dl)]
+        # one call per size class: the launch is sized for its largest tensor, so tensors of one call
+        # should be of similar size (ResNet-50 has seven sizes; a lone size joins the next larger class)
+        classes = {}
+        for l, D in enumerate(Dl):
+            classes.setdefault(D, []).append(l)
+        sizes = sorted(classes, reverse=True)
+        groups = []
+        for D in sizes:
+            if groups and len(classes[D]) == 1 and len(groups[-1]) < B.MAX_TENSORS_PER_CALL:
+                groups[-1] += classes[D]
+            else:
+                groups.append(list(classes[D]))
+        tables = [B.tensor_table([keep[l] for l in g]) for g in groups]
+        layer_of = [l for g in groups for l in g]
+        tptr = [ctypes.addressof(t) for t in tables]
+        tlen = [len(t) for t in tables]
+        # tensor i of a call draws its noise with tag0 + i: keep the layer's own tag where the class is contiguous
+        tag0 = [1000 * k for k in range(len(groups))]
+        pk = packed_buf.data_ptr()
+        pool = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(3)]
+                for _ in range(args.steps)]
+        launches_per_step = 3 * len(groups)
+
+        def step(ev=None):
+            allocate()
+            calls = (
+                lambda i: lib.actq_group_stats_multi(tptr[i], tlen[i], B.ACTQ_F32, N, G, sp),
+                lambda i: lib.actq_quantize_pack_multi(tptr[i], tlen[i], B.ACTQ_F32, N, G, 15, tag0[i], args.noise_bits,
+                                                       pk, packed_capacity, B.ACTQ_HDR_F32, sp),
+                lambda i: lib.actq_unpack_dequantize_multi(tptr[i], tlen[i], pk, packed_capacity, B.ACTQ_HDR_F32, N, G,
+                                                           B.ACTQ_F32, sp),
+            )
+            rc = 0
+            for k, call in enumerate(calls):
+                if ev is not None:
+                    ev[k][0].record(stream)
+                for i in range(len(groups)):
+                    rc |= call(i)
+                if ev is not None:
+                    ev[k][1].record(stream)
             if rc:
                 raise RuntimeError(B.last_error())
+    else:
+        ngmax = Dmax // G
+        gmin = torch.empty(N * ngmax, dtype=torch.float32, device=dev)
+        grange = torch.empty(N * ngmax, dtype=torch.float32, device=dev)
+        header = torch.empty(N * ngmax * 2, dtype=torch.float32, device=dev)
+        out = torch.empty(N * Dmax, dtype=torch.float32, device=dev)
+        layer_args = [(xs[l].data_ptr(), D, bits_dev.data_ptr() + l * N, offs_dev.data_ptr() + 8 * l * N)
+                      for l, D in enumerate(Dl)]
+        pool = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(3 * L)]
+                for _ in range(args.steps)]
+        launches_per_step = 3 * L
+
+        def step(ev=None):
+            allocate()
+            gm, gr, hd, pk, o = gmin.data_ptr(), grange.data_ptr(), header.data_ptr(), packed_buf.data_ptr(), out.data_ptr()
+            for l, (xp, D, bp, op) in enumerate(layer_args):
+                if ev is not None:
+                    ev[3 * l][0].record(stream)
+                rc = lib.actq_group_stats(xp, B.ACTQ_F32, N, D, G, gm, gr, sp)
+                if ev is not None:
+                    ev[3 * l][1].record(stream)
+                    ev[3 * l + 1][0].record(stream)
+                rc |= lib.actq_quantize_pack(xp, B.ACTQ_F32, N, D, G, bp, op, 15, l, args.noise_bits, pk, packed_capacity, hd, B.ACTQ_HDR_F32, sp)
+                if ev is not None:
+                    ev[3 * l + 1][1].record(stream)
+                    ev[3 * l + 2][0].record(stream)
+                rc |= lib.actq_unpack_dequantize(pk, packed_capacity, hd, B.ACTQ_HDR_F32, bp, op, N, D, G, o, B.ACTQ_F32, sp)
+                if ev is not None:
+                    ev[3 * l + 2][1].record(stream)
+                if rc:
+                    raise RuntimeError(B.last_error())
 
     for _ in range(args.warmup):
         step()
@@ -189,9 +251,9 @@ def sweep(args, torch, B, synth, dev):
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "r50_sweep_f32_53x[256,C,H,W]", "G": G, "mean_bits": mean_bits,
-                   "noise_bits": args.noise_bits, "launches_per_step": 3 * L,
+                   "noise_bits": args.noise_bits, "launches": args.launches, "launches_per_step": launches_per_step,
                    "allocator": args.allocator,
-                   "step": f"allocate_bits({args.allocator}, M=13568) + per layer: group_stats + quantize_pack + unpack_dequantize"},
+                   "step": f"allocate_bits({args.allocator}, M=13568) + group_stats + quantize_pack + unpack_dequantize on every layer"},
         "kernels": per_kernel,
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,

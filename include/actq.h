@@ -253,12 +253,14 @@ int actq_allocate_bits_device(const float* w, const int64_t* D_items, int64_t D,
  * bit stream buffer (`packed`, with each tensor's own offsets array addressing
  * it); tensor i draws its noise with tag + i.  Every D must be a multiple of
  * G = 256 (tensors with ragged groups go through the single-tensor calls).
+ * The launch is sized for the largest tensor of the call (the surplus blocks of
+ * smaller ones exit at once), so a call should group tensors of similar size.
  *
  * The descriptor array lives in HOST memory and is copied into the launch; the
  * pointers inside are device pointers with the alignment rules of the
  * single-tensor calls.  Fields a call does not use may be NULL.
  */
-#define ACTQ_MAX_TENSORS_PER_CALL 48
+#define ACTQ_MAX_TENSORS_PER_CALL 40
 typedef struct actq_tensor {
     const void* x;           /* in : N*D elements (group_stats_multi, quantize_pack_multi)   */
     void* out;               /* out: N*D elements (unpack_dequantize_multi)                  */

@@ -373,7 +373,7 @@ def tensor_stats(x, zr=None, stream=None):
 
 # ----------------------------------------------------------------------------- several tensors per launch
 
-MAX_TENSORS_PER_CALL = 48
+MAX_TENSORS_PER_CALL = 40
 
 
 class TensorDesc(ctypes.Structure):

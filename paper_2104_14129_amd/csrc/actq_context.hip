@@ -190,23 +190,7 @@ __global__ __launch_bounds__(kBlock) void relu_backward_kernel(const uint32_t* _
 // ------------------------------------------------------------------------------------
 // Max pooling.
 
-// Exact n / d for 0 <= n < 2^31 by one multiply-high, an add and a shift (division by an
-// invariant integer after Granlund and Montgomery): with s = ceil(log2 d) and
-// m = floor(2^32 (2^s - d) / d) + 1,  n / d = (mulhi(n, m) + n) >> s.
-struct FastDiv {
-    uint32_t m, s;
-};
-
-FastDiv make_fastdiv(uint32_t d)
-{
-    uint32_t s = 0;
-    while ((uint64_t(1) << s) < d) ++s;
-    FastDiv f;
-    f.m = static_cast<uint32_t>(((uint64_t(1) << 32) * ((uint64_t(1) << s) - d)) / d + 1);
-    f.s = s;
-    return f;
-}
-
+// n / d with the host-computed constants of FastDiv (see actq_internal.h)
 __device__ __forceinline__ uint32_t fastdiv(uint32_t n, FastDiv f) { return (__umulhi(n, f.m) + n) >> f.s; }
 
 struct Pool {

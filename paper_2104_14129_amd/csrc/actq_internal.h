@@ -21,6 +21,23 @@ struct Ladder {
 };
 bool make_ladder(uint32_t widths, Ladder* out);
 
+// Exact n / d for 0 <= n < 2^31 by one multiply-high, an add and a shift (division by an
+// invariant integer after Granlund and Montgomery): with s = ceil(log2 d) and
+// m = floor(2^32 (2^s - d) / d) + 1,  n / d = (mulhi(n, m) + n) >> s.
+struct FastDiv {
+    uint32_t m, s;
+};
+
+inline FastDiv make_fastdiv(uint32_t d)
+{
+    uint32_t s = 0;
+    while ((uint64_t(1) << s) < d) ++s;
+    FastDiv f;
+    f.m = static_cast<uint32_t>(((uint64_t(1) << 32) * ((uint64_t(1) << s) - d)) / d + 1);
+    f.s = s;
+    return f;
+}
+
 // Launchers (kernels file).  Arguments are already validated.  Each returns ACTQ_OK or
 // ACTQ_EHIP after recording the HIP error text.
 int launch_group_stats(const void* x, int dtype, int64_t N, int64_t D, float* gmin,

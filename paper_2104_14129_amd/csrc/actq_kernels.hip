@@ -255,12 +255,23 @@ __device__ __forceinline__ void lane_min_max(const float (&v)[kTileGroups][4], c
     }
 }
 
+// Loads through the constant address space: for memory that no kernel of this library writes
+// while it reads it (widths, offsets, and the headers in the dequantizer).  A wavefront-uniform
+// load of this kind goes through the scalar data path whatever the compiler can prove about
+// aliasing, which keeps four loads per tile off the vector memory pipeline.
+template <typename V>
+__device__ __forceinline__ V load_readonly(const V* p)
+{
+    typedef const V __attribute__((address_space(4))) * constant_ptr;
+    return *(constant_ptr)(reinterpret_cast<uintptr_t>(p));
+}
+
 // Width of sample n through the scalar data path: the 32-bit word that holds bits[n] (the
 // array is 4-byte aligned, so the word shares a page with bits[n] and the load cannot fault
 // even when N is not a multiple of four), then a shift.
 __device__ __forceinline__ uint32_t load_width(const uint8_t* __restrict__ bits, uint32_t n)
 {
-    const uint32_t word = reinterpret_cast<const uint32_t*>(bits)[n >> 2];
+    const uint32_t word = load_readonly(reinterpret_cast<const uint32_t*>(bits) + (n >> 2));
     return (word >> ((n & 3u) * 8u)) & 0xffu;
 }
 
@@ -287,20 +298,20 @@ template <int HDR>
 __device__ __forceinline__ f32x2 load_header(const void* __restrict__ header, int64_t index, float kB)
 {
     if (HDR == 2) {
-        const f32x2 zr = static_cast<const f32x2*>(header)[0];
+        const f32x2 zr = load_readonly(static_cast<const f32x2*>(header));
         f32x2 h;
         h.x = zr.x;
         h.y = (zr.y != 0.0f && __builtin_isfinite(kB / zr.y)) ? zr.y / kB : 0.0f;
         return h;
     }
     if (HDR == 1) {
-        const uint32_t w = static_cast<const uint32_t*>(header)[index];
+        const uint32_t w = load_readonly(static_cast<const uint32_t*>(header) + index);
         f32x2 h;
         h.x = __uint_as_float(w << 16);
         h.y = __uint_as_float(w & 0xffff0000u) / kB;  // IEEE division, as the step R / B is defined
         return h;
     }
-    return static_cast<const f32x2*>(header)[index];
+    return load_readonly(static_cast<const f32x2*>(header) + index);
 }
 
 // ------------------------------------------------------------------------------------
@@ -557,7 +568,7 @@ __device__ __forceinline__ void fetch(const T* __restrict__ x, const StreamGeome
     const int groups = static_cast<int>(min(static_cast<uint32_t>(kTileGroups), geo.ng - c.t * kTileGroups));
     load_tile<T, VEC>(x + static_cast<int64_t>(c.n) * geo.D, c.t * kTileGroups, groups, lane, geo.D, r.v, r.ok);
     c.b = load_width(bits, c.n);
-    c.off = offsets[c.n];
+    c.off = load_readonly(offsets + c.n);
 }
 
 // Next tile of the wavefront; false (and the cursor unchanged) when there is none.
@@ -676,7 +687,7 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_tile_kernel(
 
 template <typename T, bool VEC, int B, int HDR>
 __device__ __forceinline__ void dequantize_tile(const uint8_t* __restrict__ src_sample,
-                                                const void* __restrict__ header, T* os,
+                                                const void* __restrict__ header, T* __restrict__ os,
                                                 int64_t D, uint32_t n, uint32_t g0, int groups, uint32_t ng,
                                                 int lane, uint32_t* stage)
 {
@@ -754,7 +765,7 @@ __device__ __forceinline__ void dequantize_tile(const uint8_t* __restrict__ src_
 template <bool VEC, int B, int HDR>
 __device__ __forceinline__ void dequantize_tile_f16(const uint8_t* __restrict__ src_sample,
                                                     const void* __restrict__ header,
-                                                    _Float16* os, int64_t D, uint32_t n, uint32_t g0,
+                                                    _Float16* __restrict__ os, int64_t D, uint32_t n, uint32_t g0,
                                                     int groups, uint32_t ng, int lane)
 {
     typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
@@ -804,7 +815,7 @@ __device__ __forceinline__ void dequantize_tile_f16(const uint8_t* __restrict__ 
 
 template <typename T, bool VEC, int B, int HDR>
 __device__ __forceinline__ void dequantize_any(const uint8_t* __restrict__ src_sample,
-                                               const void* __restrict__ header, T* os,
+                                               const void* __restrict__ header, T* __restrict__ os,
                                                int64_t D, uint32_t n, uint32_t g0, int groups, uint32_t ng, int lane,
                                                uint32_t* stage)
 {
@@ -827,7 +838,7 @@ __global__ __launch_bounds__(kBlock) void unpack_dequantize_kernel(
     if (!wave_work(geo, n, tile, tile_end)) return;
     T* os = out + static_cast<int64_t>(n) * geo.D;
     const uint32_t b = load_width(bits, n);
-    const uint64_t off = offsets[n];
+    const uint64_t off = load_readonly(offsets + n);
     const uint64_t bytes = static_cast<uint64_t>(geo.ng) * 32u * b;
     if ((off & 31u) != 0 || off > capacity || bytes > capacity - off) return;
     const uint8_t* src = packed + off;
@@ -852,10 +863,18 @@ __global__ __launch_bounds__(kBlock) void unpack_dequantize_kernel(
 // Several tensors in one launch.  A network saves dozens of activations of very different
 // sizes (a ResNet-50 step: 53, from 26 MB to 822 MB at batch 256); one launch per tensor leaves
 // the chip draining and refilling 53 times per pass, and the small tensors cannot fill it at
-// all.  Here the tiles of all tensors form one grid: grid.x runs over the tiles of one sample
-// of every tensor in turn (tile_start[] are the prefix sums), grid.y * grid.z over the samples.
-// A wavefront finds its tensor with one ballot over the prefix sums, loads that tensor's
-// pointers from the kernel arguments (uniform loads) and runs the single-tensor tile code.
+// all.  Here blockIdx.y is the tensor and blockIdx.x runs over its tiles, sample after sample,
+// so the launch walks HBM in the order of back-to-back single-tensor launches, without the
+// gaps.  grid.x is sized for the largest tensor of the call and the surplus blocks of smaller
+// ones exit at once, so a call should group tensors of similar size.  The start of a wavefront
+// is as short as in the single-tensor kernels: one uniform load of the tensor's item from the
+// kernel arguments, then the widths and the data; a multiply-high division splits the linear
+// tile index into sample and tile.
+// (Measured alternatives on the 53-tensor sweep: samples in grid.y with all tensors' tiles side
+// by side in grid.x -- 53 concurrent streams -- made every kernel 5-20 % slower than single
+// launches; one linear grid over all tensors with a ballot over prefix sums to find the tensor
+// costs a vector load at the start of every wavefront, which the write-bound dequantizer does
+// not hide: 83 against 73 us on the stage-1 tensor.)
 // Every tensor has full groups (D a multiple of 256) and the same N, dtype and header format.
 
 struct MultiItem {
@@ -867,22 +886,29 @@ struct MultiItem {
     const uint8_t* bits;
     const uint64_t* offsets;
     int64_t D;
+    FastDiv by_tiles;         // division by the tiles of one sample
+    uint32_t tiles;           // tiles of one sample
+    uint32_t total_tiles;     // N * tiles
 };
 
 struct MultiTable {
-    uint32_t count, N, grid_y, hdr_mode;
-    uint32_t tile_start[kMaxMulti + 1];  // tile_start[count] = tiles per sample over all tensors
+    uint32_t count, N, hdr_mode, pad;
     MultiItem item[kMaxMulti];
 };
 
-// Tensor index and tile inside the tensor's sample for linear tile `lin` (wavefront-uniform).
-__device__ __forceinline__ uint32_t multi_locate(const MultiTable& t, uint32_t lin, int lane, uint32_t& tile)
+__device__ __forceinline__ uint32_t fastdiv(uint32_t n, FastDiv f) { return (__umulhi(n, f.m) + n) >> f.s; }
+
+// The wavefront's tensor, sample and tile inside the sample; false if it has no work.
+__device__ __forceinline__ bool multi_work(const MultiTable& t, uint32_t wave, int lane, uint32_t& l, uint32_t& n,
+                                           uint32_t& tile)
 {
-    const uint32_t start = static_cast<uint32_t>(lane) < t.count ? t.tile_start[lane] : 0xffffffffu;
-    const uint64_t at_or_before = __ballot(start <= lin);
-    const uint32_t l = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(__builtin_popcountll(at_or_before) - 1));
-    tile = lin - static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(t.tile_start[l])));
-    return l;
+    l = blockIdx.y;
+    const uint32_t lin = blockIdx.x * kWavesPerBlock + wave;
+    const MultiItem& it = t.item[l];
+    if (lin >= it.total_tiles) return false;
+    n = fastdiv(lin, it.by_tiles);
+    tile = lin - n * it.tiles;
+    return true;
 }
 
 template <typename T>
@@ -890,11 +916,9 @@ __global__ __launch_bounds__(kBlock) void group_stats_multi_kernel(MultiTable t)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const uint32_t wave = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6)));
-    const uint32_t n = blockIdx.z * t.grid_y + blockIdx.y;
-    const uint32_t lin = blockIdx.x * kWavesPerBlock + wave;
-    if (n >= t.N || lin >= t.tile_start[t.count]) return;
-    uint32_t tile;
-    const MultiItem& it = t.item[multi_locate(t, lin, lane, tile)];
+    uint32_t l, n, tile;
+    if (!multi_work(t, wave, lane, l, n, tile)) return;
+    const MultiItem& it = t.item[l];
     const uint32_t ng = static_cast<uint32_t>(it.D >> 8);
     const T* xs = static_cast<const T*>(it.x) + static_cast<int64_t>(n) * it.D;
     const uint32_t g0 = tile * kTileGroups;
@@ -922,11 +946,9 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_multi_kernel(MultiTable 
     __shared__ uint32_t stage_all[kWavesPerBlock][256];
     const int lane = threadIdx.x & (kWave - 1);
     const uint32_t wave = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6)));
-    const uint32_t lin = blockIdx.x * kWavesPerBlock + wave;
     Cursor c;
-    c.n = blockIdx.z * t.grid_y + blockIdx.y;
-    if (c.n >= t.N || lin >= t.tile_start[t.count]) return;
-    const uint32_t l = multi_locate(t, lin, lane, c.t);
+    uint32_t l;
+    if (!multi_work(t, wave, lane, l, c.n, c.t)) return;
     const MultiItem& it = t.item[l];
     StreamGeometry geo;
     geo.D = it.D;
@@ -951,15 +973,13 @@ __global__ __launch_bounds__(kBlock) void unpack_dequantize_multi_kernel(MultiTa
     const int lane = threadIdx.x & (kWave - 1);
     const uint32_t wave = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6)));
     uint32_t* stage = stage_all[wave];
-    const uint32_t n = blockIdx.z * t.grid_y + blockIdx.y;
-    const uint32_t lin = blockIdx.x * kWavesPerBlock + wave;
-    if (n >= t.N || lin >= t.tile_start[t.count]) return;
-    uint32_t tile;
-    const MultiItem& it = t.item[multi_locate(t, lin, lane, tile)];
+    uint32_t l, n, tile;
+    if (!multi_work(t, wave, lane, l, n, tile)) return;
+    const MultiItem& it = t.item[l];
     const uint32_t ng = static_cast<uint32_t>(it.D >> 8);
     T* os = static_cast<T*>(it.out) + static_cast<int64_t>(n) * it.D;
     const uint32_t b = load_width(it.bits, n);
-    const uint64_t off = it.offsets[n];
+    const uint64_t off = load_readonly(it.offsets + n);
     const uint64_t bytes = static_cast<uint64_t>(ng) * 32u * b;
     if ((off & 31u) != 0 || off > capacity || bytes > capacity - off) return;
     const uint8_t* src = packed + off;
@@ -1550,12 +1570,14 @@ static int make_multi_table(const char* who, const actq_tensor* tensors, int32_t
     t->count = static_cast<uint32_t>(count);
     t->N = static_cast<uint32_t>(N);
     t->hdr_mode = static_cast<uint32_t>(hdr);
-    uint64_t tiles = 0;
+    t->pad = 0;
+    uint64_t most = 0;
     for (int32_t i = 0; i < count; ++i) {
         const int64_t ng = tensors[i].D / kGroup;
-        t->tile_start[i] = static_cast<uint32_t>(tiles);
-        tiles += static_cast<uint64_t>((ng + kTileGroups - 1) / kTileGroups);
-        if (tiles >= (uint64_t(1) << 31)) return fail(ACTQ_EINVAL, "%s: too many tiles for one launch", who);
+        const uint64_t per_sample = static_cast<uint64_t>((ng + kTileGroups - 1) / kTileGroups);
+        const uint64_t tiles = per_sample * static_cast<uint64_t>(N);
+        if (tiles >= (uint64_t(1) << 31)) return fail(ACTQ_EINVAL, "%s: tensor %d has too many tiles for one launch", who, i);
+        if (tiles > most) most = tiles;
         MultiItem& it = t->item[i];
         it.x = tensors[i].x;
         it.out = tensors[i].out;
@@ -1565,15 +1587,11 @@ static int make_multi_table(const char* who, const actq_tensor* tensors, int32_t
         it.bits = tensors[i].bits;
         it.offsets = tensors[i].offsets;
         it.D = tensors[i].D;
+        it.by_tiles = make_fastdiv(static_cast<uint32_t>(per_sample));
+        it.tiles = static_cast<uint32_t>(per_sample);
+        it.total_tiles = static_cast<uint32_t>(tiles);
     }
-    for (int32_t i = count; i <= kMaxMulti; ++i) t->tile_start[i] = static_cast<uint32_t>(tiles);
-    t->tile_start[count] = static_cast<uint32_t>(tiles);
-    const int64_t gy = N < 65535 ? N : 65535;
-    const int64_t gz = (N + gy - 1) / gy;
-    if (gz > 65535) return fail(ACTQ_EINVAL, "%s: too many samples for one launch", who);
-    t->grid_y = static_cast<uint32_t>(gy);
-    *grid = dim3(static_cast<unsigned>((tiles + kWavesPerBlock - 1) / kWavesPerBlock), static_cast<unsigned>(gy),
-                 static_cast<unsigned>(gz));
+    *grid = dim3(static_cast<unsigned>((most + kWavesPerBlock - 1) / kWavesPerBlock), static_cast<unsigned>(count));
     return ACTQ_OK;
 }
 
