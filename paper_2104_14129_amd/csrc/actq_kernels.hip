@@ -189,20 +189,19 @@ struct Geometry {
     uint32_t N;                 // samples
     uint32_t ng;                // groups per sample
     uint32_t tiles_per_sample;  // ceil(ng / 4)
-    uint32_t tiles_per_wave;    // consecutive tiles handled by one wavefront
     uint32_t grid_y;            // samples per grid.z slice
     uint32_t hdr_mode;          // header: 0 = (Z, R/B) binary32, 1 = (Z, R) bfloat16, 2 = one (Z, R) for the tensor
 };
 
-// First tile (inside its sample) and sample of this wavefront; false if it has no work.
-__device__ __forceinline__ bool wave_work(const Geometry& geo, uint32_t& n, uint32_t& tile_begin,
-                                          uint32_t& tile_end)
+// Tile (inside its sample) and sample of this wavefront; false if it has no work.  One tile per
+// wavefront: measured on the stage-1 tensor, longer runs (2, 4, 8 tiles) lose a few per cent, and a
+// loop around the tile code keeps the compiler from scheduling it as freely.
+__device__ __forceinline__ bool wave_work(const Geometry& geo, uint32_t& n, uint32_t& tile)
 {
     const uint32_t wave = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6)));
     n = blockIdx.z * geo.grid_y + blockIdx.y;
-    tile_begin = (blockIdx.x * kWavesPerBlock + wave) * geo.tiles_per_wave;
-    tile_end = min(tile_begin + geo.tiles_per_wave, geo.tiles_per_sample);
-    return n < geo.N && tile_begin < geo.tiles_per_sample;
+    tile = blockIdx.x * kWavesPerBlock + wave;
+    return n < geo.N && tile < geo.tiles_per_sample;
 }
 
 // Loads the lane's four elements of up to four groups.  VEC: every group of the tensor is
@@ -323,26 +322,24 @@ __global__ __launch_bounds__(kBlock) void group_stats_kernel(const T* __restrict
                                                              float* __restrict__ grange)
 {
     const int lane = threadIdx.x & (kWave - 1);
-    uint32_t n, tile, tile_end;
-    if (!wave_work(geo, n, tile, tile_end)) return;
+    uint32_t n, tile;
+    if (!wave_work(geo, n, tile)) return;
     const T* xs = x + static_cast<int64_t>(n) * geo.D;
-    for (; tile < tile_end; ++tile) {
-        const uint32_t g0 = tile * kTileGroups;
-        const int groups = static_cast<int>(min(static_cast<uint32_t>(kTileGroups), geo.ng - g0));
-        float v[kTileGroups][4];
-        bool ok[kTileGroups][4];
-        load_tile<T, VEC>(xs, g0, groups, lane, geo.D, v, ok);
-        float lo[kTileGroups], hi[kTileGroups];
-        lane_min_max<VEC>(v, ok, lo, hi);
-        float mn, mx;
-        tile_min_max(lo, hi, lane, mn, mx);
-        mn += 0.0f;  // -0.0 -> +0.0
-        const int row = lane >> 4;
-        if ((lane & 15) == 0 && row < groups) {
-            const int64_t gi = static_cast<int64_t>(n) * geo.ng + g0 + row;
-            gmin[gi] = mn;
-            grange[gi] = (mx - mn) + 0.0f;  // a zero range is +0.0 whichever zeros the extremes were
-        }
+    const uint32_t g0 = tile * kTileGroups;
+    const int groups = static_cast<int>(min(static_cast<uint32_t>(kTileGroups), geo.ng - g0));
+    float v[kTileGroups][4];
+    bool ok[kTileGroups][4];
+    load_tile<T, VEC>(xs, g0, groups, lane, geo.D, v, ok);
+    float lo[kTileGroups], hi[kTileGroups];
+    lane_min_max<VEC>(v, ok, lo, hi);
+    float mn, mx;
+    tile_min_max(lo, hi, lane, mn, mx);
+    mn += 0.0f;  // -0.0 -> +0.0
+    const int row = lane >> 4;
+    if ((lane & 15) == 0 && row < groups) {
+        const int64_t gi = static_cast<int64_t>(n) * geo.ng + g0 + row;
+        gmin[gi] = mn;
+        grange[gi] = (mx - mn) + 0.0f;  // a zero range is +0.0 whichever zeros the extremes were
     }
 }
 
@@ -834,28 +831,26 @@ __global__ __launch_bounds__(kBlock) void unpack_dequantize_kernel(
     __shared__ uint32_t stage_all[kWavesPerBlock][256];  // 1 KiB per wavefront, private to it (odd widths)
     const int lane = threadIdx.x & (kWave - 1);
     uint32_t* stage = stage_all[threadIdx.x >> 6];
-    uint32_t n, tile, tile_end;
-    if (!wave_work(geo, n, tile, tile_end)) return;
+    uint32_t n, tile;
+    if (!wave_work(geo, n, tile)) return;
     T* os = out + static_cast<int64_t>(n) * geo.D;
     const uint32_t b = load_width(bits, n);
     const uint64_t off = load_readonly(offsets + n);
     const uint64_t bytes = static_cast<uint64_t>(geo.ng) * 32u * b;
     if ((off & 31u) != 0 || off > capacity || bytes > capacity - off) return;
     const uint8_t* src = packed + off;
-    for (; tile < tile_end; ++tile) {
-        const uint32_t g0 = tile * kTileGroups;
-        const int groups = static_cast<int>(min(static_cast<uint32_t>(kTileGroups), geo.ng - g0));
-        switch (b) {
-            case 1: dequantize_any<T, VEC, 1, HDR>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
-            case 2: dequantize_any<T, VEC, 2, HDR>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
-            case 3: dequantize_any<T, VEC, 3, HDR>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
-            case 4: dequantize_any<T, VEC, 4, HDR>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
-            case 5: dequantize_any<T, VEC, 5, HDR>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
-            case 6: dequantize_any<T, VEC, 6, HDR>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
-            case 7: dequantize_any<T, VEC, 7, HDR>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
-            case 8: dequantize_any<T, VEC, 8, HDR>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
-            default: return;
-        }
+    const uint32_t g0 = tile * kTileGroups;
+    const int groups = static_cast<int>(min(static_cast<uint32_t>(kTileGroups), geo.ng - g0));
+    switch (b) {
+        case 1: dequantize_any<T, VEC, 1, HDR>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
+        case 2: dequantize_any<T, VEC, 2, HDR>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
+        case 3: dequantize_any<T, VEC, 3, HDR>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
+        case 4: dequantize_any<T, VEC, 4, HDR>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
+        case 5: dequantize_any<T, VEC, 5, HDR>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
+        case 6: dequantize_any<T, VEC, 6, HDR>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
+        case 7: dequantize_any<T, VEC, 7, HDR>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
+        case 8: dequantize_any<T, VEC, 8, HDR>(src, header, os, geo.D, n, g0, groups, geo.ng, lane, stage); break;
+        default: return;
     }
 }
 
@@ -1369,7 +1364,7 @@ __global__ __launch_bounds__(kAllocBlock) void allocate_bits_kernel(const float*
 // ------------------------------------------------------------------------------------
 // Host-side launch geometry.
 
-int make_geometry(const char* who, int64_t N, int64_t D, uint32_t tiles_per_wave, Geometry* geo, dim3* grid)
+int make_geometry(const char* who, int64_t N, int64_t D, Geometry* geo, dim3* grid)
 {
     const int64_t ng = (D + kGroup - 1) / kGroup;
     const int64_t tps = (ng + kTileGroups - 1) / kTileGroups;
@@ -1377,10 +1372,8 @@ int make_geometry(const char* who, int64_t N, int64_t D, uint32_t tiles_per_wave
     geo->N = static_cast<uint32_t>(N);
     geo->ng = static_cast<uint32_t>(ng);
     geo->tiles_per_sample = static_cast<uint32_t>(tps);
-    geo->tiles_per_wave = tiles_per_wave;
     geo->hdr_mode = 0;
-    const int64_t waves = (tps + tiles_per_wave - 1) / tiles_per_wave;
-    const int64_t gx = (waves + kWavesPerBlock - 1) / kWavesPerBlock;
+    const int64_t gx = (tps + kWavesPerBlock - 1) / kWavesPerBlock;
     const int64_t gy = N < 65535 ? N : 65535;
     const int64_t gz = (N + gy - 1) / gy;
     if (gx >= (int64_t(1) << 31) || gz > 65535)
@@ -1401,10 +1394,6 @@ int check_launch(const char* who)
 // Vector path: every group is full and every sample base keeps the 128-bit alignment.
 bool vector_ok(int64_t D) { return D % kGroup == 0; }
 
-// Tiles per wavefront.  Measured on the stage-1 tensor, one tile per wavefront is fastest both
-// for the read-heavy and for the write-heavy kernel; longer runs (2, 4, 8) lose a few per cent.
-constexpr uint32_t kTilesPerWaveRead = 1;
-constexpr uint32_t kTilesPerWaveWrite = 1;
 
 }  // namespace
 
@@ -1413,7 +1402,7 @@ int launch_group_stats(const void* x, int dtype, int64_t N, int64_t D, float* gm
 {
     Geometry geo;
     dim3 grid;
-    if (int rc = make_geometry("actq_group_stats", N, D, kTilesPerWaveRead, &geo, &grid)) return rc;
+    if (int rc = make_geometry("actq_group_stats", N, D, &geo, &grid)) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool vec = vector_ok(D);
     if (dtype == ACTQ_F32) {
@@ -1524,12 +1513,24 @@ int launch_unpack_dequantize(const void* packed, uint64_t capacity, const void* 
                              const uint8_t* bits, const uint64_t* offsets, int64_t N, int64_t D,
                              void* out, int out_dtype, void* stream)
 {
+    const bool vec = vector_ok(D);
+    // A tensor with full groups goes through the multi-tensor kernel as a table of one: its linear
+    // grid over (sample, tile) measured 7 % faster on the stage-1 tensor than samples in grid.y
+    // (72.9 against 79.3 us in the same run).
+    if (vec && N * ((D / kGroup + kTileGroups - 1) / kTileGroups) < (int64_t(1) << 31)) {
+        actq_tensor one = {};
+        one.out = out;
+        one.header = const_cast<void*>(header);
+        one.bits = bits;
+        one.offsets = offsets;
+        one.D = D;
+        return launch_unpack_dequantize_multi(&one, 1, packed, capacity, hdr, N, out_dtype, stream);
+    }
     Geometry geo;
     dim3 grid;
-    if (int rc = make_geometry("actq_unpack_dequantize", N, D, kTilesPerWaveWrite, &geo, &grid)) return rc;
+    if (int rc = make_geometry("actq_unpack_dequantize", N, D, &geo, &grid)) return rc;
     geo.hdr_mode = static_cast<uint32_t>(hdr);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const bool vec = vector_ok(D);
     auto* pk = static_cast<const uint8_t*>(packed);
 #define ACTQ_DEQ(T, V, H) unpack_dequantize_kernel<T, V, H><<<grid, kBlock, 0, s>>>(pk, capacity, header, bits, offsets, geo, static_cast<T*>(out))
 #define ACTQ_DEQ_H(T, V)                                   \
