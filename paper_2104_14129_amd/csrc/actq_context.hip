@@ -471,6 +471,157 @@ static Pool make_pool(const PoolShape& p, int64_t planes, int64_t per_plane, dim
     return g;
 }
 
+// Forward fast path for stride 2, square windows K in {2, 3}, padding <= 1, dilation 1, rows a
+// multiple of four long.  The vector memory pipeline moves 64 bytes per clock and compute unit
+// whatever the width of the load, so nine 32-bit loads per output (16 clocks each for a
+// wavefront) keep it busier than HBM.  Here a lane produces two neighbouring outputs from one
+// aligned 128-bit load per window row plus at most one 32-bit load on either side: three times
+// fewer load cycles per output.  Window positions and their order are those of the kernel above.
+template <typename T, int K>
+__global__ __launch_bounds__(kBlock) void maxpool2d_forward_pair_kernel(const T* __restrict__ x, int64_t planes, Pool g,
+                                                                        QuadGeometry q, T* __restrict__ y,
+                                                                        uint8_t* __restrict__ argmax)
+{
+    typedef typename Quad<T>::vec vec4;
+    const int64_t plane = static_cast<int64_t>(blockIdx.z) * g.grid_y + blockIdx.y;
+    const uint32_t idx = blockIdx.x * kBlock + threadIdx.x;
+    if (plane >= planes || idx >= static_cast<uint32_t>(g.OH * q.quads_per_row)) return;  // pairs per row here
+    const int32_t i = static_cast<int32_t>(fastdiv(idx, q.by_quads));
+    const int32_t m = static_cast<int32_t>(idx) - i * q.quads_per_row;   // outputs 2m and 2m + 1
+    const T* xp = x + plane * g.H * g.W;
+    const int32_t r0 = 2 * i - g.ph;
+    const int32_t c4 = 4 * m;                  // first column of the aligned quad
+    // slot t holds input column c4 - 1 + t: slot 0 the left neighbour, 1..4 the quad, 5 the right neighbour
+    float v[K][6];
+    bool col_ok[6], row_ok[K];
+#pragma unroll
+    for (int t = 0; t < 6; ++t) col_ok[t] = c4 - 1 + t >= 0 && c4 - 1 + t < g.W;
+    const bool quad_ok = c4 + 3 < g.W;
+#pragma unroll
+    for (int a = 0; a < K; ++a) {
+        const int32_t r = r0 + a;
+        row_ok[a] = r >= 0 && r < g.H;
+        const T* row = xp + min(max(r, 0), g.H - 1) * g.W;
+        if (quad_ok) {
+            const vec4 w = *reinterpret_cast<const vec4*>(row + c4);
+            v[a][1] = static_cast<float>(w[0]); v[a][2] = static_cast<float>(w[1]);
+            v[a][3] = static_cast<float>(w[2]); v[a][4] = static_cast<float>(w[3]);
+        } else {
+#pragma unroll
+            for (int t = 1; t < 5; ++t) v[a][t] = static_cast<float>(row[min(c4 - 1 + t, g.W - 1)]);
+        }
+        v[a][0] = static_cast<float>(row[max(c4 - 1, 0)]);
+        v[a][5] = static_cast<float>(row[min(c4 + 4, g.W - 1)]);
+    }
+    float best[2];
+    uint32_t best_k[2];
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        bool have = false;
+        best[e] = 0.0f;
+        best_k[e] = 0;
+#pragma unroll
+        for (int a = 0; a < K; ++a)
+#pragma unroll
+            for (int b = 0; b < K; ++b) {
+                // column 2 * (2m + e) - pw + b = c4 + 2e - pw + b: slot 2e + b + 1 - pw, pw in {0, 1}
+                const float val = g.pw ? v[a][2 * e + b] : v[a][2 * e + b + 1];
+                const bool ok = row_ok[a] && (g.pw ? col_ok[2 * e + b] : col_ok[2 * e + b + 1]);
+                const bool take = ok && (!have || val > best[e]);
+                best[e] = take ? val : best[e];
+                best_k[e] = take ? static_cast<uint32_t>(a * K + b) : best_k[e];
+                have = have || ok;
+            }
+    }
+    const int64_t o = plane * g.OH * g.OW + i * g.OW + 2 * m;
+    if (2 * m + 1 < g.OW) {   // OW is even on this path, so this always holds; kept as the guard of the pair store
+        typedef T pair __attribute__((ext_vector_type(2)));
+        pair out;
+        out[0] = static_cast<T>(best[0]);
+        out[1] = static_cast<T>(best[1]);
+        __builtin_nontemporal_store(out, reinterpret_cast<pair*>(y + o));
+        __builtin_nontemporal_store(static_cast<uint16_t>(best_k[0] | (best_k[1] << 8)), reinterpret_cast<uint16_t*>(argmax + o));
+    }
+}
+
+// Backward fast path for stride 2, square windows K in {2, 3}, padding P <= 1, dilation 1, input
+// rows a multiple of eight and output rows a multiple of four long.  A lane produces eight
+// consecutive inputs of a row.  The outputs whose window can contain one of them are the six
+// columns 4m-1 .. 4m+4 of one or two output rows: their gradients come in as one aligned 128-bit
+// load plus a 32-bit load on either side, their positions as one 32-bit load plus two bytes --
+// twelve loads for eight inputs instead of four loads per input.  Which window position an
+// output column would need for an input column is fixed at compile time; the order of the
+// additions is that of the kernels above (ascending output row, then column).
+template <typename T, int K, int P>
+__global__ __launch_bounds__(kBlock) void maxpool2d_backward_oct_kernel(const uint8_t* __restrict__ argmax,
+                                                                        const T* __restrict__ grad_y, int64_t planes,
+                                                                        Pool g, QuadGeometry q, T* __restrict__ grad_x)
+{
+    typedef typename Quad<T>::vec vec4;
+    constexpr int MR = (K - 1) / 2 + 1;   // output rows whose window can contain one input row
+    const int64_t plane = static_cast<int64_t>(blockIdx.z) * g.grid_y + blockIdx.y;
+    const uint32_t idx = blockIdx.x * kBlock + threadIdx.x;
+    if (plane >= planes || idx >= static_cast<uint32_t>(g.H * q.quads_per_row)) return;  // octets per row here
+    const int32_t r = static_cast<int32_t>(fastdiv(idx, q.by_quads));
+    const int32_t m = static_cast<int32_t>(idx) - r * q.quads_per_row;   // inputs 8m .. 8m+7
+    const uint8_t* ap = argmax + plane * g.OH * g.OW;
+    const T* gp = grad_y + plane * g.OH * g.OW;
+    const int32_t j4 = 4 * m;                 // slot t is output column j4 - 1 + t
+    const int32_t i_hi = (r + P) >> 1;
+    float gy[MR][6];
+    uint32_t code[MR][6];
+    int32_t row_code[MR];                     // a * K for the row, or a value no stored position can match
+    const bool quad_ok = j4 + 3 < g.OW;
+#pragma unroll
+    for (int u = 0; u < MR; ++u) {
+        const int32_t i = i_hi - u;
+        const int32_t a = r + P - 2 * i;      // >= 0
+        row_code[u] = (i >= 0 && i < g.OH && a < K) ? a * K : -1000;
+        const int32_t base = min(max(i, 0), g.OH - 1) * g.OW;
+        if (quad_ok) {
+            const vec4 w = *reinterpret_cast<const vec4*>(gp + base + j4);
+            const uint32_t c = *reinterpret_cast<const uint32_t*>(ap + base + j4);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                gy[u][1 + t] = static_cast<float>(w[t]);
+                code[u][1 + t] = (c >> (8 * t)) & 0xffu;
+            }
+        } else {
+#pragma unroll
+            for (int t = 1; t < 5; ++t) {
+                const int32_t j = j4 - 1 + t;
+                gy[u][t] = static_cast<float>(gp[base + min(j, g.OW - 1)]);
+                code[u][t] = j < g.OW ? static_cast<uint32_t>(ap[base + min(j, g.OW - 1)]) : 0xffffu;
+            }
+        }
+        gy[u][0] = static_cast<float>(gp[base + max(j4 - 1, 0)]);
+        code[u][0] = j4 >= 1 ? static_cast<uint32_t>(ap[base + max(j4 - 1, 0)]) : 0xffffu;
+        gy[u][5] = static_cast<float>(gp[base + min(j4 + 4, g.OW - 1)]);
+        code[u][5] = j4 + 4 < g.OW ? static_cast<uint32_t>(ap[base + min(j4 + 4, g.OW - 1)]) : 0xffffu;
+    }
+    T out[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        float acc = 0.0f;
+#pragma unroll
+        for (int u = MR - 1; u >= 0; --u)     // ascending output row
+#pragma unroll
+            for (int t = 0; t < 6; ++t) {     // ascending output column
+                constexpr int kOffset = P + 2;
+                const int b = e + kOffset - 2 * t;   // position of input column 8m+e in the window of column j4-1+t
+                if (b < 0 || b >= K) continue;
+                acc += static_cast<int32_t>(code[u][t]) == row_code[u] + b ? gy[u][t] : 0.0f;  // + 0 changes nothing
+            }
+        out[e] = static_cast<T>(acc);
+    }
+    T* dst = grad_x + plane * g.H * g.W + r * g.W + 8 * m;
+    vec4 lo, hi;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { lo[e] = out[e]; hi[e] = out[4 + e]; }
+    __builtin_nontemporal_store(lo, reinterpret_cast<vec4*>(dst));
+    __builtin_nontemporal_store(hi, reinterpret_cast<vec4*>(dst) + 1);
+}
+
 static bool aligned_to(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 static bool quad_geometry(const PoolShape& p) {
@@ -481,6 +632,19 @@ template <typename T>
 static void maxpool_forward_typed(const T* x, int64_t planes, const PoolShape& p, T* y, uint8_t* argmax, hipStream_t s)
 {
     dim3 grid;
+    const bool pair_geometry = p.kh == p.kw && (p.kh == 2 || p.kh == 3) && p.sh == 2 && p.sw == 2 && p.dh == 1 &&
+                               p.dw == 1 && p.pw <= 1 && p.W % 4 == 0 && p.OW % 2 == 0 && aligned_to(x, 4 * sizeof(T)) &&
+                               aligned_to(y, 2 * sizeof(T)) && aligned_to(argmax, 2);
+    if (pair_geometry) {
+        QuadGeometry q;
+        q.quads_per_row = p.OW / 2;   // pairs of outputs per row
+        q.by_quads = make_fastdiv(static_cast<uint32_t>(q.quads_per_row));
+        q.vector_ok = 1;
+        const Pool g = make_pool(p, planes, static_cast<int64_t>(p.OH) * q.quads_per_row, &grid);
+        if (p.kh == 3) maxpool2d_forward_pair_kernel<T, 3><<<grid, kBlock, 0, s>>>(x, planes, g, q, y, argmax);
+        else maxpool2d_forward_pair_kernel<T, 2><<<grid, kBlock, 0, s>>>(x, planes, g, q, y, argmax);
+        return;
+    }
     const Pool g = make_pool(p, planes, static_cast<int64_t>(p.OH) * p.OW, &grid);
     if (p.kh == 3 && p.kw == 3) maxpool2d_forward_kernel<T, 3, 3><<<grid, kBlock, 0, s>>>(x, planes, g, y, argmax);
     else if (p.kh == 2 && p.kw == 2) maxpool2d_forward_kernel<T, 2, 2><<<grid, kBlock, 0, s>>>(x, planes, g, y, argmax);
@@ -492,6 +656,24 @@ static void maxpool_backward_typed(const uint8_t* argmax, const T* grad_y, int64
                                    T* grad_x, hipStream_t s)
 {
     dim3 grid;
+    const bool oct_geometry = p.kh == p.kw && (p.kh == 2 || p.kh == 3) && p.sh == 2 && p.sw == 2 && p.dh == 1 &&
+                              p.dw == 1 && p.ph <= 1 && p.pw <= 1 && p.ph == p.pw && p.W % 8 == 0 && p.OW % 4 == 0 &&
+                              aligned_to(grad_x, 4 * sizeof(T)) && aligned_to(grad_y, 4 * sizeof(T)) &&
+                              aligned_to(argmax, 4);
+    if (oct_geometry) {
+        QuadGeometry q;
+        q.quads_per_row = p.W / 8;   // octets of inputs per row
+        q.by_quads = make_fastdiv(static_cast<uint32_t>(q.quads_per_row));
+        q.vector_ok = 1;
+        const Pool g = make_pool(p, planes, static_cast<int64_t>(p.H) * q.quads_per_row, &grid);
+#define ACTQ_POOL_OCT(K, P) maxpool2d_backward_oct_kernel<T, K, P><<<grid, kBlock, 0, s>>>(argmax, grad_y, planes, g, q, grad_x)
+        if (p.kh == 3 && p.pw == 1) ACTQ_POOL_OCT(3, 1);
+        else if (p.kh == 3) ACTQ_POOL_OCT(3, 0);
+        else if (p.pw == 1) ACTQ_POOL_OCT(2, 1);
+        else ACTQ_POOL_OCT(2, 0);
+#undef ACTQ_POOL_OCT
+        return;
+    }
     if (quad_geometry(p)) {
         QuadGeometry q;
         q.quads_per_row = (p.W + 3) / 4;

@@ -95,6 +95,13 @@ CONFIGS = [
     ((3,), 14, 20, (2, 2), (2, 2), (1, 1), (1, 1)),
     ((3,), 15, 19, (3, 3), (2, 2), (0, 0), (1, 1)),
     ((2,), 17, 24, (3, 3), (2, 2), (1, 0), (1, 1)),
+    ((5,), 12, 16, (3, 3), (2, 2), (1, 1), (1, 1)),     # two outputs per lane
+    ((5,), 9, 4, (3, 3), (2, 2), (1, 1), (1, 1)),
+    ((3,), 10, 36, (2, 2), (2, 2), (0, 0), (1, 1)),
+    ((3,), 7, 8, (3, 3), (2, 2), (0, 1), (1, 1)),
+    ((4,), 11, 24, (3, 3), (2, 2), (1, 1), (1, 1)),     # eight inputs per lane in the backward pass
+    ((4,), 6, 32, (2, 2), (2, 2), (0, 0), (1, 1)),
+    ((2,), 5, 8, (3, 3), (2, 2), (1, 1), (1, 1)),
      # more planes than one grid dimension holds
 ]
 
