@@ -544,6 +544,67 @@ __global__ __launch_bounds__(kBlock) void maxpool2d_forward_pair_kernel(const T*
     }
 }
 
+// The same with four outputs per lane when the rows allow it (input rows a multiple of eight and
+// output rows a multiple of four long): two aligned 128-bit loads and at most one 32-bit load per
+// window row serve four windows.
+template <typename T, int K, int P>
+__global__ __launch_bounds__(kBlock) void maxpool2d_forward_four_kernel(const T* __restrict__ x, int64_t planes, Pool g,
+                                                                        QuadGeometry q, T* __restrict__ y,
+                                                                        uint8_t* __restrict__ argmax)
+{
+    typedef typename Quad<T>::vec vec4;
+    const int64_t plane = static_cast<int64_t>(blockIdx.z) * g.grid_y + blockIdx.y;
+    const uint32_t idx = blockIdx.x * kBlock + threadIdx.x;
+    if (plane >= planes || idx >= static_cast<uint32_t>(g.OH * q.quads_per_row)) return;
+    const int32_t i = static_cast<int32_t>(fastdiv(idx, q.by_quads));
+    const int32_t m = static_cast<int32_t>(idx) - i * q.quads_per_row;   // outputs 4m .. 4m+3
+    const T* xp = x + plane * g.H * g.W;
+    const int32_t r0 = 2 * i - P;
+    const int32_t c8 = 8 * m;                  // slot t holds input column c8 - 1 + t
+    float v[K][9];
+    bool row_ok[K];
+    const bool left_ok = c8 >= 1;
+#pragma unroll
+    for (int a = 0; a < K; ++a) {
+        const int32_t r = r0 + a;
+        row_ok[a] = r >= 0 && r < g.H;
+        const T* row = xp + min(max(r, 0), g.H - 1) * g.W;
+        const vec4 w0 = *reinterpret_cast<const vec4*>(row + c8);
+        const vec4 w1 = *reinterpret_cast<const vec4*>(row + c8 + 4);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            v[a][1 + t] = static_cast<float>(w0[t]);
+            v[a][5 + t] = static_cast<float>(w1[t]);
+        }
+        v[a][0] = P ? static_cast<float>(row[max(c8 - 1, 0)]) : 0.0f;
+    }
+    vec4 out;
+    uint32_t codes = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        bool have = false;
+        float best = 0.0f;
+        uint32_t best_k = 0;
+#pragma unroll
+        for (int a = 0; a < K; ++a)
+#pragma unroll
+            for (int b = 0; b < K; ++b) {
+                constexpr int kShift = 1 - P;
+                const int t = 2 * e + b + kShift;  // column 2 * (4m + e) - P + b = c8 - 1 + t
+                const bool ok = row_ok[a] && (t > 0 || left_ok);
+                const bool take = ok && (!have || v[a][t] > best);
+                best = take ? v[a][t] : best;
+                best_k = take ? static_cast<uint32_t>(a * K + b) : best_k;
+                have = have || ok;
+            }
+        out[e] = static_cast<T>(best);
+        codes |= best_k << (8 * e);
+    }
+    const int64_t o = plane * g.OH * g.OW + i * g.OW + 4 * m;
+    __builtin_nontemporal_store(out, reinterpret_cast<vec4*>(y + o));
+    __builtin_nontemporal_store(codes, reinterpret_cast<uint32_t*>(argmax + o));
+}
+
 // Backward fast path for stride 2, square windows K in {2, 3}, padding P <= 1, dilation 1, input
 // rows a multiple of eight and output rows a multiple of four long.  A lane produces eight
 // consecutive inputs of a row.  The outputs whose window can contain one of them are the six
@@ -635,6 +696,20 @@ static void maxpool_forward_typed(const T* x, int64_t planes, const PoolShape& p
     const bool pair_geometry = p.kh == p.kw && (p.kh == 2 || p.kh == 3) && p.sh == 2 && p.sw == 2 && p.dh == 1 &&
                                p.dw == 1 && p.pw <= 1 && p.W % 4 == 0 && p.OW % 2 == 0 && aligned_to(x, 4 * sizeof(T)) &&
                                aligned_to(y, 2 * sizeof(T)) && aligned_to(argmax, 2);
+    // all window columns of four outputs lie inside [8m - 1, 8m + 7]: K = 3 with P = 1, or K = 2 with P = 0
+    const bool four_geometry = pair_geometry && p.ph == p.pw && p.W % 8 == 0 && p.OW % 4 == 0 && 2 * p.OW == p.W &&
+                               ((p.kh == 3 && p.pw == 1) || (p.kh == 2 && p.pw == 0)) &&
+                               aligned_to(y, 4 * sizeof(T)) && aligned_to(argmax, 4);
+    if (four_geometry) {
+        QuadGeometry q;
+        q.quads_per_row = p.OW / 4;
+        q.by_quads = make_fastdiv(static_cast<uint32_t>(q.quads_per_row));
+        q.vector_ok = 1;
+        const Pool g = make_pool(p, planes, static_cast<int64_t>(p.OH) * q.quads_per_row, &grid);
+        if (p.kh == 3) maxpool2d_forward_four_kernel<T, 3, 1><<<grid, kBlock, 0, s>>>(x, planes, g, q, y, argmax);
+        else maxpool2d_forward_four_kernel<T, 2, 0><<<grid, kBlock, 0, s>>>(x, planes, g, q, y, argmax);
+        return;
+    }
     if (pair_geometry) {
         QuadGeometry q;
         q.quads_per_row = p.OW / 2;   // pairs of outputs per row
