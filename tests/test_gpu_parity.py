@@ -471,6 +471,28 @@ def test_device_allocator_feeds_the_quantizer_without_a_host_hop():
     assert np.array_equal(out.cpu().numpy().view(np.uint32), want.view(np.uint32))
 
 
+def test_device_chain_at_the_benchmark_configuration():
+    """The step bench.py times on the stage-1 tensor: group_stats -> sample_sensitivity (with the
+    benchmark's gradient norms) -> device allocator; the widths must be the workload's and equal
+    the oracle's allocation for the sensitivities the device computed."""
+    wl = synth.r50_stage1()
+    x = torch.from_numpy(synth.make_input(wl).reshape(wl.N, wl.D)).cuda()
+    gmin, grange = B.group_stats(x)
+    target = synth.tiered_sensitivities(wl.bits, seed=7)
+    unit = B.sample_sensitivity(grange).cpu().numpy().astype(np.float64)
+    grad2 = torch.from_numpy((target / unit).astype(np.float32)).cuda()
+    w = B.sample_sensitivity(grange, grad2)
+    budget = 2 * wl.N * wl.D
+    bits, offs, res = B.allocate_bits_device(w, wl.D, budget)
+    torch.cuda.synchronize()
+    assert int(res[1]) == 0
+    assert np.array_equal(bits.cpu().numpy(), wl.bits)
+    want = oracle.allocate_bits(w.cpu().numpy(), np.full(wl.N, wl.D, dtype=np.int64), budget)
+    assert np.array_equal(bits.cpu().numpy(), want)
+    ooff, total = oracle.packed_bytes(wl.N, wl.D, 256, want)
+    assert np.array_equal(offs.cpu().numpy().view(np.uint64), ooff) and int(res[0]) == total
+
+
 def test_device_allocator_full_sweep_size():
     """M = 53 layers x 256 samples with the element counts of the ResNet-50 sweep."""
     shapes = synth.resnet50_conv_input_shapes()
