@@ -38,7 +38,7 @@ extern "C" {
 typedef enum actq_status {
     ACTQ_OK = 0,
     ACTQ_EINVAL = -1,      /* bad argument (null, size, alignment, G, dtype, bits) */
-    ACTQ_EINFEASIBLE = -2, /* allocate_bits: budget below one bit per element      */
+    ACTQ_EINFEASIBLE = -2, /* allocate_bits: budget below the narrowest allowed width */
     ACTQ_EHIP = -3         /* the HIP runtime refused the launch                   */
 } actq_status;
 
@@ -98,6 +98,8 @@ int actq_header_bytes(int64_t N, int64_t D, int32_t G, actq_header_format hf, ui
  * gmin   device, out : [N*ng] float, Z of every group; -0.0 is stored as +0.0
  * grange device, out : [N*ng] float, R = max - min rounded to nearest; a zero range is +0.0
  * Only the valid elements of a ragged group take part.
+ * Errors: ACTQ_EINVAL on a null or misaligned pointer, N or D out of range
+ * (N < 2^32, D < 2^34), unsupported G or dtype; ACTQ_EHIP if the launch fails.
  */
 int actq_group_stats(const void* x, actq_dtype dt, int64_t N, int64_t D, int32_t G,
                      float* gmin, float* grange, void* stream);
@@ -137,6 +139,9 @@ int actq_group_stats(const void* x, actq_dtype dt, int64_t N, int64_t D, int32_t
  * bits and offsets live on the device, so the host cannot check them: a sample
  * whose width is not in 1..8 or whose byte range would leave
  * [0, packed_capacity) is skipped (no byte of its output is written).
+ * Errors: ACTQ_EINVAL on a null or misaligned pointer, sizes out of range,
+ * unsupported G, dtype, noise_bits or header format, or a capacity below one bit
+ * per element; ACTQ_EHIP if the launch fails.
  */
 int actq_quantize_pack(const void* x, actq_dtype dt, int64_t N, int64_t D, int32_t G,
                        const uint8_t* bits, const uint64_t* offsets,
@@ -157,6 +162,7 @@ int actq_quantize_pack(const void* x, actq_dtype dt, int64_t N, int64_t D, int32
  * bits, offsets       : as for actq_quantize_pack; a sample that fails the same
  *                       checks against `packed_capacity` is skipped
  * out     device, out : N*D elements of dtype `out_dt`
+ * Errors: as for actq_quantize_pack.
  */
 int actq_unpack_dequantize(const void* packed, uint64_t packed_capacity,
                            const void* header, actq_header_format hf, const uint8_t* bits,
@@ -186,6 +192,8 @@ int actq_tensor_stats(const void* x, actq_dtype dt, int64_t n, float* zr, void* 
  * grad2  device, in  : [N] float, the squared gradient norms (or their running
  *                      estimate, Sec. 4.3); NULL means 1
  * w      device, out : [N] float
+ * Errors: ACTQ_EINVAL on a null or misaligned pointer (grad2 may be null) or
+ * N, ng outside [1, 2^32); ACTQ_EHIP if the launch fails.
  */
 int actq_sample_sensitivity(const float* grange, int64_t N, int64_t ng, int32_t G,
                             const float* grad2, float* w, void* stream);
