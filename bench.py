@@ -33,8 +33,8 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 def parse():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
-    p.add_argument("--steps", type=int, default=30)
-    p.add_argument("--warmup", type=int, default=5)
+    p.add_argument("--steps", type=int, default=100)
+    p.add_argument("--warmup", type=int, default=10)
     p.add_argument("--workload", default="r50_stage1", choices=["r50_stage1", "tiny", "r50_stem_f16", "fpn", "r50_sweep", "contexts", "block"])
     p.add_argument("--noise-bits", type=int, default=16, choices=[24, 16])
     p.add_argument("--header", default="f32", choices=["f32", "bf16"],
