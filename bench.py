@@ -401,8 +401,9 @@ def block(args, torch, dev):
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU only (the path shards with no exchange; "
-              "see DESIGN.md); --gpus N with N > 1 is not supported", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU only (every sample is independent, so data-parallel "
+              "ranks would each quantize their own activations with no exchange); --gpus N with N > 1 "
+              "is not supported", file=sys.stderr)
         sys.exit(2)
 
     import torch
