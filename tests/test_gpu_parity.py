@@ -584,6 +584,65 @@ def test_multi_tensor_call_with_the_maximum_number_of_tensors():
         assert np.array_equal(entries[i]["out"].cpu().numpy().view(np.uint32), want.view(np.uint32)), i
 
 
+# ----------------------------------------------------------------------------- under graph capture
+
+def test_the_whole_step_can_be_captured_in_a_graph_and_replayed():
+    """The library allocates nothing, never synchronises and clears nothing with memset calls, so a
+    caller may capture the step (statistics, sensitivities, device allocator, quantize, dequantize)
+    in a HIP graph.  Every replay -- with new data in the same buffers and eager work in between --
+    must equal the eager result for that data."""
+    wl = synth.r50_stage1(N=16)
+    N, D, ng = wl.N, wl.D, wl.ng
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(3)
+    x = torch.empty((N, D), dtype=torch.float32, device=dev)
+    gmin = torch.empty((N, ng), dtype=torch.float32, device=dev)
+    grange = torch.empty((N, ng), dtype=torch.float32, device=dev)
+    w = torch.empty(N, dtype=torch.float32, device=dev)
+    bits = torch.empty(N, dtype=torch.uint8, device=dev)
+    offs = torch.empty(N, dtype=torch.int64, device=dev)
+    res = torch.empty(2, dtype=torch.int64, device=dev)
+    packed = torch.empty(N * D, dtype=torch.uint8, device=dev)
+    header = torch.empty(N * ng * 2, dtype=torch.float32, device=dev)
+    out = torch.empty((N, D), dtype=torch.float32, device=dev)
+    budget = 3 * N * D
+
+    def step():
+        B.group_stats(x, gmin, grange)
+        B.sample_sensitivity(grange, None, w)
+        B.allocate_bits_device(w, D, budget, B.ACTQ_WIDTHS_ALL, bits, offs, res)
+        B.quantize_pack(x, bits, offs, packed, header, 21, 4, 16)
+        B.unpack_dequantize(packed, header, bits, offs, out)
+
+    def fill(k):
+        scale = np.exp(rng.normal(0, 1.5, (N, 1))).astype(np.float32)
+        x.copy_(torch.from_numpy(np.maximum(rng.standard_normal((N, D)).astype(np.float32), 0) * scale))
+
+    fill(0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                               # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for k in range(1, 4):
+        fill(k)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (bits.clone(), packed.clone(), header.clone(), out.clone(), res.clone())
+        packed.fill_(0xA5)
+        out.fill_(float("nan"))
+        step()                               # eager, same data
+        torch.cuda.synchronize()
+        total = int(res[0])
+        for a, b in zip(got, (bits, packed[:total], header, out, res)):
+            assert torch.equal(a[:total] if a.numel() == packed.numel() else a, b), k
+        assert len(set(bits.cpu().tolist())) > 1 and int(res[1]) == 0
+
+
 # ----------------------------------------------------------------------------- beyond 32-bit indices
 
 def test_element_indices_and_byte_offsets_beyond_32_bits():
