@@ -45,6 +45,8 @@ def parse():
                    help="r50_sweep: all tensors in a few multi-tensor launches, or one launch per tensor and kernel")
     p.add_argument("--uniform-bits", type=int, default=0, choices=range(0, 9), metavar="B",
                    help="give every sample the width B (1..8) instead of the workload's mixed widths")
+    p.add_argument("--event-every", type=int, default=4,
+                   help="single-tensor workloads: record the per-kernel HIP events in every n-th timed step")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--profile-pass", action="store_true",
                    help="for rocprofv3 counter runs: a few launches of each kernel plus a plain device copy "
@@ -559,11 +561,15 @@ def main():
     read_back()
     assert np.array_equal(state["bits"], wl.bits), "allocator did not return the workload's widths"
 
+    # Every `--event-every`-th timed step carries the HIP events that give the per-kernel durations;
+    # the steps in between run bare, so that recording events (about 4 us each on the stream) does
+    # not dominate the gaps between five short launches.
     events = {}
+    every = max(1, args.event_every)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step(events)
+    for i in range(args.steps):
+        step(events if i % every == 0 else None)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -622,7 +628,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": wl.name, "G": G, "mean_bits": float(wl.bits.astype(np.float64).mean()),
                    "noise_bits": args.noise_bits, "header": args.header,
-                   "allocator": args.allocator,
+                   "allocator": args.allocator, "steps_with_events": (args.steps + max(1, args.event_every) - 1) // max(1, args.event_every),
                    "step": ("group_stats + sample_sensitivity + allocate_bits_device + quantize_pack + unpack_dequantize"
                             if args.allocator == "device" else
                             "group_stats + allocate_bits(host) + quantize_pack + unpack_dequantize")},
