@@ -108,7 +108,8 @@ __device__ __forceinline__ void tile_min_max(const float (&lo)[4], const float (
 }
 
 // ------------------------------------------------------------------------------------
-// Philox4x32-10 (Salmon et al., SC'11), state in registers.
+// Philox4x32-10 (Salmon et al., SC'11), state in registers.  The two three-way exclusive-ors
+// of a round are one gfx950 three-input bit operation each (truth table 0x96 = a ^ b ^ c).
 
 __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
                                               uint32_t k0, uint32_t k1, uint32_t (&out)[4])
@@ -117,8 +118,8 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     for (int round = 0; round < 10; ++round) {
         const uint64_t prod_a = static_cast<uint64_t>(c0) * 0xD2511F53u;
         const uint64_t prod_b = static_cast<uint64_t>(c2) * 0xCD9E8D57u;
-        const uint32_t y0 = static_cast<uint32_t>(prod_b >> 32) ^ c1 ^ k0;
-        const uint32_t y2 = static_cast<uint32_t>(prod_a >> 32) ^ c3 ^ k1;
+        const uint32_t y0 = __builtin_amdgcn_bitop3_b32(static_cast<uint32_t>(prod_b >> 32), c1, k0, 0x96);
+        const uint32_t y2 = __builtin_amdgcn_bitop3_b32(static_cast<uint32_t>(prod_a >> 32), c3, k1, 0x96);
         c1 = static_cast<uint32_t>(prod_b);
         c3 = static_cast<uint32_t>(prod_a);
         c0 = y0;
