@@ -14,6 +14,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <type_traits>
 
 #include "actq_internal.h"
 
@@ -605,6 +606,122 @@ __global__ __launch_bounds__(kBlock) void maxpool2d_forward_four_kernel(const T*
     __builtin_nontemporal_store(codes, reinterpret_cast<uint32_t*>(argmax + o));
 }
 
+// Forward path for the common down-sampling pools (3x3 / stride 2 / padding 1 and 2x2 / stride 2 /
+// padding 0 on even extents, H = 2 OH and W = 2 OW, rows a multiple of 16 bytes long).  Because
+// H = 2 OH, output row q = plane * OH + i of the whole tensor reads the rows 2q - P .. 2q - P + K - 1
+// of the whole input, so planes and rows flatten into one index.  A lane owns 16 bytes of an input
+// row (E = 4 or 8 columns) and R consecutive output rows; every load instruction of a wavefront then
+// covers whole cache lines (the window-per-lane kernels above touch each line from several
+// instructions, which makes the first-level cache, not HBM, the limit).  The one column to the left
+// of a lane's 16 bytes (P = 1) comes from the neighbouring lane by a wavefront shift; lane 0 takes
+// it through the scalar data path.
+struct StreamPool {
+    uint32_t chunks_per_row;   // W / E
+    FastDiv by_chunks, by_rows;  // by_rows: division by OH / R
+    uint32_t rows_per_plane;   // OH / R
+    uint32_t total;            // planes * (OH / R) * chunks_per_row
+};
+
+template <typename V>
+__device__ __forceinline__ V load_uniform(const V* p)
+{
+    typedef const V __attribute__((address_space(4))) * constant_ptr;
+    return *(constant_ptr)(reinterpret_cast<uintptr_t>(p));
+}
+
+__device__ __forceinline__ float from_left_lane(float v)
+{
+    constexpr int kWaveShiftRight1 = 0x138;
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), kWaveShiftRight1, 0xf, 0xf, false));
+}
+
+template <typename T, int K, int P, int R>
+__global__ __launch_bounds__(kBlock) void maxpool2d_forward_stream_kernel(const T* __restrict__ x, Pool g, StreamPool q,
+                                                                          T* __restrict__ y,
+                                                                          uint8_t* __restrict__ argmax)
+{
+    constexpr int E = 16 / sizeof(T);    // input columns per lane
+    constexpr int NO = E / 2;            // outputs per lane and output row
+    constexpr int NR = 2 * R + K - 2;    // input rows per lane
+    typedef T vec_in __attribute__((ext_vector_type(E)));
+    typedef T vec_out __attribute__((ext_vector_type(NO)));
+    const uint32_t idx = blockIdx.x * kBlock + threadIdx.x;
+    const bool live = idx < q.total;
+    // lanes past the end repeat the last lane's loads (every lane takes part in the shift) and store nothing
+    const uint32_t id = live ? idx : q.total - 1;
+    const uint32_t strip = fastdiv(id, q.by_chunks);            // plane * (OH / R) + i / R
+    const uint32_t c = id - strip * q.chunks_per_row;
+    const uint32_t plane = fastdiv(strip, q.by_rows);
+    const bool top = strip - plane * q.rows_per_plane == 0;     // the strip starts at output row 0 of its plane
+    const int64_t q0 = static_cast<int64_t>(strip) * R;         // first output row, counted over all planes
+    const bool left_ok = c > 0;
+    const int lane = threadIdx.x & (kWave - 1);
+    float v[NR][E + 1];   // slot 0: the column left of the lane's own, slots 1..E its own
+    bool row_ok[NR];
+#pragma unroll
+    for (int a = 0; a < NR; ++a) {
+        row_ok[a] = !(P == 1 && a == 0 && top);
+        // the row above the plane is padding: read the plane's first row instead and ignore it
+        const int64_t r = 2 * q0 - P + a + (row_ok[a] ? 0 : 1);
+        const T* row = x + r * g.W + static_cast<int64_t>(E) * c;
+        const vec_in w = *reinterpret_cast<const vec_in*>(row);
+#pragma unroll
+        for (int t = 0; t < E; ++t) v[a][1 + t] = static_cast<float>(w[t]);
+        v[a][0] = 0.0f;
+        if (P == 1) {
+            v[a][0] = from_left_lane(v[a][E]);
+            // lane 0 has no neighbour: its left column comes through the scalar data path, as the
+            // aligned 32-bit word that ends where the lane's own 16 bytes start
+            const uint32_t c_first = __builtin_amdgcn_readfirstlane(c);
+            const uint32_t r_lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(r));
+            const uint32_t r_hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(static_cast<uint64_t>(r) >> 32));
+            const int64_t r_first = static_cast<int64_t>((static_cast<uint64_t>(r_hi) << 32) | r_lo);
+            const T* first = x + r_first * g.W + static_cast<int64_t>(E) * c_first;
+            float edge = 0.0f;
+            if (c_first > 0) {
+                const uint32_t word = load_uniform(reinterpret_cast<const uint32_t*>(first) - 1);
+                if (sizeof(T) == 4) edge = __uint_as_float(word);
+                else {
+                    const uint16_t hi = static_cast<uint16_t>(word >> 16);
+                    _Float16 h;
+                    __builtin_memcpy(&h, &hi, 2);
+                    edge = static_cast<float>(h);
+                }
+            }
+            v[a][0] = lane == 0 ? edge : v[a][0];
+        }
+    }
+#pragma unroll
+    for (int rr = 0; rr < R; ++rr) {
+        vec_out out;
+        uint32_t codes = 0;
+#pragma unroll
+        for (int e = 0; e < NO; ++e) {
+            bool have = false;
+            float best = 0.0f;
+            uint32_t best_k = 0;
+#pragma unroll
+            for (int a = 0; a < K; ++a)
+#pragma unroll
+                for (int b = 0; b < K; ++b) {
+                    const int t = 2 * e + b + 1 - P;   // column 2 * (NO c + e) - P + b = E c - 1 + t
+                    const bool ok = row_ok[2 * rr + a] && (t > 0 || left_ok);
+                    const bool take = ok && (!have || v[2 * rr + a][t] > best);
+                    best = take ? v[2 * rr + a][t] : best;
+                    best_k = take ? static_cast<uint32_t>(a * K + b) : best_k;
+                    have = have || ok;
+                }
+            out[e] = static_cast<T>(best);
+            codes |= best_k << (8 * e);
+        }
+        if (!live) continue;
+        const int64_t o = (q0 + rr) * g.OW + static_cast<int64_t>(NO) * c;
+        __builtin_nontemporal_store(out, reinterpret_cast<vec_out*>(y + o));
+        if (NO == 2) __builtin_nontemporal_store(static_cast<uint16_t>(codes), reinterpret_cast<uint16_t*>(argmax + o));
+        else __builtin_nontemporal_store(codes, reinterpret_cast<uint32_t*>(argmax + o));
+    }
+}
+
 // Backward fast path for stride 2, square windows K in {2, 3}, padding P <= 1, dilation 1, input
 // rows a multiple of eight and output rows a multiple of four long.  A lane produces eight
 // consecutive inputs of a row.  The outputs whose window can contain one of them are the six
@@ -683,6 +800,110 @@ __global__ __launch_bounds__(kBlock) void maxpool2d_backward_oct_kernel(const ui
     __builtin_nontemporal_store(hi, reinterpret_cast<vec4*>(dst) + 1);
 }
 
+// Backward counterpart of the streaming forward kernel, for the same geometries.  A lane owns the
+// NO = E / 2 output columns of one output row q (counted over all planes) that lie over its 16
+// bytes of input columns, and produces the two input rows 2q and 2q + 1 there: every gradient and
+// position is loaded once per output row that needs it, in whole cache lines, and the results
+// leave as two 128-bit stores.  With a 3x3 window input row 2q + 1 also lies in the window of
+// output row q + 1, and the lane's last column in that of the first output column of the lane to
+// its right, which arrives by a wavefront shift (lane 63 takes it through the scalar data path).
+// The additions run over ascending output row, then column, as in the kernels above.
+__device__ __forceinline__ uint32_t from_right_lane(uint32_t v)
+{
+    constexpr int kWaveShiftLeft1 = 0x130;
+    return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), kWaveShiftLeft1, 0xf, 0xf, false));
+}
+
+template <typename T, int K, int P>
+__global__ __launch_bounds__(kBlock) void maxpool2d_backward_stream_kernel(const uint8_t* __restrict__ argmax,
+                                                                           const T* __restrict__ grad_y, Pool g,
+                                                                           StreamPool q, T* __restrict__ grad_x)
+{
+    constexpr int E = 16 / sizeof(T);    // input columns per lane
+    constexpr int NO = E / 2;            // output columns per lane
+    constexpr int MR = K == 3 ? 2 : 1;   // output rows whose windows reach the lane's two input rows
+    typedef T vec_in __attribute__((ext_vector_type(E)));
+    typedef T vec_out __attribute__((ext_vector_type(NO)));
+    typedef typename std::conditional<NO == 2, uint16_t, uint32_t>::type code_word;
+    const uint32_t idx = blockIdx.x * kBlock + threadIdx.x;
+    const bool live = idx < q.total;
+    const uint32_t id = live ? idx : q.total - 1;   // every lane takes part in the shift
+    const uint32_t strip = fastdiv(id, q.by_chunks);             // output row over all planes
+    const uint32_t ch = id - strip * q.chunks_per_row;
+    const uint32_t plane = fastdiv(strip, q.by_rows);
+    const bool bottom = strip - plane * q.rows_per_plane == q.rows_per_plane - 1;
+    const bool right_ok = ch + 1 < q.chunks_per_row;
+    const int lane = threadIdx.x & (kWave - 1);
+    float gy[MR][NO + 1];
+    uint32_t code[MR][NO + 1];
+    bool valid[MR];
+#pragma unroll
+    for (int u = 0; u < MR; ++u) {
+        valid[u] = !(u == 1 && bottom);   // below the plane's last output row there is nothing
+        const int64_t at = (static_cast<int64_t>(strip) + (valid[u] ? u : 0)) * g.OW + static_cast<int64_t>(NO) * ch;
+        const vec_out w = *reinterpret_cast<const vec_out*>(grad_y + at);
+        const uint32_t cw = *reinterpret_cast<const code_word*>(argmax + at);
+#pragma unroll
+        for (int t = 0; t < NO; ++t) {
+            gy[u][t] = static_cast<float>(w[t]);
+            code[u][t] = (cw >> (8 * t)) & 0xffu;
+        }
+        gy[u][NO] = 0.0f;
+        code[u][NO] = 0;
+        if (K == 3) {
+            gy[u][NO] = __uint_as_float(from_right_lane(__float_as_uint(gy[u][0])));
+            code[u][NO] = from_right_lane(code[u][0]);
+            // lane 63: the element after its own, as aligned 32-bit words through the scalar data path
+            const uint32_t at_lo = __builtin_amdgcn_readlane(static_cast<uint32_t>(at), kWave - 1);
+            const uint32_t at_hi = __builtin_amdgcn_readlane(static_cast<uint32_t>(static_cast<uint64_t>(at) >> 32), kWave - 1);
+            const bool last_right_ok = __builtin_amdgcn_readlane(static_cast<uint32_t>(right_ok), kWave - 1) != 0;
+            const int64_t next = static_cast<int64_t>((static_cast<uint64_t>(at_hi) << 32) | at_lo) + NO;
+            float edge_g = 0.0f;
+            uint32_t edge_c = 0;
+            if (last_right_ok) {
+                if (sizeof(T) == 4) {
+                    edge_g = __uint_as_float(load_uniform(reinterpret_cast<const uint32_t*>(grad_y) + next));
+                } else {
+                    // NO = 4: the element is 8-byte aligned, so it is the low half of its word
+                    const uint32_t word = load_uniform(reinterpret_cast<const uint32_t*>(grad_y) + (next >> 1));
+                    const uint16_t lo = static_cast<uint16_t>(word);
+                    _Float16 h;
+                    __builtin_memcpy(&h, &lo, 2);
+                    edge_g = static_cast<float>(h);
+                }
+                const uint32_t word = load_uniform(reinterpret_cast<const uint32_t*>(argmax) + (next >> 2));
+                edge_c = (word >> (8 * (static_cast<uint32_t>(next) & 3u))) & 0xffu;
+            }
+            gy[u][NO] = lane == kWave - 1 ? edge_g : gy[u][NO];
+            code[u][NO] = lane == kWave - 1 ? edge_c : code[u][NO];
+        }
+    }
+#pragma unroll
+    for (int rr = 0; rr < 2; ++rr) {
+        vec_in out;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            float acc = 0.0f;
+#pragma unroll
+            for (int u = 0; u < MR; ++u) {            // ascending output row
+                const int a = rr + P - 2 * u;         // row of input row 2q + rr in the window of output row q + u
+                if (a < 0 || a >= K) continue;
+#pragma unroll
+                for (int t = 0; t <= NO; ++t) {       // ascending output column
+                    const int b = e + P - 2 * t;      // column E ch + e in the window of output column NO ch + t
+                    if (b < 0 || b >= K) continue;
+                    const bool ok = valid[u] && (t < NO || right_ok);
+                    acc += ok && code[u][t] == static_cast<uint32_t>(a * K + b) ? gy[u][t] : 0.0f;  // + 0 changes nothing
+                }
+            }
+            out[e] = static_cast<T>(acc);
+        }
+        if (!live) continue;
+        T* dst = grad_x + (2 * static_cast<int64_t>(strip) + rr) * g.W + static_cast<int64_t>(E) * ch;
+        __builtin_nontemporal_store(out, reinterpret_cast<vec_in*>(dst));
+    }
+}
+
 static bool aligned_to(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 static bool quad_geometry(const PoolShape& p) {
@@ -700,6 +921,26 @@ static void maxpool_forward_typed(const T* x, int64_t planes, const PoolShape& p
     const bool four_geometry = pair_geometry && p.ph == p.pw && p.W % 8 == 0 && p.OW % 4 == 0 && 2 * p.OW == p.W &&
                                ((p.kh == 3 && p.pw == 1) || (p.kh == 2 && p.pw == 0)) &&
                                aligned_to(y, 4 * sizeof(T)) && aligned_to(argmax, 4);
+    // the flattened streaming path: even extents, whole 16-byte chunks per row, fewer than 2^31 lanes
+    constexpr int kE = 16 / static_cast<int>(sizeof(T));
+    constexpr int kStreamRows = 1;
+    const bool stream_geometry = four_geometry && 2 * p.OH == p.H && p.W % kE == 0 && p.OH % kStreamRows == 0 &&
+                                 aligned_to(x, 16) &&
+                                 planes * (p.OH / kStreamRows) * (p.W / kE) < (int64_t(1) << 31);
+    if (stream_geometry) {
+        StreamPool q;
+        q.chunks_per_row = static_cast<uint32_t>(p.W / kE);
+        q.by_chunks = make_fastdiv(q.chunks_per_row);
+        q.rows_per_plane = static_cast<uint32_t>(p.OH / kStreamRows);
+        q.by_rows = make_fastdiv(q.rows_per_plane);
+        q.total = static_cast<uint32_t>(planes * q.rows_per_plane * q.chunks_per_row);
+        dim3 unused;
+        const Pool g = make_pool(p, planes, 1, &unused);
+        const unsigned blocks = (q.total + kBlock - 1) / kBlock;
+        if (p.kh == 3) maxpool2d_forward_stream_kernel<T, 3, 1, kStreamRows><<<blocks, kBlock, 0, s>>>(x, g, q, y, argmax);
+        else maxpool2d_forward_stream_kernel<T, 2, 0, kStreamRows><<<blocks, kBlock, 0, s>>>(x, g, q, y, argmax);
+        return;
+    }
     if (four_geometry) {
         QuadGeometry q;
         q.quads_per_row = p.OW / 4;
@@ -735,6 +976,24 @@ static void maxpool_backward_typed(const uint8_t* argmax, const T* grad_y, int64
                               p.dw == 1 && p.ph <= 1 && p.pw <= 1 && p.ph == p.pw && p.W % 8 == 0 && p.OW % 4 == 0 &&
                               aligned_to(grad_x, 4 * sizeof(T)) && aligned_to(grad_y, 4 * sizeof(T)) &&
                               aligned_to(argmax, 4);
+    constexpr int kE = 16 / static_cast<int>(sizeof(T));
+    const bool stream_geometry = oct_geometry && 2 * p.OH == p.H && 2 * p.OW == p.W && p.W % kE == 0 &&
+                                 ((p.kh == 3 && p.pw == 1) || (p.kh == 2 && p.pw == 0)) && aligned_to(grad_x, 16) &&
+                                 aligned_to(grad_y, 8) && planes * p.OH * (p.W / kE) < (int64_t(1) << 31);
+    if (stream_geometry) {
+        StreamPool q;
+        q.chunks_per_row = static_cast<uint32_t>(p.W / kE);
+        q.by_chunks = make_fastdiv(q.chunks_per_row);
+        q.rows_per_plane = static_cast<uint32_t>(p.OH);
+        q.by_rows = make_fastdiv(q.rows_per_plane);
+        q.total = static_cast<uint32_t>(planes * q.rows_per_plane * q.chunks_per_row);
+        dim3 unused;
+        const Pool g = make_pool(p, planes, 1, &unused);
+        const unsigned blocks = (q.total + kBlock - 1) / kBlock;
+        if (p.kh == 3) maxpool2d_backward_stream_kernel<T, 3, 1><<<blocks, kBlock, 0, s>>>(argmax, grad_y, g, q, grad_x);
+        else maxpool2d_backward_stream_kernel<T, 2, 0><<<blocks, kBlock, 0, s>>>(argmax, grad_y, g, q, grad_x);
+        return;
+    }
     if (oct_geometry) {
         QuadGeometry q;
         q.quads_per_row = p.W / 8;   // octets of inputs per row

@@ -102,6 +102,10 @@ CONFIGS = [
     ((4,), 11, 24, (3, 3), (2, 2), (1, 1), (1, 1)),     # eight inputs per lane in the backward pass
     ((4,), 6, 32, (2, 2), (2, 2), (0, 0), (1, 1)),
     ((2,), 5, 8, (3, 3), (2, 2), (1, 1), (1, 1)),
+    ((3,), 6, 520, (3, 3), (2, 2), (1, 1), (1, 1)),     # flattened rows: longer than a wavefront covers
+    ((3,), 4, 264, (2, 2), (2, 2), (0, 0), (1, 1)),
+    ((7,), 2, 8, (3, 3), (2, 2), (1, 1), (1, 1)),       # one output row per plane: first and last at once
+    ((9,), 10, 24, (3, 3), (2, 2), (1, 1), (1, 1)),     # lanes of one wavefront in several planes
      # more planes than one grid dimension holds
 ]
 
