@@ -779,15 +779,24 @@ __device__ __forceinline__ void dequantize_tile_f16(const uint8_t* __restrict__ 
         live[p] = u < groups;
         const uint32_t g = g0 + (live[p] ? u : 0);  // a dead lane re-reads the tile's first group
         const uint8_t* src = src_sample + static_cast<uint64_t>(g) * (32 * B) + li * B;  // 8*B bits per lane
-        if (B == 1) code_lo[p] = __builtin_nontemporal_load(src);
-        if (B == 2) code_lo[p] = __builtin_nontemporal_load(reinterpret_cast<const uint16_t*>(src));
+        if (B < 4) {
+            // the aligned word around the lane's 8*B bits (a group's stream starts 32-byte aligned)
+            const uint32_t word = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(src - ((li * B) & 3)));
+            code_lo[p] = word >> (((li * B) & 3) * 8);
+        }
         if (B == 4) code_lo[p] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(src));
         if (B == 8) {
             const u32x2 w = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(src));
             code_lo[p] = w.x;
             code_hi[p] = w.y;
         }
-        hd[p] = load_header<HDR>(header, static_cast<int64_t>(n) * ng + g, static_cast<float>(code_mask));
+        // both groups' headers through the scalar data path (their indices are uniform), then the
+        // lane's half picks one: a per-lane load would be a second vector load in front of each store
+        const int u_even = 2 * p < groups ? 2 * p : 0, u_odd = 2 * p + 1 < groups ? 2 * p + 1 : 0;
+        const f32x2 hd_even = load_header<HDR>(header, static_cast<int64_t>(n) * ng + g0 + u_even, static_cast<float>(code_mask));
+        const f32x2 hd_odd = load_header<HDR>(header, static_cast<int64_t>(n) * ng + g0 + u_odd, static_cast<float>(code_mask));
+        hd[p].x = half ? hd_odd.x : hd_even.x;
+        hd[p].y = half ? hd_odd.y : hd_even.y;
     }
 #pragma unroll
     for (int p = 0; p < 2; ++p) {
