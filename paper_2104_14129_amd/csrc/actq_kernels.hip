@@ -1156,6 +1156,7 @@ __global__ __launch_bounds__(kSensMaxBlock) void sample_sensitivity_kernel(const
 constexpr int kAllocBlock = 1024;
 constexpr int kAllocWavesMax = kAllocBlock / kWave;
 constexpr int kMaxSteps = 7;
+constexpr int kAllocCached = 12;  // items per thread whose (w, D) the allocator keeps in registers
 
 struct AllocArgs {
     int64_t M;
@@ -1218,10 +1219,15 @@ __device__ __forceinline__ uint64_t block_exclusive_scan(uint64_t v, uint64_t* w
 }
 
 // price of one step of item (w, D): two separately rounded double operations; -0.0 becomes +0.0
+__device__ __forceinline__ uint64_t price_bits(double w, double D, double step_price)
+{
+    const double key = (w * step_price) / D + 0.0;
+    return static_cast<uint64_t>(__double_as_longlong(key));
+}
+
 __device__ __forceinline__ uint64_t price_bits(float w, int64_t D, double step_price)
 {
-    const double key = (static_cast<double>(w) * step_price) / static_cast<double>(D) + 0.0;
-    return static_cast<uint64_t>(__double_as_longlong(key));
+    return price_bits(static_cast<double>(w), static_cast<double>(D), step_price);
 }
 
 __global__ __launch_bounds__(kAllocBlock) void allocate_bits_kernel(const float* __restrict__ w, AllocArgs a,
@@ -1244,27 +1250,35 @@ __global__ __launch_bounds__(kAllocBlock) void allocate_bits_kernel(const float*
     __syncthreads();
     const int widest = width[0], narrowest = width[steps];
 
-    // totals and validation; the first item of every thread keeps its prices in registers
+    // Totals and validation.  The first kAllocCached items of every thread stay in registers, as the
+    // two doubles their prices are computed from (an empty or invalid slot has D = 0), so that the
+    // eight passes below run from registers: a pass that reloads its items pays one memory round
+    // trip per item and thread.  The first item also keeps its prices.
     uint64_t my_elems = 0;
     bool bad = false;
-    uint64_t first_key[kMaxSteps];
-    uint64_t first_D = 0;
+    double cached_w[kAllocCached], cached_D[kAllocCached];   // D < 2^34 is exact in a double
 #pragma unroll
-    for (int r = 0; r < kMaxSteps; ++r) first_key[r] = ~uint64_t(0);
-    for (int64_t i = tid; i < a.M; i += threads) {
+    for (int j = 0; j < kAllocCached; ++j) {
+        const int64_t i = tid + static_cast<int64_t>(j) * threads;
+        const bool live = i < a.M;
+        const float wi = live ? w[i] : 0.0f;
+        const int64_t Di = live ? (a.D_items ? a.D_items[i] : a.D) : 0;
+        const bool ok = live && wi >= 0.0f && __builtin_isfinite(wi) && Di > 0 && Di < (int64_t(1) << 34);
+        bad = bad || (live && !ok);
+        cached_w[j] = static_cast<double>(wi);
+        cached_D[j] = ok ? static_cast<double>(Di) : 0.0;
+        my_elems += ok ? static_cast<uint64_t>(Di) : 0;
+    }
+    uint64_t first_key[kMaxSteps];
+#pragma unroll
+    for (int r = 0; r < kMaxSteps; ++r)
+        first_key[r] = (r < steps && cached_D[0] != 0.0) ? price_bits(cached_w[0], cached_D[0], price[r])
+                                                  : ~uint64_t(0);
+    for (int64_t i = tid + static_cast<int64_t>(kAllocCached) * threads; i < a.M; i += threads) {
         const float wi = w[i];
         const int64_t Di = a.D_items ? a.D_items[i] : a.D;
-        if (!(wi >= 0.0f) || !__builtin_isfinite(wi) || Di <= 0 || Di >= (int64_t(1) << 34)) {
-            bad = true;
-        } else {
-            my_elems += static_cast<uint64_t>(Di);
-            if (i == tid) {
-                first_D = static_cast<uint64_t>(Di);
-#pragma unroll
-                for (int r = 0; r < kMaxSteps; ++r)
-                    if (r < steps) first_key[r] = price_bits(wi, Di, price[r]);
-            }
-        }
+        if (!(wi >= 0.0f) || !__builtin_isfinite(wi) || Di <= 0 || Di >= (int64_t(1) << 34)) bad = true;
+        else my_elems += static_cast<uint64_t>(Di);
     }
     const bool invalid = __syncthreads_or(bad ? 1 : 0) != 0;
     uint64_t elems;
@@ -1283,17 +1297,30 @@ __global__ __launch_bounds__(kAllocBlock) void allocate_bits_kernel(const float*
             uint64_t* h = hist[pass % 3];
             const int shift = 8 * pass;
             // first item: cached prices
-            if (tid < a.M) {
+            if (cached_D[0] != 0.0) {
 #pragma unroll
                 for (int r = 0; r < kMaxSteps; ++r) {
                     if (r >= steps) continue;
                     const uint64_t key = first_key[r];
                     if (pass == 7 || (key >> (shift + 8)) == prefix)
-                        __hip_atomic_fetch_add(&h[(key >> shift) & 255u], first_D * (width[r] - width[r + 1]),
+                        __hip_atomic_fetch_add(&h[(key >> shift) & 255u], static_cast<uint64_t>(cached_D[0]) * (width[r] - width[r + 1]),
                                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                 }
             }
-            for (int64_t i = tid + threads; i < a.M; i += threads) {
+            // further cached items: prices recomputed from registers
+#pragma unroll
+            for (int j = 1; j < kAllocCached; ++j) {
+                if (static_cast<int64_t>(j) * threads >= a.M) break;   // uniform
+                if (cached_D[j] == 0.0) continue;
+                const uint64_t Dj = static_cast<uint64_t>(cached_D[j]);
+                for (int r = 0; r < steps; ++r) {
+                    const uint64_t key = price_bits(cached_w[j], cached_D[j], price[r]);
+                    if (pass == 7 || (key >> (shift + 8)) == prefix)
+                        __hip_atomic_fetch_add(&h[(key >> shift) & 255u], Dj * (width[r] - width[r + 1]),
+                                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                }
+            }
+            for (int64_t i = tid + static_cast<int64_t>(kAllocCached) * threads; i < a.M; i += threads) {
                 const float wi = w[i];
                 const int64_t Di = a.D_items ? a.D_items[i] : a.D;
                 for (int r = 0; r < steps; ++r) {
@@ -1333,11 +1360,19 @@ __global__ __launch_bounds__(kAllocBlock) void allocate_bits_kernel(const float*
     // widths, then offsets, in item order
     uint64_t tie_carry = 0, byte_carry = 0;
     const uint64_t rest = need - below;  // bits still to free among the moves priced exactly at the threshold
+    // the next round's item is loaded before this round's two workgroup scans, which hide the latency
+    float next_w = tid < a.M ? w[tid] : 0.0f;
+    int64_t next_D = tid < a.M ? (a.D_items ? a.D_items[tid] : a.D) : 0;
     for (int64_t base = 0; base < a.M; base += threads) {
         const int64_t i = base + tid;
         const bool live = i < a.M;
-        const float wi = live ? w[i] : 0.0f;
-        int64_t Di = live ? (a.D_items ? a.D_items[i] : a.D) : 0;
+        const float wi = next_w;
+        int64_t Di = next_D;
+        {
+            const int64_t ahead = i + threads;
+            next_w = ahead < a.M ? w[ahead] : 0.0f;
+            next_D = ahead < a.M ? (a.D_items ? a.D_items[ahead] : a.D) : 0;
+        }
         if (Di <= 0 || Di >= (int64_t(1) << 34)) Di = live ? 1 : 0;  // invalid input: stay memory-safe
         int rung = loose ? 0 : steps, ties = 0;
         if (search && live) {

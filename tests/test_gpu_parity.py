@@ -395,7 +395,7 @@ def _check_alloc(w, D, budget, widths, uniform):
 @pytest.mark.parametrize("case", range(40))
 def test_device_allocator_equals_the_greedy(case):
     rng = np.random.default_rng(5000 + case)
-    M = int(rng.choice([1, 2, 7, 64, 128, 500, 1023, 1024, 1025, 3000, 9000]))
+    M = int(rng.choice([1, 2, 7, 64, 128, 500, 1023, 1024, 1025, 3000, 9000, 13000, 20000]))
     w = rng.lognormal(0, 2, M).astype(np.float32)
     if case % 3 == 0:
         w[rng.integers(0, M, M // 3 + 1)] = w[0]                  # equal prices: ties by index
