@@ -1293,6 +1293,9 @@ __global__ __launch_bounds__(kAllocBlock) void allocate_bits_kernel(const float*
     if (search) {
         need = elems * widest - budget;  // bits that must be freed, > 0
         uint64_t prefix = 0;
+        uint32_t alive[(kAllocCached + 3) / 4];   // one byte per cached item: which of its moves are still in play
+#pragma unroll
+        for (int k = 0; k < (kAllocCached + 3) / 4; ++k) alive[k] = ~0u;
         for (int pass = 7; pass >= 0; --pass) {
             uint64_t* h = hist[pass % 3];
             const int shift = 8 * pass;
@@ -1307,18 +1310,27 @@ __global__ __launch_bounds__(kAllocBlock) void allocate_bits_kernel(const float*
                                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                 }
             }
-            // further cached items: prices recomputed from registers
+            // further cached items: prices recomputed from registers, but only for the moves whose
+            // price still matches the digits found so far -- a move that fell out of the prefix in
+            // one pass stays out, and after two passes few are left
 #pragma unroll
             for (int j = 1; j < kAllocCached; ++j) {
                 if (static_cast<int64_t>(j) * threads >= a.M) break;   // uniform
-                if (cached_D[j] == 0.0) continue;
+                constexpr uint32_t kAll = (1u << kMaxSteps) - 1u;
+                const int field = 8 * (j % 4);
+                uint32_t in_play = (alive[j / 4] >> field) & kAll;
+                if (cached_D[j] == 0.0 || in_play == 0) continue;
                 const uint64_t Dj = static_cast<uint64_t>(cached_D[j]);
                 for (int r = 0; r < steps; ++r) {
+                    if (!((in_play >> r) & 1u)) continue;
                     const uint64_t key = price_bits(cached_w[j], cached_D[j], price[r]);
                     if (pass == 7 || (key >> (shift + 8)) == prefix)
                         __hip_atomic_fetch_add(&h[(key >> shift) & 255u], Dj * (width[r] - width[r + 1]),
                                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    else
+                        in_play &= ~(1u << r);
                 }
+                alive[j / 4] = (alive[j / 4] & ~(kAll << field)) | (in_play << field);
             }
             for (int64_t i = tid + static_cast<int64_t>(kAllocCached) * threads; i < a.M; i += threads) {
                 const float wi = w[i];
