@@ -28,6 +28,7 @@
 
 #include <atomic>
 #include <cstdint>
+#include <type_traits>
 
 #include "actq_internal.h"
 
@@ -1156,7 +1157,7 @@ __global__ __launch_bounds__(kSensMaxBlock) void sample_sensitivity_kernel(const
 constexpr int kAllocBlock = 1024;
 constexpr int kAllocWavesMax = kAllocBlock / kWave;
 constexpr int kMaxSteps = 7;
-constexpr int kAllocCached = 12;  // items per thread whose (w, D) the allocator keeps in registers
+constexpr int kAllocCached = 11;  // items per thread whose (w, D) the allocator keeps in registers
 
 struct AllocArgs {
     int64_t M;
@@ -1299,6 +1300,19 @@ __global__ __launch_bounds__(kAllocBlock) void allocate_bits_kernel(const float*
         for (int pass = 7; pass >= 0; --pass) {
             uint64_t* h = hist[pass % 3];
             const int shift = 8 * pass;
+            // A lane adds up the moves it sends to one bin in a row and issues one atomic per run:
+            // in the first passes (sign and exponent bits) nearly every price falls into the same
+            // one or two bins, and 64 lanes adding to one LDS address are served one after another.
+            uint32_t run_bin = 0;
+            uint64_t run_sum = 0;
+            const auto add = [&](uint32_t bin, uint64_t freed) {
+                if (bin != run_bin && run_sum) {
+                    __hip_atomic_fetch_add(&h[run_bin], run_sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    run_sum = 0;
+                }
+                run_bin = bin;
+                run_sum += freed;
+            };
             // first item: cached prices
             if (cached_D[0] != 0.0) {
 #pragma unroll
@@ -1306,8 +1320,7 @@ __global__ __launch_bounds__(kAllocBlock) void allocate_bits_kernel(const float*
                     if (r >= steps) continue;
                     const uint64_t key = first_key[r];
                     if (pass == 7 || (key >> (shift + 8)) == prefix)
-                        __hip_atomic_fetch_add(&h[(key >> shift) & 255u], static_cast<uint64_t>(cached_D[0]) * (width[r] - width[r + 1]),
-                                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                        add(static_cast<uint32_t>(key >> shift) & 255u, static_cast<uint64_t>(cached_D[0]) * (width[r] - width[r + 1]));
                 }
             }
             // further cached items: prices recomputed from registers, but only for the moves whose
@@ -1325,8 +1338,7 @@ __global__ __launch_bounds__(kAllocBlock) void allocate_bits_kernel(const float*
                     if (!((in_play >> r) & 1u)) continue;
                     const uint64_t key = price_bits(cached_w[j], cached_D[j], price[r]);
                     if (pass == 7 || (key >> (shift + 8)) == prefix)
-                        __hip_atomic_fetch_add(&h[(key >> shift) & 255u], Dj * (width[r] - width[r + 1]),
-                                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                        add(static_cast<uint32_t>(key >> shift) & 255u, Dj * (width[r] - width[r + 1]));
                     else
                         in_play &= ~(1u << r);
                 }
@@ -1338,11 +1350,11 @@ __global__ __launch_bounds__(kAllocBlock) void allocate_bits_kernel(const float*
                 for (int r = 0; r < steps; ++r) {
                     const uint64_t key = price_bits(wi, Di, price[r]);
                     if (pass == 7 || (key >> (shift + 8)) == prefix)
-                        __hip_atomic_fetch_add(&h[(key >> shift) & 255u],
-                                               static_cast<uint64_t>(Di) * (width[r] - width[r + 1]),
-                                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                        add(static_cast<uint32_t>(key >> shift) & 255u, static_cast<uint64_t>(Di) * (width[r] - width[r + 1]));
                 }
             }
+            if (run_sum)
+                __hip_atomic_fetch_add(&h[run_bin], run_sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             __syncthreads();
             // Every wavefront finds, for itself, the bin in which the running sum of freed bits
             // first reaches `need`.  Exactly one lane holds it.
@@ -1369,49 +1381,71 @@ __global__ __launch_bounds__(kAllocBlock) void allocate_bits_kernel(const float*
         threshold = prefix;
     }
 
-    // widths, then offsets, in item order
+    // Widths, then offsets, in item order.  A round gives every thread Q consecutive items, so the
+    // two workgroup prefix sums (ties at the threshold, then bytes) run over thread totals: once
+    // per Q * threads items.  The barriers of those sums, not the arithmetic, are what a round costs.
     uint64_t tie_carry = 0, byte_carry = 0;
     const uint64_t rest = need - below;  // bits still to free among the moves priced exactly at the threshold
-    // the next round's item is loaded before this round's two workgroup scans, which hide the latency
-    float next_w = tid < a.M ? w[tid] : 0.0f;
-    int64_t next_D = tid < a.M ? (a.D_items ? a.D_items[tid] : a.D) : 0;
-    for (int64_t base = 0; base < a.M; base += threads) {
-        const int64_t i = base + tid;
-        const bool live = i < a.M;
-        const float wi = next_w;
-        int64_t Di = next_D;
-        {
-            const int64_t ahead = i + threads;
-            next_w = ahead < a.M ? w[ahead] : 0.0f;
-            next_D = ahead < a.M ? (a.D_items ? a.D_items[ahead] : a.D) : 0;
-        }
-        if (Di <= 0 || Di >= (int64_t(1) << 34)) Di = live ? 1 : 0;  // invalid input: stay memory-safe
-        int rung = loose ? 0 : steps, ties = 0;
-        if (search && live) {
-            rung = 0;
-            for (int r = 0; r < steps; ++r) {
-                const uint64_t key = price_bits(wi, Di, price[r]);
-                rung += key < threshold ? 1 : 0;
-                ties += key == threshold ? 1 : 0;
+    const auto assign = [&](auto items_per_thread) {
+        constexpr int Q = decltype(items_per_thread)::value;
+        for (int64_t base = 0; base < a.M; base += static_cast<int64_t>(threads) * Q) {
+            const int64_t i0 = base + static_cast<int64_t>(tid) * Q;
+            int64_t Dq[Q];
+            int rung[Q], ties[Q];
+            bool live[Q];
+            uint64_t tie_bits[Q], tie_sum = 0;
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                const int64_t i = i0 + q;
+                live[q] = i < a.M;
+                const float wi = live[q] ? w[i] : 0.0f;
+                int64_t Di = live[q] ? (a.D_items ? a.D_items[i] : a.D) : 0;
+                if (Di <= 0 || Di >= (int64_t(1) << 34)) Di = live[q] ? 1 : 0;  // invalid input: stay memory-safe
+                Dq[q] = Di;
+                rung[q] = loose ? 0 : steps;
+                ties[q] = 0;
+                if (search && live[q]) {
+                    rung[q] = 0;
+                    for (int r = 0; r < steps; ++r) {
+                        const uint64_t key = price_bits(wi, Di, price[r]);
+                        rung[q] += key < threshold ? 1 : 0;
+                        ties[q] += key == threshold ? 1 : 0;
+                    }
+                }
+                tie_bits[q] = static_cast<uint64_t>(Di) * (width[rung[q]] - width[rung[q] + ties[q]]);
+                tie_sum += tie_bits[q];
+            }
+            uint64_t tie_total;
+            uint64_t before = tie_carry + block_exclusive_scan(tie_sum, wave_totals, tie_total);
+            tie_carry += tie_total;
+            uint64_t my_bytes[Q], byte_sum = 0;
+            int b[Q];
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                uint64_t freed = before;      // by the tie moves of all items before this one
+                before += tie_bits[q];
+                for (; ties[q] > 0 && freed < rest; --ties[q], ++rung[q])
+                    freed += static_cast<uint64_t>(Dq[q]) * (width[rung[q]] - width[rung[q] + 1]);
+                b[q] = width[rung[q]];
+                const uint64_t groups = (static_cast<uint64_t>(Dq[q]) + kGroup - 1) / kGroup;
+                my_bytes[q] = live[q] ? groups * 32u * b[q] : 0;
+                byte_sum += my_bytes[q];
+            }
+            uint64_t byte_total;
+            uint64_t off = byte_carry + block_exclusive_scan(byte_sum, wave_totals, byte_total);
+            byte_carry += byte_total;
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                if (live[q]) {
+                    bits[i0 + q] = static_cast<uint8_t>(b[q]);
+                    offsets[i0 + q] = off;
+                }
+                off += my_bytes[q];
             }
         }
-        const uint64_t tie_bits = static_cast<uint64_t>(Di) * (width[rung] - width[rung + ties]);
-        uint64_t tie_total;
-        uint64_t before = tie_carry + block_exclusive_scan(tie_bits, wave_totals, tie_total);
-        tie_carry += tie_total;
-        for (; ties > 0 && before < rest; --ties, ++rung)
-            before += static_cast<uint64_t>(Di) * (width[rung] - width[rung + 1]);
-        const int b = width[rung];
-        const uint64_t groups = (static_cast<uint64_t>(Di) + kGroup - 1) / kGroup;
-        const uint64_t my_bytes = live ? groups * 32u * b : 0;
-        uint64_t byte_total;
-        const uint64_t off = byte_carry + block_exclusive_scan(my_bytes, wave_totals, byte_total);
-        byte_carry += byte_total;
-        if (live) {
-            bits[i] = static_cast<uint8_t>(b);
-            offsets[i] = off;
-        }
-    }
+    };
+    if (a.M <= threads) assign(std::integral_constant<int, 1>());
+    else assign(std::integral_constant<int, 4>());
     if (tid == 0) {
         result[0] = static_cast<int64_t>(byte_carry);
         result[1] = status;
