@@ -455,6 +455,21 @@ def main():
     from paper_2104_14129_amd import binding as B
     from paper_2104_14129_amd import synth
 
+    codec = args.workload in ("r50_stage1", "tiny", "r50_stem_f16", "fpn")
+    single_thread = None
+    if codec:
+        wl = {"r50_stage1": synth.r50_stage1, "tiny": synth.tiny, "r50_stem_f16": synth.r50_stem_f16,
+              "fpn": synth.fpn}[args.workload]()
+        N, D, ng, G = wl.N, wl.D, wl.ng, wl.G
+        x_np = synth.make_input(wl).reshape(N, D)
+        if args.uniform_bits:
+            wl.bits = np.full(N, args.uniform_bits, dtype=np.uint8)
+        if not args.no_cpu_baseline and not args.profile_pass:
+            # the one-thread leg of the CPU baseline is a child process: started here, before this
+            # process touches the GPU
+            single_thread = oracle_single_thread(x_np, wl.bits, wl.philox_seed, wl.tag, args.noise_bits,
+                                                 args.header == "bf16")
+
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
@@ -467,16 +482,11 @@ def main():
     if args.workload == "block":
         return block(args, torch, dev)
 
-    wl = {"r50_stage1": synth.r50_stage1, "tiny": synth.tiny, "r50_stem_f16": synth.r50_stem_f16,
-          "fpn": synth.fpn}[args.workload]()
-    N, D, ng, G = wl.N, wl.D, wl.ng, wl.G
-    x_np = synth.make_input(wl).reshape(N, D)
     x = torch.from_numpy(x_np).to(dev)
 
     # sensitivities whose greedy allocation at a 2.0-bit budget is the workload's width multiset
     widths = B.ACTQ_WIDTHS_POW2
     if args.uniform_bits:
-        wl.bits = np.full(N, args.uniform_bits, dtype=np.uint8)
         widths = 1 << args.uniform_bits           # the only allowed width
         w_host = np.ones(N, dtype=np.float32)
     else:
@@ -674,8 +684,7 @@ def main():
                         "kind": "oracle",
                         "sample": f"one full step (group_stats + quantize_pack + unpack_dequantize) on the whole "
                                   f"workload, {N * D} elements, {cpu_s:.2f} s",
-                        "single_thread": oracle_single_thread(x_np, wl.bits, wl.philox_seed, wl.tag, args.noise_bits,
-                                                              hf == B.ACTQ_HDR_BF16)}
+                        "single_thread": single_thread}
 
     result = {
         "metric": "quantize+pack and unpack+dequant GB/s (fp32 input); % of HBM peak",
