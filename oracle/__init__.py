@@ -196,7 +196,7 @@ def quantize_pack(x: np.ndarray, bits, seed: int, tag: int = 0, G: int = 256,
     ng = (D + G - 1) // G
     bits = np.ascontiguousarray(bits, dtype=np.uint8)
     offsets, total = packed_bytes(N, D, G, bits)
-    packed = np.zeros(total, dtype=np.uint8)
+    packed = np.full(total, 0xFF, dtype=np.uint8)   # every byte of the stream must come from the oracle
     header = np.empty((N, ng, 2), dtype=np.float32)
     rc = lib().orc_quantize_pack(_p(x2), _dtype_code(x2), N, D, G, _p(bits), _p(offsets),
                                  seed, tag, noise_bits, _p(packed), _p(header))
@@ -228,7 +228,7 @@ def quantize_pack_bf16(x: np.ndarray, bits, seed: int, tag: int = 0, G: int = 25
     ng = (D + G - 1) // G
     bits = np.ascontiguousarray(bits, dtype=np.uint8)
     offsets, total = packed_bytes(N, D, G, bits)
-    packed = np.zeros(total, dtype=np.uint8)
+    packed = np.full(total, 0xFF, dtype=np.uint8)   # every byte of the stream must come from the oracle
     header = np.empty((N, ng, 2), dtype=np.uint16)
     rc = lib().orc_quantize_pack_bf16(_p(x2), _dtype_code(x2), N, D, G, _p(bits), _p(offsets),
                                       seed, tag, noise_bits, _p(packed), _p(header))
@@ -417,7 +417,7 @@ def quantize_pack_tensor(x: np.ndarray, bits, zr, seed: int, tag: int = 0, G: in
     bits = np.ascontiguousarray(bits, dtype=np.uint8)
     zr = np.ascontiguousarray(zr, dtype=np.float32)
     offsets, total = packed_bytes(N, D, G, bits)
-    packed = np.zeros(total, dtype=np.uint8)
+    packed = np.full(total, 0xFF, dtype=np.uint8)   # every byte of the stream must come from the oracle
     rc = lib().orc_quantize_pack_tensor(_p(x), _dtype_code(x), N, D, G, _p(bits), _p(offsets), seed, tag,
                                         noise_bits, _p(zr), _p(packed))
     if rc != OK:
