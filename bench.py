@@ -572,7 +572,8 @@ def main():
         seed, tag, nb = wl.philox_seed, wl.tag, args.noise_bits
         names = ("group_stats", "sensitivity+allocate", "quantize_pack", "unpack_dequantize")
         # five boundary events per step: the end of one launch is the start of the next
-        pool = [[torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)] for _ in range(args.steps)]
+        # (and a sixth right behind the fifth: the interval with nothing in it, which every interval contains)
+        pool = [[torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 2)] for _ in range(args.steps)]
         cursor = [0]
 
         def step(events=None):
@@ -596,6 +597,8 @@ def main():
             rc |= lib.actq_unpack_dequantize(pkp, cap, hp, hf, bp, op, N, D, G, outp, dt, sp)
             if ev:
                 ev[4].record(stream)
+                ev[5].record(stream)
+                events.setdefault("_empty", []).extend([(0, ev[4]), (1, ev[5])])
             if rc:
                 raise RuntimeError(B.last_error())
 
@@ -628,6 +631,10 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
     kernel_ms, kernel_spread = {}, {}
+    empty_marks = events.pop("_empty", None)
+    empty_interval_ms = None
+    if empty_marks:
+        empty_interval_ms = float(np.mean([a.elapsed_time(b) for (_, a), (_, b) in zip(empty_marks[0::2], empty_marks[1::2])]))
     for name, marks in events.items():
         starts = [e for when, e in marks if when == 0]
         stops = [e for when, e in marks if when == 1]
@@ -706,6 +713,7 @@ def main():
                             if args.allocator == "device" else
                             "group_stats + allocate_bits(host) + quantize_pack + unpack_dequantize")},
         "kernels": per_kernel,
+        "empty_event_interval_ms": empty_interval_ms,
         "ceilings": ceilings,
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
