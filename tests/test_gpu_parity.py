@@ -748,3 +748,69 @@ def test_config5_resnet50_sweep_batch256(chunk):
         x = xt.cpu().numpy()
         del xt
         _round_trip(x, bits_all[l * N:(l + 1) * N], seed=15, tag=l, noise_bits=24)
+
+
+# ----------------------------------------------------------------------------- accepted sides of the argument limits
+
+def test_arguments_exactly_at_their_limits_are_accepted():
+    """The host-only tests can only show that a call beyond a limit is refused; here the calls
+    exactly at the limits go through and give the oracle's results."""
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(12)
+    # a stream buffer of exactly one bit per element with every width 1, D with one element in the last group
+    N, D = 3, 2 * 256 + 1
+    x_np = rng.standard_normal((N, D)).astype(np.float32)
+    bits_np = np.ones(N, dtype=np.uint8)
+    off_np, total = B.packed_bytes(N, D, bits_np)
+    assert total == N * 3 * 32
+    x = torch.from_numpy(x_np).to(dev)
+    bits = torch.from_numpy(bits_np).to(dev)
+    offs = torch.from_numpy(off_np.view(np.int64)).to(dev)
+    buf = torch.full((total + 64,), 0xA5, dtype=torch.uint8, device=dev)
+    header = torch.empty(N * 3 * 2, dtype=torch.float32, device=dev)
+    for noise_bits in (16, 24):                         # the two accepted values
+        B.quantize_pack(x, bits, offs, buf[:total], header, seed=3, tag=1, noise_bits=noise_bits)
+        torch.cuda.synchronize()
+        opacked, oheader, _ = oracle.quantize_pack(x_np, bits_np, 3, 1, noise_bits=noise_bits)
+        assert np.array_equal(buf[:total].cpu().numpy(), opacked) and (buf[total:] == 0xA5).all()
+        assert np.array_equal(header.cpu().numpy().view(np.uint32), oheader.reshape(-1).view(np.uint32))
+    # one tensor in a multi-tensor call (the smallest count)
+    xm_np = rng.standard_normal((N, 512)).astype(np.float32)
+    o2, t2 = B.packed_bytes(N, 512, bits_np)
+    entry = {"x": torch.from_numpy(xm_np).to(dev), "out": torch.empty((N, 512), device=dev),
+             "gmin": torch.empty((N, 2), device=dev), "grange": torch.empty((N, 2), device=dev),
+             "header": torch.empty(N * 2 * 2, device=dev), "bits": bits,
+             "offsets": torch.from_numpy(o2.view(np.int64)).to(dev), "D": 512}
+    table = B.tensor_table([entry])
+    pk = torch.zeros(t2, dtype=torch.uint8, device=dev)
+    B.group_stats_multi(table, B.ACTQ_F32, N)
+    B.quantize_pack_multi(table, B.ACTQ_F32, N, pk, seed=3, tag=7, noise_bits=16)
+    torch.cuda.synchronize()
+    omin, orange = oracle.group_stats(xm_np)
+    assert np.array_equal(entry["gmin"].cpu().numpy().view(np.uint32), omin.view(np.uint32))
+    assert np.array_equal(pk.cpu().numpy(), oracle.quantize_pack(xm_np, bits_np, 3, 7, noise_bits=16)[0])
+    # device allocator: a budget of zero is a valid argument (status: infeasible, narrowest widths);
+    # with per-item sizes the common size is ignored, whatever it is
+    M = 5
+    w = torch.from_numpy(rng.lognormal(0, 1, M).astype(np.float32)).to(dev)
+    D_items_np = np.array([1, 255, 256, 257, 1024], dtype=np.int64)
+    D_items = torch.from_numpy(D_items_np).to(dev)
+    got_bits = torch.empty(M, dtype=torch.uint8, device=dev)
+    got_offs = torch.empty(M, dtype=torch.int64, device=dev)
+    res = torch.empty(2, dtype=torch.int64, device=dev)
+    B.allocate_bits_device(w, D_items, 0, B.ACTQ_WIDTHS_ALL, got_bits, got_offs, res)
+    torch.cuda.synchronize()
+    assert int(res[1]) == B.ACTQ_EINFEASIBLE and (got_bits == 1).all()
+    budget = int(3 * D_items_np.sum())
+    B.allocate_bits_device(w, D_items, budget, B.ACTQ_WIDTHS_ALL, got_bits, got_offs, res)
+    torch.cuda.synchronize()
+    want = oracle.allocate_bits(w.cpu().numpy(), D_items_np, budget, oracle.WIDTHS_ALL)
+    assert int(res[1]) == 0 and np.array_equal(got_bits.cpu().numpy(), want)
+    # one item of one element, and a tensor of one element
+    one = torch.ones(1, dtype=torch.float32, device=dev)
+    B.allocate_bits_device(one, 1, 4, B.ACTQ_WIDTHS_POW2, got_bits[:1], got_offs[:1], res)
+    torch.cuda.synchronize()
+    assert int(res[1]) == 0 and int(got_bits[0]) == 4 and int(res[0]) == 32 * 4
+    zr = B.tensor_stats(torch.full((16,), 2.5, device=dev)[:1].contiguous())
+    torch.cuda.synchronize()
+    assert zr.cpu().tolist() == [2.5, 0.0]
