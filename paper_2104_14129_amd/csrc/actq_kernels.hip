@@ -761,7 +761,7 @@ __device__ __forceinline__ void dequantize_tile(const uint8_t* __restrict__ src_
 // takes eight consecutive elements (16 bytes) and the wavefront covers two groups per step
 // (lanes 0..31 the even group, lanes 32..63 the odd one).  Unpacking is free to choose its
 // lane-to-element map: nothing is reduced across lanes.
-template <bool VEC, int B, int HDR>
+template <bool VEC, int B, int HDR, int NP = 2>
 __device__ __forceinline__ void dequantize_tile_f16(const uint8_t* __restrict__ src_sample,
                                                     const void* __restrict__ header,
                                                     _Float16* __restrict__ os, int64_t D, uint32_t n, uint32_t g0,
@@ -771,11 +771,12 @@ __device__ __forceinline__ void dequantize_tile_f16(const uint8_t* __restrict__ 
     constexpr uint32_t code_mask = (1u << B) - 1u;
     const int half = lane >> 5;   // which group of the pair
     const int li = lane & 31;     // position inside the group: elements 8*li .. 8*li+7
-    uint32_t code_lo[2] = {0, 0}, code_hi[2] = {0, 0};  // 8*B bits per lane; the high word only for B = 8
-    f32x2 hd[2];
-    bool live[2];
+    uint32_t code_lo[NP], code_hi[NP];  // 8*B bits per lane; the high word only for B = 8
+    f32x2 hd[NP];
+    bool live[NP];
 #pragma unroll
-    for (int p = 0; p < 2; ++p) {
+    for (int p = 0; p < NP; ++p) {
+        code_lo[p] = code_hi[p] = 0;
         const int u = 2 * p + half;
         live[p] = u < groups;
         const uint32_t g = g0 + (live[p] ? u : 0);  // a dead lane re-reads the tile's first group
@@ -800,7 +801,7 @@ __device__ __forceinline__ void dequantize_tile_f16(const uint8_t* __restrict__ 
         hd[p].y = half ? hd_odd.y : hd_even.y;
     }
 #pragma unroll
-    for (int p = 0; p < 2; ++p) {
+    for (int p = 0; p < NP; ++p) {
         const uint32_t g = g0 + 2 * p + half;
         f16x8 o;
 #pragma unroll
@@ -821,16 +822,25 @@ __device__ __forceinline__ void dequantize_tile_f16(const uint8_t* __restrict__ 
     }
 }
 
-template <typename T, bool VEC, int B, int HDR>
+// NG groups starting at g0 (NG = 4, or 8 for binary16 output in the multi-tensor kernel).
+template <typename T, bool VEC, int B, int HDR, int NG = kTileGroups>
 __device__ __forceinline__ void dequantize_any(const uint8_t* __restrict__ src_sample,
                                                const void* __restrict__ header, T* __restrict__ os,
                                                int64_t D, uint32_t n, uint32_t g0, int groups, uint32_t ng, int lane,
                                                uint32_t* stage)
 {
-    if constexpr (sizeof(T) == 2 && (8 % B) == 0)
-        dequantize_tile_f16<VEC, B, HDR>(src_sample, header, os, D, n, g0, groups, ng, lane);
-    else
-        dequantize_tile<T, VEC, B, HDR>(src_sample, header, os, D, n, g0, groups, ng, lane, stage);
+    static_assert(NG % kTileGroups == 0, "whole tiles");
+    if constexpr (sizeof(T) == 2 && (8 % B) == 0) {
+        dequantize_tile_f16<VEC, B, HDR, NG / 2>(src_sample, header, os, D, n, g0, groups, ng, lane);
+    } else {
+#pragma unroll
+        for (int t = 0; t < NG / kTileGroups; ++t) {
+            const int left = groups - t * kTileGroups;     // uniform
+            if (left <= 0) break;
+            dequantize_tile<T, VEC, B, HDR>(src_sample, header, os, D, n, g0 + t * kTileGroups,
+                                            left < kTileGroups ? left : kTileGroups, ng, lane, stage);
+        }
+    }
 }
 
 template <typename T, bool VEC, int HDR>
@@ -971,7 +981,7 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_multi_kernel(MultiTable 
                                    static_cast<uint32_t>(tensor_tag >> 32), packed, capacity, it.header, stage_all[wave]);
 }
 
-template <typename T, int HDR>
+template <typename T, int HDR, int NG>
 __global__ __launch_bounds__(kBlock) void unpack_dequantize_multi_kernel(MultiTable t, const uint8_t* __restrict__ packed,
                                                                          uint64_t capacity)
 {
@@ -989,17 +999,17 @@ __global__ __launch_bounds__(kBlock) void unpack_dequantize_multi_kernel(MultiTa
     const uint64_t bytes = static_cast<uint64_t>(ng) * 32u * b;
     if ((off & 31u) != 0 || off > capacity || bytes > capacity - off) return;
     const uint8_t* src = packed + off;
-    const uint32_t g0 = tile * kTileGroups;
-    const int groups = static_cast<int>(min(static_cast<uint32_t>(kTileGroups), ng - g0));
+    const uint32_t g0 = tile * NG;
+    const int groups = static_cast<int>(min(static_cast<uint32_t>(NG), ng - g0));
     switch (b) {
-        case 1: dequantize_any<T, true, 1, HDR>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
-        case 2: dequantize_any<T, true, 2, HDR>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
-        case 3: dequantize_any<T, true, 3, HDR>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
-        case 4: dequantize_any<T, true, 4, HDR>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
-        case 5: dequantize_any<T, true, 5, HDR>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
-        case 6: dequantize_any<T, true, 6, HDR>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
-        case 7: dequantize_any<T, true, 7, HDR>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
-        case 8: dequantize_any<T, true, 8, HDR>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
+        case 1: dequantize_any<T, true, 1, HDR, NG>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
+        case 2: dequantize_any<T, true, 2, HDR, NG>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
+        case 3: dequantize_any<T, true, 3, HDR, NG>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
+        case 4: dequantize_any<T, true, 4, HDR, NG>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
+        case 5: dequantize_any<T, true, 5, HDR, NG>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
+        case 6: dequantize_any<T, true, 6, HDR, NG>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
+        case 7: dequantize_any<T, true, 7, HDR, NG>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
+        case 8: dequantize_any<T, true, 8, HDR, NG>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
         default: return;
     }
 }
@@ -1657,7 +1667,7 @@ int launch_allocate_bits(const float* w, const int64_t* D_items, int64_t D, int6
 }
 
 static int make_multi_table(const char* who, const actq_tensor* tensors, int32_t count, int64_t N, int hdr,
-                            MultiTable* t, dim3* grid)
+                            MultiTable* t, dim3* grid, int groups_per_wave = kTileGroups)
 {
     t->count = static_cast<uint32_t>(count);
     t->N = static_cast<uint32_t>(N);
@@ -1666,7 +1676,7 @@ static int make_multi_table(const char* who, const actq_tensor* tensors, int32_t
     uint64_t most = 0;
     for (int32_t i = 0; i < count; ++i) {
         const int64_t ng = tensors[i].D / kGroup;
-        const uint64_t per_sample = static_cast<uint64_t>((ng + kTileGroups - 1) / kTileGroups);
+        const uint64_t per_sample = static_cast<uint64_t>((ng + groups_per_wave - 1) / groups_per_wave);
         const uint64_t tiles = per_sample * static_cast<uint64_t>(N);
         if (tiles >= (uint64_t(1) << 31)) return fail(ACTQ_EINVAL, "%s: tensor %d has too many tiles for one launch", who, i);
         if (tiles > most) most = tiles;
@@ -1722,16 +1732,19 @@ int launch_unpack_dequantize_multi(const actq_tensor* tensors, int32_t count, co
 {
     MultiTable t;
     dim3 grid;
-    if (int rc = make_multi_table("actq_unpack_dequantize_multi", tensors, count, N, hdr, &t, &grid)) return rc;
+    // binary16 output: eight groups per wavefront, so that a wavefront writes the same 4 KiB as with binary32
+    constexpr int kGroupsF16 = 2 * kTileGroups;
+    const int per_wave = out_dtype == ACTQ_F16 ? kGroupsF16 : kTileGroups;
+    if (int rc = make_multi_table("actq_unpack_dequantize_multi", tensors, count, N, hdr, &t, &grid, per_wave)) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint8_t* pk = static_cast<const uint8_t*>(packed);
-#define ACTQ_DEQM(T)                                                                                     \
+#define ACTQ_DEQM(T, NG)                                                                                    \
     do {                                                                                                 \
-        if (hdr == ACTQ_HDR_F32) unpack_dequantize_multi_kernel<T, 0><<<grid, kBlock, 0, s>>>(t, pk, capacity);       \
-        else if (hdr == ACTQ_HDR_BF16) unpack_dequantize_multi_kernel<T, 1><<<grid, kBlock, 0, s>>>(t, pk, capacity); \
-        else unpack_dequantize_multi_kernel<T, 2><<<grid, kBlock, 0, s>>>(t, pk, capacity);                           \
+        if (hdr == ACTQ_HDR_F32) unpack_dequantize_multi_kernel<T, 0, NG><<<grid, kBlock, 0, s>>>(t, pk, capacity);       \
+        else if (hdr == ACTQ_HDR_BF16) unpack_dequantize_multi_kernel<T, 1, NG><<<grid, kBlock, 0, s>>>(t, pk, capacity); \
+        else unpack_dequantize_multi_kernel<T, 2, NG><<<grid, kBlock, 0, s>>>(t, pk, capacity);                           \
     } while (0)
-    if (out_dtype == ACTQ_F32) ACTQ_DEQM(float); else ACTQ_DEQM(_Float16);
+    if (out_dtype == ACTQ_F32) ACTQ_DEQM(float, kTileGroups); else ACTQ_DEQM(_Float16, kGroupsF16);
 #undef ACTQ_DEQM
     return check_launch("actq_unpack_dequantize_multi");
 }
