@@ -1241,6 +1241,7 @@ __device__ __forceinline__ uint64_t price_bits(float w, int64_t D, double step_p
     return price_bits(static_cast<double>(w), static_cast<double>(D), step_price);
 }
 
+template <int CACHED>
 __global__ __launch_bounds__(kAllocBlock) void allocate_bits_kernel(const float* __restrict__ w, AllocArgs a,
                                                                     uint8_t* __restrict__ bits,
                                                                     uint64_t* __restrict__ offsets,
@@ -1261,15 +1262,16 @@ __global__ __launch_bounds__(kAllocBlock) void allocate_bits_kernel(const float*
     __syncthreads();
     const int widest = width[0], narrowest = width[steps];
 
-    // Totals and validation.  The first kAllocCached items of every thread stay in registers, as the
+    // Totals and validation.  The first CACHED items of every thread stay in registers, as the
     // two doubles their prices are computed from (an empty or invalid slot has D = 0), so that the
     // eight passes below run from registers: a pass that reloads its items pays one memory round
-    // trip per item and thread.  The first item also keeps its prices.
+    // trip per item and thread.  The first item also keeps its prices.  (CACHED is 1 when every
+    // thread has at most one item, which keeps the kernel of the small problem small.)
     uint64_t my_elems = 0;
     bool bad = false;
-    double cached_w[kAllocCached], cached_D[kAllocCached];   // D < 2^34 is exact in a double
+    double cached_w[CACHED], cached_D[CACHED];   // D < 2^34 is exact in a double
 #pragma unroll
-    for (int j = 0; j < kAllocCached; ++j) {
+    for (int j = 0; j < CACHED; ++j) {
         const int64_t i = tid + static_cast<int64_t>(j) * threads;
         const bool live = i < a.M;
         const float wi = live ? w[i] : 0.0f;
@@ -1285,7 +1287,7 @@ __global__ __launch_bounds__(kAllocBlock) void allocate_bits_kernel(const float*
     for (int r = 0; r < kMaxSteps; ++r)
         first_key[r] = (r < steps && cached_D[0] != 0.0) ? price_bits(cached_w[0], cached_D[0], price[r])
                                                   : ~uint64_t(0);
-    for (int64_t i = tid + static_cast<int64_t>(kAllocCached) * threads; i < a.M; i += threads) {
+    for (int64_t i = tid + static_cast<int64_t>(CACHED) * threads; i < a.M; i += threads) {
         const float wi = w[i];
         const int64_t Di = a.D_items ? a.D_items[i] : a.D;
         if (!(wi >= 0.0f) || !__builtin_isfinite(wi) || Di <= 0 || Di >= (int64_t(1) << 34)) bad = true;
@@ -1304,9 +1306,9 @@ __global__ __launch_bounds__(kAllocBlock) void allocate_bits_kernel(const float*
     if (search) {
         need = elems * widest - budget;  // bits that must be freed, > 0
         uint64_t prefix = 0;
-        uint32_t alive[(kAllocCached + 3) / 4];   // one byte per cached item: which of its moves are still in play
+        uint32_t alive[(CACHED + 3) / 4];   // one byte per cached item: which of its moves are still in play
 #pragma unroll
-        for (int k = 0; k < (kAllocCached + 3) / 4; ++k) alive[k] = ~0u;
+        for (int k = 0; k < (CACHED + 3) / 4; ++k) alive[k] = ~0u;
         for (int pass = 7; pass >= 0; --pass) {
             uint64_t* h = hist[pass % 3];
             const int shift = 8 * pass;
@@ -1337,7 +1339,7 @@ __global__ __launch_bounds__(kAllocBlock) void allocate_bits_kernel(const float*
             // price still matches the digits found so far -- a move that fell out of the prefix in
             // one pass stays out, and after two passes few are left
 #pragma unroll
-            for (int j = 1; j < kAllocCached; ++j) {
+            for (int j = 1; j < CACHED; ++j) {
                 if (static_cast<int64_t>(j) * threads >= a.M) break;   // uniform
                 constexpr uint32_t kAll = (1u << kMaxSteps) - 1u;
                 const int field = 8 * (j % 4);
@@ -1354,7 +1356,7 @@ __global__ __launch_bounds__(kAllocBlock) void allocate_bits_kernel(const float*
                 }
                 alive[j / 4] = (alive[j / 4] & ~(kAll << field)) | (in_play << field);
             }
-            for (int64_t i = tid + static_cast<int64_t>(kAllocCached) * threads; i < a.M; i += threads) {
+            for (int64_t i = tid + static_cast<int64_t>(CACHED) * threads; i < a.M; i += threads) {
                 const float wi = w[i];
                 const int64_t Di = a.D_items ? a.D_items[i] : a.D;
                 for (int r = 0; r < steps; ++r) {
@@ -1662,7 +1664,8 @@ int launch_allocate_bits(const float* w, const int64_t* D_items, int64_t D, int6
     // a workgroup no larger than the problem: barriers and scans get cheaper with fewer wavefronts
     const int64_t lanes = (M + kWave - 1) / kWave * kWave;
     const int block = static_cast<int>(lanes < kAllocBlock ? lanes : kAllocBlock);
-    allocate_bits_kernel<<<1, block, 0, static_cast<hipStream_t>(stream)>>>(w, a, bits, offsets, result);
+    if (M <= block) allocate_bits_kernel<1><<<1, block, 0, static_cast<hipStream_t>(stream)>>>(w, a, bits, offsets, result);
+    else allocate_bits_kernel<kAllocCached><<<1, block, 0, static_cast<hipStream_t>(stream)>>>(w, a, bits, offsets, result);
     return check_launch("actq_allocate_bits_device");
 }
 
