@@ -675,6 +675,19 @@ def main():
                 "traffic": None if args.uniform_bits else measured_traffic(wl.name, args.noise_bits, dominant),
                 "algorithmic_bytes_per_launch": alg[dominant], "avg_launch_ms": kernel_ms[dominant]}
 
+    if wl.dtype == "f16" and dominant == "quantize_pack" and args.noise_bits == 16 and hf == B.ACTQ_HDR_F32:
+        # The binary16 quantizer is bound by vector-ALU issue, not by HBM (rocprofv3 shows every SIMD issuing
+        # all the time): its roofline is the issue rate of one wavefront instruction per four clocks and SIMD.
+        # The instruction count per 1024 elements is the SQ_INSTS_VALU figure of
+        # profiles/sq_counters_r50_stem_f16_noise16.md; the duration is this run's.
+        valu_per_tile = 352
+        issued = valu_per_tile * (N * D / 1024) / (kernel_ms[dominant] * 1e-3) / 1e9
+        peak = 1024 * 2.4 / 4                      # 256 compute units x 4 SIMDs at 2.4 GHz: G wavefront instructions / s
+        roofline = {"bound": "alu", "kernel": dominant, "achieved": issued, "peak": peak,
+                    "unit": "G wavefront instructions/s", "frac": issued / peak, "traffic": None,
+                    "valu_instructions_per_1024_elements": valu_per_tile, "avg_launch_ms": kernel_ms[dominant],
+                    "hbm_frac": achieved / HBM_PEAK_GBS}
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import oracle
