@@ -47,6 +47,8 @@ def parse():
                    help="give every sample the width B (1..8) instead of the workload's mixed widths")
     p.add_argument("--event-every", type=int, default=4,
                    help="single-tensor workloads: record the per-kernel HIP events in every n-th timed step")
+    p.add_argument("--contexts-dtype", default="f32", choices=["f32", "f16"],
+                   help="element type of the `contexts` workload")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--profile-pass", action="store_true",
                    help="for rocprofv3 counter runs: a few launches of each kernel plus a plain device copy "
@@ -271,21 +273,23 @@ def contexts(args, torch, B, dev):
     (8-bit window positions).  One step is the four launches."""
     N, C, H, W = 256, 64, 112, 112
     k, s_, p = (3, 3), (2, 2), (1, 1)
+    tdt = torch.float16 if args.contexts_dtype == "f16" else torch.float32
+    eb = 2 if args.contexts_dtype == "f16" else 4
     gen = torch.Generator(device=dev)
     gen.manual_seed(77)
-    x = torch.randn((N, C, H, W), generator=gen, device=dev, dtype=torch.float32)
+    x = torch.randn((N, C, H, W), generator=gen, device=dev, dtype=torch.float32).to(tdt)
     OH, OW = B.pool2d_output_size(H, W, k, s_, p)
-    gy_pool = torch.randn((N, C, OH, OW), generator=gen, device=dev, dtype=torch.float32)
+    gy_pool = torch.randn((N, C, OH, OW), generator=gen, device=dev, dtype=torch.float32).to(tdt)
     y = torch.empty_like(x)
     mask = torch.empty(B.relu_mask_bytes(x.numel()), dtype=torch.uint8, device=dev)
-    pooled = torch.empty((N, C, OH, OW), dtype=torch.float32, device=dev)
+    pooled = torch.empty((N, C, OH, OW), dtype=tdt, device=dev)
     arg = torch.empty((N, C, OH, OW), dtype=torch.uint8, device=dev)
     g_act = torch.empty_like(x)
     g_in = torch.empty_like(x)
     stream = torch.cuda.current_stream()
     n_in, n_out = x.numel(), pooled.numel()
-    alg = {"relu_forward": n_in * 8 + mask.numel(), "maxpool2d_forward": n_in * 4 + n_out * 5,
-           "maxpool2d_backward": n_out * 5 + n_in * 4, "relu_backward": n_in * 8 + mask.numel()}
+    alg = {"relu_forward": n_in * 2 * eb + mask.numel(), "maxpool2d_forward": n_in * eb + n_out * (eb + 1),
+           "maxpool2d_backward": n_out * (eb + 1) + n_in * eb, "relu_backward": n_in * 2 * eb + mask.numel()}
 
     def step(events=None):
         def timed(name, fn):
@@ -329,11 +333,11 @@ def contexts(args, torch, B, dev):
                         "sample": f"the same four calls on the whole workload, {cpu_s:.2f} s "
                                   "(the ReLU loops of the oracle are single-threaded)"}
     print(json.dumps({
-        "metric": "exact layer contexts (ReLU mask, max-pool positions): GB/s of fp32 input per step; % of HBM peak",
-        "value": n_in * 4 / (ms_per_step * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "metric": "exact layer contexts (ReLU mask, max-pool positions): GB/s of input per step; % of HBM peak",
+        "value": n_in * eb / (ms_per_step * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "contexts_r50_stem_f32_256x64x112x112", "pool": "3x3 stride 2 padding 1",
+        "vs_baseline": None, "dtype": args.contexts_dtype, "data": "synthetic",
+        "config": {"workload": f"contexts_r50_stem_{args.contexts_dtype}_256x64x112x112", "pool": "3x3 stride 2 padding 1",
                    "step": "relu_forward + maxpool2d_forward + maxpool2d_backward + relu_backward"},
         "kernels": per_kernel,
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
