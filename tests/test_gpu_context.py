@@ -166,3 +166,33 @@ def test_maxpool_stem_size():
     x = np.maximum(rng.standard_normal((32, 64, 112, 112), dtype=np.float32), 0)   # post-ReLU: many ties at 0
     g = rng.standard_normal((32, 64, 56, 56), dtype=np.float32)
     _pool_round_trip(x, g, 112, 112, (3, 3), (2, 2), (1, 1), (1, 1))
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+def test_maxpool_sees_new_contents_of_the_same_buffers(dtype):
+    """The pooling kernels take one column per wavefront through the scalar data path; a second
+    call on the same buffers, refilled by another kernel on the same stream, must see the new
+    contents (rows longer than a wavefront covers, so that those columns are in use)."""
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(17)
+    planes, H, W = 3, 6, 520
+    k, s, p = (3, 3), (2, 2), (1, 1)
+    OH, OW = B.pool2d_output_size(H, W, k, s, p)
+    x = torch.empty((planes, H, W), dtype=NP[dtype], device=dev)
+    y = torch.empty((planes, OH, OW), dtype=NP[dtype], device=dev)
+    arg = torch.empty((planes, OH, OW), dtype=torch.uint8, device=dev)
+    gy = torch.empty((planes, OH, OW), dtype=NP[dtype], device=dev)
+    gx = torch.empty((planes, H, W), dtype=NP[dtype], device=dev)
+    for round_ in range(3):
+        x_np = rng.standard_normal((planes, H, W)).astype(dtype)
+        g_np = rng.standard_normal((planes, OH, OW)).astype(dtype)
+        staged_x, staged_g = torch.from_numpy(x_np).to(dev), torch.from_numpy(g_np).to(dev)
+        x.copy_(staged_x)                       # device-side writes, then the kernels, no synchronisation between
+        gy.copy_(staged_g)
+        B.maxpool2d_forward(x, k, s, p, (1, 1), y, arg)
+        B.maxpool2d_backward(arg, gy, H, W, k, s, p, (1, 1), gx)
+        torch.cuda.synchronize()
+        oy, oarg = oracle.maxpool2d_forward(x_np, k, s, p)
+        assert np.array_equal(arg.cpu().numpy(), oarg), round_
+        assert _bits_equal(y.cpu().numpy(), oy), round_
+        assert _bits_equal(gx.cpu().numpy(), oracle.maxpool2d_backward(oarg, g_np, H, W, k, s, p)), round_
