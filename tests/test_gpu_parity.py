@@ -70,7 +70,9 @@ def test_config1_tiny(noise_bits):
 @pytest.mark.parametrize("dtype", [np.float32, np.float16])
 @pytest.mark.parametrize("noise_bits", [24, 16])
 @pytest.mark.parametrize("N,D", [(5, 256 * 7), (3, 256 * 13 + 100), (2, 257), (4, 255), (1, 4 * 256 + 1),
-                                 (7, 256 * 33 + 252), (9, 256)])
+                                 (7, 256 * 33 + 252), (9, 256),
+                                 # whole groups around the eight groups a wavefront takes for binary16 output
+                                 (2, 256 * 8), (2, 256 * 9), (3, 256 * 15), (2, 256 * 16), (2, 256 * 17), (4, 256 * 3)])
 def test_shapes_spanning_tiles_and_ragged_tails(N, D, noise_bits, dtype):
     rng = np.random.default_rng(N * 1000 + D)
     x = (rng.standard_normal((N, D)) * np.exp(rng.uniform(-3, 3, (N, 1)))).astype(dtype)
@@ -195,7 +197,7 @@ def _round_trip_bf16(x, bits, seed, tag, noise_bits, out_dtypes=(torch.float32,)
 
 @pytest.mark.parametrize("dtype", [np.float32, np.float16])
 @pytest.mark.parametrize("noise_bits", [24, 16])
-@pytest.mark.parametrize("N,D", [(5, 256 * 7), (3, 256 * 13 + 100), (2, 257), (6, 256 * 40)])
+@pytest.mark.parametrize("N,D", [(5, 256 * 7), (3, 256 * 13 + 100), (2, 257), (6, 256 * 40), (2, 256 * 9), (3, 256 * 16)])
 def test_bf16_header_mode(N, D, noise_bits, dtype):
     rng = np.random.default_rng(N * 77 + D)
     x = (rng.standard_normal((N, D)) * np.exp(rng.uniform(-3, 3, (N, 1))) + rng.standard_normal((N, 1))).astype(dtype)
