@@ -61,6 +61,29 @@ def test_saved_context_equals_the_oracle(shape, mixed):
         assert c.nbytes() < x.numel() * 4 / 6
 
 
+@pytest.mark.parametrize("shape", [(4, 16, 16, 16), (3, 2304)])
+def test_saved_context_of_a_binary16_activation_equals_the_oracle(shape):
+    """Mixed-precision training (Sec. 6.1) saves binary16 activations: the context is computed from
+    the widened values and decompresses to binary16, both as the oracle has them."""
+    torch.manual_seed(1)
+    x = (torch.randn(shape, device=DEV) * 3).to(torch.float16).contiguous()
+    L.config.mixed, L.config.bits, L.config.seed = False, 4.0, 7
+    import itertools
+    L._tags = itertools.count(5)
+    c = L.compress(x)
+    torch.cuda.synchronize()
+    x_np = x.cpu().numpy().reshape(c.N, c.D)
+    bits = c.bits.cpu().numpy()
+    assert c.dtype == torch.float16 and np.all(bits == 4)
+    opacked, oheader, ooff = oracle.quantize_pack(x_np, bits, 7, 5, noise_bits=16)
+    assert np.array_equal(c.packed[:opacked.size].cpu().numpy(), opacked)
+    assert np.array_equal(c.header.cpu().numpy().view(np.uint32), oheader.reshape(-1).view(np.uint32))
+    want = oracle.unpack_dequantize(opacked, oheader, bits, ooff, c.N, c.D, out_dtype=np.float16)
+    got = L.decompress(c)
+    assert got.dtype == torch.float16 and tuple(got.shape) == tuple(shape)
+    assert np.array_equal(got.cpu().numpy().reshape(c.N, c.D).view(np.uint16), want.view(np.uint16))
+
+
 def _dequantized_like(layer_input_hook):
     return layer_input_hook
 
