@@ -6,9 +6,8 @@
 // elements per lane, so one 128-bit load per lane brings in a whole group.  A *tile* is
 // four consecutive groups of one sample (4 KiB of binary32 input, four loads in flight per
 // lane); tiles never cross a sample, so the width b_n is uniform over a tile and every
-// branch on it is divergence-free.  One wavefront handles one tile (or a short run of
-// consecutive tiles) and exits: on this part many short-lived wavefronts stream HBM
-// faster than a few long-lived ones.
+// branch on it is divergence-free.  One wavefront handles one tile and exits: on this part
+// many short-lived wavefronts stream HBM faster than a few long-lived ones.
 //
 // The path is bound by HBM only if the integer work of the noise generator stays hidden,
 // so the per-group bookkeeping is kept off the vector ALU as far as possible:
@@ -26,7 +25,6 @@
 // and a multiplication that are rounded separately.
 #include <hip/hip_runtime.h>
 
-#include <atomic>
 #include <cstdint>
 #include <type_traits>
 
@@ -217,9 +215,8 @@ __device__ __forceinline__ void load_tile(const T* xs, uint32_t g0, int groups, 
         const int64_t d0 = (static_cast<int64_t>(g0 + u) << 8) + lane * 4;
         if (VEC) {
             // A group past the end of the sample re-reads the tile's first group (valid memory;
-            // its results are never stored).  Keeping the load unconditional keeps the number
-            // of loads per tile fixed, which is what lets the wait for a tile's data be a
-            // counted wait that leaves the next tile's loads in flight.
+            // its results are never stored): the loads stay unconditional and all four are
+            // issued back to back.
             const int64_t d_safe = u < groups ? d0 : (static_cast<int64_t>(g0) << 8) + lane * 4;
             Io<T>::load4(xs + d_safe, v[u]);
             ok[u][0] = ok[u][1] = ok[u][2] = ok[u][3] = true;
@@ -538,21 +535,16 @@ __device__ __forceinline__ void encode_tile(const TileRegs& td, const uint32_t (
     wave_lds_handover();  // the slice is reused by the next tile of this wavefront
 }
 
-// Geometry of the streaming quantizer.  The launch holds at most as many wavefronts as the
-// chip keeps resident; wavefront w handles the linear tiles w, w + waves, w + 2*waves, ...
-// (linear tile = sample * tiles_per_sample + tile-in-sample), so at any moment the
-// resident wavefronts sweep one contiguous window of HBM.
+// Geometry of the quantizer's launch.
 struct StreamGeometry {
     int64_t D;
     uint32_t N;
     uint32_t ng;
     uint32_t tiles_per_sample;
-    uint32_t total_tiles;
-    uint32_t step_n, step_t;  // waves = step_n * tiles_per_sample + step_t
     uint32_t hdr_mode;        // header: 0 = (Z, R/B) binary32 per group, 1 = (Z, R) bfloat16 per group, 2 = one (Z, R) given
 };
 
-// Position of a wavefront in its sequence of tiles, with the scalar facts of the sample.
+// The tile of a wavefront, with the scalar facts of its sample.
 struct Cursor {
     uint32_t n, t;   // sample, tile inside the sample
     uint32_t b;      // width of the sample
@@ -568,17 +560,6 @@ __device__ __forceinline__ void fetch(const T* __restrict__ x, const StreamGeome
     load_tile<T, VEC>(x + static_cast<int64_t>(c.n) * geo.D, c.t * kTileGroups, groups, lane, geo.D, r.v, r.ok);
     c.b = load_width(bits, c.n);
     c.off = load_readonly(offsets + c.n);
-}
-
-// Next tile of the wavefront; false (and the cursor unchanged) when there is none.
-__device__ __forceinline__ bool advance(const StreamGeometry& geo, Cursor& c)
-{
-    uint32_t n2 = c.n + geo.step_n, t2 = c.t + geo.step_t;
-    if (t2 >= geo.tiles_per_sample) { t2 -= geo.tiles_per_sample; ++n2; }
-    if (n2 >= geo.N) return false;
-    c.n = n2;
-    c.t = t2;
-    return true;
 }
 
 template <int NOISE_BITS, bool VEC>
@@ -621,48 +602,12 @@ __device__ __forceinline__ void quantize_one(const TileRegs& r, const Cursor& c,
     }
 }
 
-// The quantizer is a software pipeline: while a wavefront works on one tile (noise,
-// reduction, rounding, packing: all vector-ALU work) the HBM loads of its next tile are
-// already in flight, so every resident wavefront keeps 4 KiB of reads outstanding at all
-// times and the ALU work hides under the memory time instead of adding to it.  Two
-// register sets alternate (no copies); a wavefront without a next tile re-reads its
-// current one, so that every step issues the same number of loads.
-template <typename T, int NOISE_BITS, bool VEC>
-__global__ __launch_bounds__(kBlock) void quantize_pack_kernel(
-    const T* __restrict__ x, StreamGeometry geo, const uint8_t* __restrict__ bits,
-    const uint64_t* __restrict__ offsets, uint32_t k0, uint32_t k1, uint32_t tag0, uint32_t tag1,
-    uint8_t* __restrict__ packed, uint64_t capacity, void* __restrict__ header)
-{
-    __shared__ uint32_t stage_all[kWavesPerBlock][256];  // 1 KiB per wavefront, private to it
-    const int lane = threadIdx.x & (kWave - 1);
-    const uint32_t wave_in_block = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6)));
-    const uint32_t w = blockIdx.x * kWavesPerBlock + wave_in_block;
-    if (w >= geo.total_tiles) return;
-    uint32_t* stage = stage_all[wave_in_block];
-
-    Cursor ca, cb;
-    ca.n = w / geo.tiles_per_sample;
-    ca.t = w - ca.n * geo.tiles_per_sample;
-    TileRegs ra, rb;
-    fetch<T, VEC>(x, geo, bits, offsets, lane, ca, ra);
-    for (;;) {
-        cb = ca;
-        const bool more_b = advance(geo, cb);
-        fetch<T, VEC>(x, geo, bits, offsets, lane, cb, rb);
-        quantize_one<NOISE_BITS, VEC>(ra, ca, geo, lane, k0, k1, tag0, tag1, packed, capacity, header, stage);
-        if (!more_b) break;
-        ca = cb;
-        const bool more_a = advance(geo, ca);
-        fetch<T, VEC>(x, geo, bits, offsets, lane, ca, ra);
-        quantize_one<NOISE_BITS, VEC>(rb, cb, geo, lane, k0, k1, tag0, tag1, packed, capacity, header, stage);
-        if (!more_a) break;
-    }
-}
-
-// One tile per wavefront (grid.x = tiles of a sample, grid.y * grid.z = samples): the
-// alternative launch shape of the same work.  Short-lived wavefronts lose the least HBM
-// bandwidth to the small writes of codes and headers, so this shape wins when the per-tile
-// ALU work is light enough to hide behind other wavefronts' loads (16-bit noise).
+// One tile per wavefront (grid.x = tiles of a sample, grid.y * grid.z = samples).  Short-lived
+// wavefronts lose the least HBM bandwidth to the small writes of codes and headers, and the
+// other resident wavefronts' loads hide a tile's ALU work.  (A persistent software pipeline
+// -- as many wavefronts as the chip holds, each striding over the tiles with the next tile's
+// loads in flight while the current one is encoded -- measured slower in every mode: 80
+// against 70 us with 16-bit noise, 96 against 83 us with 24-bit noise on the stage-1 tensor.)
 template <typename T, int NOISE_BITS, bool VEC>
 __global__ __launch_bounds__(kBlock) void quantize_pack_tile_kernel(
     const T* __restrict__ x, StreamGeometry geo, uint32_t grid_y, const uint8_t* __restrict__ bits,
@@ -971,8 +916,6 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_multi_kernel(MultiTable 
     geo.N = t.N;
     geo.ng = static_cast<uint32_t>(it.D >> 8);
     geo.tiles_per_sample = (geo.ng + kTileGroups - 1) / kTileGroups;
-    geo.total_tiles = 0;
-    geo.step_n = geo.step_t = 0;
     geo.hdr_mode = t.hdr_mode;
     const uint64_t tensor_tag = tag + l;  // every tensor of the launch draws its own noise
     TileRegs r;
@@ -1520,24 +1463,6 @@ int launch_group_stats(const void* x, int dtype, int64_t N, int64_t D, float* gm
     return check_launch("actq_group_stats");
 }
 
-// Resident wavefronts the chip holds for a kernel: occupancy (blocks per CU) x CUs x 4.
-template <typename K>
-static int resident_blocks(K kernel, int* out)
-{
-    int device = 0, cus = 0, per_cu = 0;
-    if (hipGetDevice(&device) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess ||
-        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kBlock, 0) != hipSuccess || cus <= 0 || per_cu <= 0)
-        return fail(ACTQ_EHIP, "actq_quantize_pack: cannot query the device: %s", hipGetErrorString(hipGetLastError()));
-    *out = cus * per_cu;
-    return ACTQ_OK;
-}
-
-// Launch shape per noise mode, from measurement on MI355X: the 24-bit comparison path is
-// bound by the vector ALU and gains from the persistent pipeline; the lighter 16-bit path is
-// bound by HBM and is fastest as one tile per wavefront.
-constexpr bool persistent_shape(int noise_bits) { return noise_bits == 24; }
-
 template <typename T, int NOISE_BITS, bool VEC>
 static int launch_quantize_variant(const T* x, StreamGeometry geo, hipStream_t s, const uint8_t* bits,
                                    const uint64_t* offsets, uint64_t seed, uint64_t tag, uint8_t* packed,
@@ -1545,29 +1470,11 @@ static int launch_quantize_variant(const T* x, StreamGeometry geo, hipStream_t s
 {
     const uint32_t k0 = static_cast<uint32_t>(seed), k1 = static_cast<uint32_t>(seed >> 32);
     const uint32_t t0 = static_cast<uint32_t>(tag), t1 = static_cast<uint32_t>(tag >> 32);
-    if (!persistent_shape(NOISE_BITS)) {
-        const uint32_t gx = (geo.tiles_per_sample + kWavesPerBlock - 1) / kWavesPerBlock;
-        const uint32_t gy = geo.N < 65535u ? geo.N : 65535u;
-        const uint32_t gz = (geo.N + gy - 1) / gy;
-        if (gz > 65535u) return fail(ACTQ_EINVAL, "actq_quantize_pack: too many samples for one launch");
-        quantize_pack_tile_kernel<T, NOISE_BITS, VEC><<<dim3(gx, gy, gz), kBlock, 0, s>>>(x, geo, gy, bits, offsets, k0, k1, t0, t1, packed, capacity, header);
-        return ACTQ_OK;
-    }
-    // memo per device of a pure function of (device, kernel); racing threads store the same value
-    static std::atomic<int> blocks_cache[16];
-    int device = 0;
-    if (hipGetDevice(&device) != hipSuccess) return fail(ACTQ_EHIP, "actq_quantize_pack: no current device");
-    int resident = (device >= 0 && device < 16) ? blocks_cache[device].load(std::memory_order_relaxed) : 0;
-    if (resident <= 0) {
-        if (int rc = resident_blocks(quantize_pack_kernel<T, NOISE_BITS, VEC>, &resident)) return rc;
-        if (device >= 0 && device < 16) blocks_cache[device].store(resident, std::memory_order_relaxed);
-    }
-    const uint32_t want = (geo.total_tiles + kWavesPerBlock - 1) / kWavesPerBlock;
-    const uint32_t blocks = want < static_cast<uint32_t>(resident) ? want : static_cast<uint32_t>(resident);
-    const uint32_t waves = blocks * kWavesPerBlock;
-    geo.step_n = waves / geo.tiles_per_sample;
-    geo.step_t = waves % geo.tiles_per_sample;
-    quantize_pack_kernel<T, NOISE_BITS, VEC><<<dim3(blocks), kBlock, 0, s>>>(x, geo, bits, offsets, k0, k1, t0, t1, packed, capacity, header);
+    const uint32_t gx = (geo.tiles_per_sample + kWavesPerBlock - 1) / kWavesPerBlock;
+    const uint32_t gy = geo.N < 65535u ? geo.N : 65535u;
+    const uint32_t gz = (geo.N + gy - 1) / gy;
+    if (gz > 65535u) return fail(ACTQ_EINVAL, "actq_quantize_pack: too many samples for one launch");
+    quantize_pack_tile_kernel<T, NOISE_BITS, VEC><<<dim3(gx, gy, gz), kBlock, 0, s>>>(x, geo, gy, bits, offsets, k0, k1, t0, t1, packed, capacity, header);
     return ACTQ_OK;
 }
 
@@ -1598,8 +1505,6 @@ int launch_quantize_pack(const void* x, int dtype, int64_t N, int64_t D, const u
     geo.N = static_cast<uint32_t>(N);
     geo.ng = static_cast<uint32_t>(ng);
     geo.tiles_per_sample = static_cast<uint32_t>(tps);
-    geo.total_tiles = static_cast<uint32_t>(N * tps);
-    geo.step_n = geo.step_t = 0;
     geo.hdr_mode = static_cast<uint32_t>(hdr);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool vec = vector_ok(D);
