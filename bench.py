@@ -2,14 +2,17 @@
 """Benchmark of the activation-compression hot path on one MI355X.
 
 One *step* is one pass of the whole path over one batch that is already resident in HBM:
-  group_stats -> sample_sensitivity -> allocate_bits (greedy) -> quantize_pack -> unpack_dequantize.
+  group_stats -> allocate_bits (greedy) -> quantize_pack -> unpack_dequantize.
 By default the allocator runs on the device (actq_allocate_bits_device) and the step never
 touches the host; --allocator host runs the host greedy between the kernels instead (widths
 and offsets then travel host-to-device in every step).
-The default workload is the ResNet-50 stage-1 post-ReLU activation, fp32 [128,256,56,56],
-G = 256, per-sample widths in {1,2,4,8} averaging 2.0 bits.  `value` is input-activation
-bytes per second through the whole step; the per-kernel figures and the HBM roofline of
-the slowest kernel are reported beside it, and the CPU oracle is timed as a baseline.
+The default workload is the full ResNet-50 activation sweep at batch 256: the 53 conv-input
+tensors (fp32, 10.9 GB), G = 256, one greedy allocation over all 53 x 256 (layer, sample) items
+to a 2.0-bit average over widths {1,2,4,8}, multi-tensor launches (one per size class and
+kernel).  `value` is input-activation bytes per second through the whole step; the per-kernel
+and per-size-class figures and the HBM roofline of the slowest kernel are reported beside it,
+the CPU oracle is timed as a baseline, and the single ResNet-50 stage-1 tensor
+(--workload r50_stage1) is appended under `r50_stage1`.
 
 Prints one JSON line.
 """
@@ -33,9 +36,9 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 def parse():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
-    p.add_argument("--steps", type=int, default=100)
-    p.add_argument("--warmup", type=int, default=10)
-    p.add_argument("--workload", default="r50_stage1", choices=["r50_stage1", "tiny", "r50_stem_f16", "fpn", "r50_sweep", "contexts", "block"])
+    p.add_argument("--steps", type=int, default=40)
+    p.add_argument("--warmup", type=int, default=5)
+    p.add_argument("--workload", default="r50_sweep", choices=["r50_stage1", "tiny", "r50_stem_f16", "fpn", "r50_sweep", "contexts", "block"])
     p.add_argument("--noise-bits", type=int, default=16, choices=[24, 16])
     p.add_argument("--header", default="f32", choices=["f32", "bf16"],
                    help="group header format: (Z, R/B) binary32, 8 B/group, or (Z, R) bfloat16, 4 B/group")
@@ -50,6 +53,11 @@ def parse():
     p.add_argument("--contexts-dtype", default="f32", choices=["f32", "f16"],
                    help="element type of the `contexts` workload")
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--cpu-seconds", type=float, default=12.0,
+                   help="r50_sweep: oracle time after which the CPU baseline stops taking further layers")
+    p.add_argument("--sweep-batch", type=int, default=256, help="r50_sweep: samples per tensor")
+    p.add_argument("--no-secondary", action="store_true",
+                   help="r50_sweep: do not append the ResNet-50 stage-1 tensor's figures under `r50_stage1`")
     p.add_argument("--profile-pass", action="store_true",
                    help="for rocprofv3 counter runs: a few launches of each kernel plus a plain device copy "
                         "of the input tensor (known size, calibrates FETCH_SIZE / WRITE_SIZE), then exit")
@@ -80,14 +88,64 @@ def measured_traffic(workload: str, noise_bits: int, kernel: str):
         return None
 
 
-def sweep(args, torch, B, synth, dev):
-    """The 53 conv-input tensors of ResNet-50 at batch 256 (fp32, 10.9 GB): one step allocates
-    widths for all 53 x 256 (layer, sample) items under a 2.0-bit average budget, then runs
-    group_stats, quantize_pack and unpack_dequantize on every layer -- by default as multi-tensor
-    launches (one call per size class and kernel), with --launches single as one launch
-    per layer and kernel."""
-    import ctypes
-    N, G = 256, 256
+SWEEP_NAME = "r50_sweep_f32_53x[256,C,H,W]"
+
+
+def sweep_traffic(noise_bits: int):
+    """HBM bytes per step of every sweep kernel from the committed rocprofv3 counter summary
+    (profiles/hbm_traffic.json; a property of that profiling run, not of this one), or None."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
+            return json.load(f)[SWEEP_NAME][f"noise{noise_bits}"]
+    except (OSError, KeyError, ValueError):
+        return None
+
+
+_SWEEP_SINGLE_THREAD_LEG = r'''
+import json, sys, time
+import numpy as np
+sys.path.insert(0, sys.argv[1])
+import oracle
+from paper_2104_14129_amd import synth
+rows, noise_bits = int(sys.argv[2]), int(sys.argv[3])
+Dl = [c * h * w for c, h, w in synth.resnet50_conv_input_shapes()]
+rng = np.random.default_rng(1)
+spent, nbytes = 0.0, 0
+for l, D in enumerate(Dl):
+    x = np.maximum(rng.standard_normal((rows, D), dtype=np.float32), 0.0)
+    bits = np.full(rows, 2, dtype=np.uint8)
+    t = time.perf_counter()
+    oracle.group_stats(x, 256)
+    pk, hd, off = oracle.quantize_pack(x, bits, 15, l, 256, noise_bits)
+    oracle.unpack_dequantize(pk, hd, bits, off, rows, D, 256, out_dtype=x.dtype)
+    spent += time.perf_counter() - t
+    nbytes += x.nbytes
+print(json.dumps({"value": nbytes / spent / 1e9, "unit": "GB/s", "cores": oracle.threads(),
+                  "sample": f"{rows} samples of each of the 53 layers at 2 bits, {nbytes} input bytes, {spent:.2f} s"}))
+'''
+
+
+def sweep_single_thread(rows, noise_bits):
+    """One OpenMP thread of the oracle on a few samples of every layer, in a child process that is
+    started before this process touches the GPU (the thread count is fixed when the library loads)."""
+    import subprocess
+    try:
+        out = subprocess.run([sys.executable, "-c", _SWEEP_SINGLE_THREAD_LEG, ROOT, str(rows), str(noise_bits)],
+                             env=dict(os.environ, OMP_NUM_THREADS="1"), capture_output=True, text=True,
+                             timeout=300, check=True).stdout
+        return json.loads(out.strip().splitlines()[-1])
+    except Exception as exc:  # the baseline is a report, never a reason for the bench to fail
+        return {"error": f"{type(exc).__name__}: {exc}"}
+
+
+def sweep(args, torch, B, synth, dev, single_thread=None):
+    """The 53 conv-input tensors of ResNet-50 at batch 256 (fp32, 10.9 GB).  One step: group_stats on
+    every layer, one greedy allocation over all 53 x 256 (layer, sample) items under a 2.0-bit
+    average budget, quantize_pack and unpack_dequantize on every layer -- by default as multi-tensor
+    launches (one call per size class and kernel), with --launches single as one launch per layer
+    and kernel."""
+    from paper_2104_14129_amd.plan import TensorSetPlan
+    N, G = args.sweep_batch, 256
     shapes = synth.resnet50_conv_input_shapes()
     Dl = [c * h * w for c, h, w in shapes]
     L = len(Dl)
@@ -102,26 +160,38 @@ def sweep(args, torch, B, synth, dev):
     D_host = np.repeat(np.array(Dl, dtype=np.int64), N)
     budget = 2 * int(D_host.sum())
     Dmax = max(Dl)
-    # The offsets run over all layers (one shared bit stream of budget / 8 bytes) whenever the device
-    # allocator writes them or the multi-tensor calls read them; one launch per layer with the host
-    # allocator reuses a one-layer buffer with room for 8 bits everywhere.
-    shared_stream = multi or device_alloc
-    packed_buf = torch.empty(budget // 8 + 4096 if shared_stream else N * Dmax, dtype=torch.uint8, device=dev)
-    packed_capacity = packed_buf.numel()
+    stream = torch.cuda.current_stream()
     w_dev = torch.from_numpy(w_host).to(dev)
     D_dev = torch.from_numpy(D_host).to(dev)
-    result_dev = torch.zeros(2, dtype=torch.int64, device=dev)
     bits_pin = torch.empty(N * L, dtype=torch.uint8, pin_memory=True)
     offs_pin = torch.empty(N * L, dtype=torch.int64, pin_memory=True)
-    bits_dev = torch.empty(N * L, dtype=torch.uint8, device=dev)
-    offs_dev = torch.empty(N * L, dtype=torch.int64, device=dev)
-    stream = torch.cuda.current_stream()
     state = {}
-    # The per-launch host cost must stay far below the kernel times, so the sweep calls the C ABI with
-    # pointers and sizes worked out once (the checks of the Python binding run in all tests).
+    names = ("group_stats", "quantize_pack", "unpack_dequantize")
     lib = B.lib()
     sp = stream.cuda_stream
-    names = ("group_stats", "quantize_pack", "unpack_dequantize")
+    every = max(1, args.event_every)
+
+    if multi:
+        # one shared bit stream of budget / 8 bytes; every layer keeps its own statistics, header and
+        # output arrays, as a training step would
+        plan = TensorSetPlan(xs, N, budget // 8 + 4096, noise_bits=args.noise_bits, seed=15, G=G)
+        bits_dev, offs_dev, result_dev = plan.bits, plan.offsets, plan.result
+        classes = plan.classes
+        launches_per_step = 3 * len(classes) + 1
+        # boundary events: the end of one launch is the start of the next
+        n_ev = 3 * (len(classes) + 1)
+    else:
+        shared_stream = device_alloc
+        packed_buf = torch.empty(budget // 8 + 4096 if shared_stream else N * Dmax, dtype=torch.uint8, device=dev)
+        packed_capacity = packed_buf.numel()
+        bits_dev = torch.empty(N * L, dtype=torch.uint8, device=dev)
+        offs_dev = torch.empty(N * L, dtype=torch.int64, device=dev)
+        result_dev = torch.zeros(2, dtype=torch.int64, device=dev)
+        classes = [[l] for l in range(L)]
+        launches_per_step = 3 * L + 1
+        n_ev = 6 * L
+    steps_with_events = [i for i in range(args.steps) if i % every == 0]
+    pool = {i: [torch.cuda.Event(enable_timing=True) for _ in range(n_ev)] for i in steps_with_events}
 
     def allocate():
         if device_alloc:
@@ -131,7 +201,7 @@ def sweep(args, torch, B, synth, dev):
         totals, base = [], 0
         for l, D in enumerate(Dl):
             offsets, total = B.packed_bytes(N, D, bits[l * N:(l + 1) * N], G)
-            offs_pin.numpy()[l * N:(l + 1) * N] = offsets.view(np.int64) + (base if shared_stream else 0)
+            offs_pin.numpy()[l * N:(l + 1) * N] = offsets.view(np.int64) + (base if (multi or device_alloc) else 0)
             base += total
             totals.append(total)
         bits_pin.numpy()[:] = bits
@@ -140,55 +210,28 @@ def sweep(args, torch, B, synth, dev):
         state["bits"], state["totals"] = bits, totals
 
     if multi:
-        # every layer keeps its own statistics, header and output arrays, as a training step would
-        keep = [{"x": xs[l], "out": torch.empty((N, D), dtype=torch.float32, device=dev),
-                 "gmin": torch.empty(N * (D // G), dtype=torch.float32, device=dev),
-                 "grange": torch.empty(N * (D // G), dtype=torch.float32, device=dev),
-                 "header": torch.empty(N * (D // G) * 2, dtype=torch.float32, device=dev),
-                 "bits": bits_dev[l * N:(l + 1) * N], "offsets": offs_dev[l * N:(l + 1) * N], "D": D}
-                for l, D in enumerate(Dl)]
-        # one call per size class: the launch is sized for its largest tensor, so tensors of one call
-        # should be of similar size (ResNet-50 has seven sizes; a lone size joins the next larger class)
-        classes = {}
-        for l, D in enumerate(Dl):
-            classes.setdefault(D, []).append(l)
-        sizes = sorted(classes, reverse=True)
-        groups = []
-        for D in sizes:
-            if groups and len(classes[D]) == 1 and len(groups[-1]) < B.MAX_TENSORS_PER_CALL:
-                groups[-1] += classes[D]
-            else:
-                groups.append(list(classes[D]))
-        tables = [B.tensor_table([keep[l] for l in g]) for g in groups]
-        layer_of = [l for g in groups for l in g]
-        tptr = [ctypes.addressof(t) for t in tables]
-        tlen = [len(t) for t in tables]
-        # tensor i of a call draws its noise with tag0 + i: keep the layer's own tag where the class is contiguous
-        tag0 = [1000 * k for k in range(len(groups))]
-        pk = packed_buf.data_ptr()
-        pool = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(3)]
-                for _ in range(args.steps)]
-        launches_per_step = 3 * len(groups)
+        nc = len(classes)
 
         def step(ev=None):
+            # the statistics come first: in training the sensitivities are computed from them (Eq. (8))
+            if ev is None:
+                plan.group_stats(stream)
+                allocate()
+                plan.quantize_pack(stream)
+                plan.unpack_dequantize(stream)
+                return
+            ev[0].record(stream)
+            plan.group_stats(stream, lambda k: ev[1 + k].record(stream))
             allocate()
-            calls = (
-                lambda i: lib.actq_group_stats_multi(tptr[i], tlen[i], B.ACTQ_F32, N, G, sp),
-                lambda i: lib.actq_quantize_pack_multi(tptr[i], tlen[i], B.ACTQ_F32, N, G, 15, tag0[i], args.noise_bits,
-                                                       pk, packed_capacity, B.ACTQ_HDR_F32, sp),
-                lambda i: lib.actq_unpack_dequantize_multi(tptr[i], tlen[i], pk, packed_capacity, B.ACTQ_HDR_F32, N, G,
-                                                           B.ACTQ_F32, sp),
-            )
-            rc = 0
-            for k, call in enumerate(calls):
-                if ev is not None:
-                    ev[k][0].record(stream)
-                for i in range(len(groups)):
-                    rc |= call(i)
-                if ev is not None:
-                    ev[k][1].record(stream)
-            if rc:
-                raise RuntimeError(B.last_error())
+            ev[nc + 1].record(stream)
+            plan.quantize_pack(stream, lambda k: ev[nc + 2 + k].record(stream))
+            ev[2 * nc + 2].record(stream)
+            plan.unpack_dequantize(stream, lambda k: ev[2 * nc + 3 + k].record(stream))
+
+        def durations(ev):
+            """ms of (kernel j, class k) from the boundary events of one step."""
+            starts = (0, nc + 1, 2 * nc + 2)
+            return [[ev[starts[j] + k].elapsed_time(ev[starts[j] + k + 1]) for k in range(nc)] for j in range(3)]
     else:
         ngmax = Dmax // G
         gmin = torch.empty(N * ngmax, dtype=torch.float32, device=dev)
@@ -197,74 +240,134 @@ def sweep(args, torch, B, synth, dev):
         out = torch.empty(N * Dmax, dtype=torch.float32, device=dev)
         layer_args = [(xs[l].data_ptr(), D, bits_dev.data_ptr() + l * N, offs_dev.data_ptr() + 8 * l * N)
                       for l, D in enumerate(Dl)]
-        pool = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(3 * L)]
-                for _ in range(args.steps)]
-        launches_per_step = 3 * L
 
         def step(ev=None):
             allocate()
             gm, gr, hd, pk, o = gmin.data_ptr(), grange.data_ptr(), header.data_ptr(), packed_buf.data_ptr(), out.data_ptr()
             for l, (xp, D, bp, op) in enumerate(layer_args):
                 if ev is not None:
-                    ev[3 * l][0].record(stream)
+                    ev[6 * l].record(stream)
                 rc = lib.actq_group_stats(xp, B.ACTQ_F32, N, D, G, gm, gr, sp)
                 if ev is not None:
-                    ev[3 * l][1].record(stream)
-                    ev[3 * l + 1][0].record(stream)
+                    ev[6 * l + 1].record(stream)
+                    ev[6 * l + 2].record(stream)
                 rc |= lib.actq_quantize_pack(xp, B.ACTQ_F32, N, D, G, bp, op, 15, l, args.noise_bits, pk, packed_capacity, hd, B.ACTQ_HDR_F32, sp)
                 if ev is not None:
-                    ev[3 * l + 1][1].record(stream)
-                    ev[3 * l + 2][0].record(stream)
+                    ev[6 * l + 3].record(stream)
+                    ev[6 * l + 4].record(stream)
                 rc |= lib.actq_unpack_dequantize(pk, packed_capacity, hd, B.ACTQ_HDR_F32, bp, op, N, D, G, o, B.ACTQ_F32, sp)
                 if ev is not None:
-                    ev[3 * l + 2][1].record(stream)
+                    ev[6 * l + 5].record(stream)
                 if rc:
                     raise RuntimeError(B.last_error())
+
+        def durations(ev):
+            return [[ev[6 * l + 2 * j].elapsed_time(ev[6 * l + 2 * j + 1]) for l in range(L)] for j in range(3)]
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.profile_pass:
+        # for rocprofv3 counter runs: two steps and, beside them, plain device copies of the largest
+        # tensor (known size: calibrates FETCH_SIZE / WRITE_SIZE)
+        big = max(range(L), key=lambda l: Dl[l])
+        copy_dst = torch.empty_like(xs[big])
+        for _ in range(2):
+            copy_dst.copy_(xs[big])
+            step()
+        torch.cuda.synchronize()
+        total, status = (int(v) for v in result_dev.cpu()) if device_alloc else (sum(state["totals"]), 0)
+        print(json.dumps({"profile_pass": True, "workload": SWEEP_NAME, "copy_bytes_each_way": 4 * N * Dl[big],
+                          "input_bytes": 4 * N * sum(Dl), "packed_bytes": total,
+                          "header_bytes": sum(N * (D // G) * 8 for D in Dl), "allocator_status": status}))
+        return None
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(pool[i])
+        step(pool.get(i))
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
-    kernel_ms = {k: 0.0 for k in names}
-    for ev in pool:
-        for j, (a, b) in enumerate(ev):
-            kernel_ms[names[j % 3]] += a.elapsed_time(b) / args.steps
 
     if device_alloc:
         total, status = (int(v) for v in result_dev.cpu())
         if status != 0:
             raise RuntimeError(f"device allocator reported status {status}")
-        state["bits"], state["totals"] = bits_dev.cpu().numpy(), [total]
+        state["bits"] = bits_dev.cpu().numpy()
+    bits_all = state["bits"]
+    if N * L <= 20000:
+        assert np.array_equal(bits_all, B.allocate_bits(w_host, D_host, budget)), "device and host allocators disagree"
+
+    # per (kernel, class): mean over the instrumented steps
+    per = np.mean([durations(pool[i]) for i in steps_with_events], axis=0)        # [3][classes] ms
     in_bytes = 4 * N * sum(Dl)
-    hdr = sum(N * (D // G) * 8 for D in Dl)
-    code = sum(state["totals"])
-    alg = {"group_stats": in_bytes + hdr, "quantize_pack": in_bytes + code + hdr, "unpack_dequantize": in_bytes + code + hdr}
+
+    def class_bytes(members, j):
+        tensor = sum(4 * N * Dl[l] for l in members)
+        hdr = sum(N * (Dl[l] // G) * 8 for l in members)
+        code = sum(int((bits_all[l * N:(l + 1) * N].astype(np.int64) * (Dl[l] // 8)).sum()) for l in members)
+        return tensor + hdr + (0 if j == 0 else code)
+
+    alg = {names[j]: sum(class_bytes(m, j) for m in classes) for j in range(3)}
+    kernel_ms = {names[j]: float(per[j].sum()) for j in range(3)}
     per_kernel = {k: {"ms_per_step_all_layers": kernel_ms[k], "input_GBps": in_bytes / kernel_ms[k] / 1e6,
                       "algorithmic_GBps": alg[k] / kernel_ms[k] / 1e6,
-                      "frac_of_hbm_peak": alg[k] / kernel_ms[k] / 1e6 / HBM_PEAK_GBS} for k in kernel_ms}
+                      "frac_of_hbm_peak": alg[k] / kernel_ms[k] / 1e6 / HBM_PEAK_GBS} for k in names}
+    class_table = None
+    if multi:
+        class_table = [{"D": Dl[m[0]], "tensors": len(m), "input_MB": sum(4 * N * Dl[l] for l in m) / 1e6,
+                        **{names[j]: {"us": float(per[j][k]) * 1e3,
+                                      "frac_of_hbm_peak": class_bytes(m, j) / float(per[j][k]) / 1e6 / HBM_PEAK_GBS}
+                           for j in range(3)}} for k, m in enumerate(classes)]
     dominant = max(kernel_ms, key=kernel_ms.get)
     achieved = alg[dominant] / kernel_ms[dominant] / 1e6
-    mean_bits = float((state["bits"].astype(np.float64) * D_host).sum() / D_host.sum())
+    mean_bits = float((bits_all.astype(np.float64) * D_host).sum() / D_host.sum())
+    traffic_table = sweep_traffic(args.noise_bits) if (multi and N == 256) else None
+    traffic = traffic_table[dominant]["hbm_bytes_per_step"] if traffic_table and dominant in traffic_table else None
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        # The oracle (all OpenMP threads) on whole layers of the same inputs and widths, layer by layer so
+        # that host memory stays bounded, until about `--cpu-seconds` of oracle time are spent.
+        import oracle
+        spent, done_bytes, done_layers = 0.0, 0, 0
+        order = sorted(range(L), key=lambda l: Dl[l])          # small layers first: the sample spans every size
+        for l in order:
+            if spent > args.cpu_seconds:
+                break
+            x_np = xs[l].cpu().numpy()
+            b_np = np.ascontiguousarray(bits_all[l * N:(l + 1) * N])
+            t = time.perf_counter()
+            oracle.group_stats(x_np, G)
+            opk, ohd, ooff = oracle.quantize_pack(x_np, b_np, 15, l, G, args.noise_bits)
+            oracle.unpack_dequantize(opk, ohd, b_np, ooff, N, Dl[l], G, out_dtype=x_np.dtype)
+            spent += time.perf_counter() - t
+            done_bytes += x_np.nbytes
+            done_layers += 1
+            del x_np, opk, ohd
+        cpu_baseline = {"value": done_bytes / spent / 1e9, "unit": "GB/s", "cores": oracle.threads(), "kind": "oracle",
+                        "sample": f"group_stats + quantize_pack + unpack_dequantize on {done_layers} of the {L} layers "
+                                  f"(whole layers, smallest first, the step's own inputs and widths), "
+                                  f"{done_bytes} input bytes, {spent:.2f} s",
+                        "single_thread": single_thread}
+
     result = {
         "metric": "quantize+pack and unpack+dequant GB/s (fp32 input); % of HBM peak",
         "value": in_bytes / (ms_per_step * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "r50_sweep_f32_53x[256,C,H,W]", "G": G, "mean_bits": mean_bits,
+        "config": {"workload": SWEEP_NAME.replace("256", str(N)) if N != 256 else SWEEP_NAME, "G": G, "mean_bits": mean_bits,
                    "noise_bits": args.noise_bits, "launches": args.launches, "launches_per_step": launches_per_step,
-                   "allocator": args.allocator,
-                   "step": f"allocate_bits({args.allocator}, M=13568) + group_stats + quantize_pack + unpack_dequantize on every layer"},
+                   "allocator": args.allocator, "steps_with_events": len(steps_with_events),
+                   "step": f"group_stats + allocate_bits({args.allocator}, M={N * L}) + quantize_pack + unpack_dequantize on every layer"},
         "kernels": per_kernel,
+        "size_classes": class_table,
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "algorithmic_bytes_per_step": alg[dominant], "sum_launch_ms_per_step": kernel_ms[dominant]},
-        "cpu_baseline": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "traffic_source": "profiles/hbm_traffic.json (rocprofv3 FETCH_SIZE + WRITE_SIZE of a separate run of this workload)" if traffic else None,
+                     "algorithmic_bytes_per_step": alg[dominant], "sum_launch_ms_per_step": kernel_ms[dominant],
+                     "launches_per_step": len(classes)},
+        "cpu_baseline": cpu_baseline,
     }
-    print(json.dumps(result))
+    return result
 
 
 def contexts(args, torch, B, dev):
@@ -461,18 +564,20 @@ def main():
 
     codec = args.workload in ("r50_stage1", "tiny", "r50_stem_f16", "fpn")
     single_thread = None
+    wl = x_np = None
+    # the one-thread legs of the CPU baseline are child processes: started here, before this
+    # process touches the GPU
     if codec:
         wl = {"r50_stage1": synth.r50_stage1, "tiny": synth.tiny, "r50_stem_f16": synth.r50_stem_f16,
               "fpn": synth.fpn}[args.workload]()
-        N, D, ng, G = wl.N, wl.D, wl.ng, wl.G
-        x_np = synth.make_input(wl).reshape(N, D)
+        x_np = synth.make_input(wl).reshape(wl.N, wl.D)
         if args.uniform_bits:
-            wl.bits = np.full(N, args.uniform_bits, dtype=np.uint8)
+            wl.bits = np.full(wl.N, args.uniform_bits, dtype=np.uint8)
         if not args.no_cpu_baseline and not args.profile_pass:
-            # the one-thread leg of the CPU baseline is a child process: started here, before this
-            # process touches the GPU
             single_thread = oracle_single_thread(x_np, wl.bits, wl.philox_seed, wl.tag, args.noise_bits,
                                                  args.header == "bf16")
+    elif args.workload == "r50_sweep" and not args.no_cpu_baseline and not args.profile_pass:
+        single_thread = sweep_single_thread(4, args.noise_bits)
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -480,12 +585,30 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     if args.workload == "r50_sweep":
-        return sweep(args, torch, B, synth, dev)
+        result = sweep(args, torch, B, synth, dev, single_thread)
+        if result is not None and not args.no_secondary and not args.profile_pass:
+            # the single ResNet-50 stage-1 tensor (the second configuration), as a secondary figure
+            torch.cuda.empty_cache()
+            sub = argparse.Namespace(**vars(args))
+            sub.workload, sub.no_cpu_baseline, sub.uniform_bits, sub.header, sub.steps, sub.warmup = "r50_stage1", True, 0, "f32", 40, 5
+            wl2 = synth.r50_stage1()
+            r2 = codec_run(sub, torch, B, synth, dev, wl2, synth.make_input(wl2).reshape(wl2.N, wl2.D), None)
+            result["r50_stage1"] = {k: r2[k] for k in ("value", "unit", "ms_per_step", "config", "kernels", "roofline")}
+        if result is not None:
+            print(json.dumps(result))
+        return
     if args.workload == "contexts":
         return contexts(args, torch, B, dev)
     if args.workload == "block":
         return block(args, torch, dev)
+    result = codec_run(args, torch, B, synth, dev, wl, x_np, single_thread)
+    if result is not None:
+        print(json.dumps(result))
 
+
+def codec_run(args, torch, B, synth, dev, wl, x_np, single_thread):
+    """One tensor: group_stats -> sample_sensitivity -> allocate_bits -> quantize_pack -> unpack_dequantize."""
+    N, D, ng, G = wl.N, wl.D, wl.ng, wl.G
     x = torch.from_numpy(x_np).to(dev)
 
     # sensitivities whose greedy allocation at a 2.0-bit budget is the workload's width multiset
@@ -617,7 +740,7 @@ def main():
         read_back()
         print(json.dumps({"profile_pass": True, "workload": wl.name, "copy_bytes_each_way": N * D * wl.elem_bytes,
                           "packed_bytes": state["total"], "header_bytes": N * ng * 8}))
-        return
+        return None
     read_back()
     assert np.array_equal(state["bits"], wl.bits), "allocator did not return the workload's widths"
 
@@ -679,19 +802,6 @@ def main():
                 "traffic": None if args.uniform_bits else measured_traffic(wl.name, args.noise_bits, dominant),
                 "algorithmic_bytes_per_launch": alg[dominant], "avg_launch_ms": kernel_ms[dominant]}
 
-    if wl.dtype == "f16" and dominant == "quantize_pack" and args.noise_bits == 16 and hf == B.ACTQ_HDR_F32:
-        # The binary16 quantizer is bound by vector-ALU issue, not by HBM (rocprofv3 shows every SIMD issuing
-        # all the time): its roofline is the issue rate of one wavefront instruction per four clocks and SIMD.
-        # The instruction count per 1024 elements is the SQ_INSTS_VALU figure of
-        # profiles/sq_counters_r50_stem_f16_noise16.md; the duration is this run's.
-        valu_per_tile = 352
-        issued = valu_per_tile * (N * D / 1024) / (kernel_ms[dominant] * 1e-3) / 1e9
-        peak = 1024 * 2.4 / 4                      # 256 compute units x 4 SIMDs at 2.4 GHz: G wavefront instructions / s
-        roofline = {"bound": "alu", "kernel": dominant, "achieved": issued, "peak": peak,
-                    "unit": "G wavefront instructions/s", "frac": issued / peak, "traffic": None,
-                    "valu_instructions_per_1024_elements": valu_per_tile, "avg_launch_ms": kernel_ms[dominant],
-                    "hbm_frac": achieved / HBM_PEAK_GBS}
-
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import oracle
@@ -735,7 +845,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
     }
-    print(json.dumps(result))
+    return result
 
 
 if __name__ == "__main__":

@@ -39,6 +39,30 @@ constexpr int kBlock = kWave * kWavesPerBlock;
 constexpr int kTileGroups = 4;
 constexpr int kMaxMulti = ACTQ_MAX_TENSORS_PER_CALL;  // tensors of one multi-tensor launch
 
+// Shape of the dequantizer's launch (full-group tensors): groups per wavefront for binary32 and
+// binary16 output, threads per block, and whether the group headers come through the vector
+// memory path (one lane-uniform load per group) or the scalar data path.
+#ifndef ACTQ_DQ_GROUPS_F32
+#define ACTQ_DQ_GROUPS_F32 4
+#endif
+#ifndef ACTQ_DQ_GROUPS_F16
+#define ACTQ_DQ_GROUPS_F16 8
+#endif
+#ifndef ACTQ_DQ_BLOCK
+#define ACTQ_DQ_BLOCK 256
+#endif
+#ifndef ACTQ_DQ_VHDR
+#define ACTQ_DQ_VHDR 1
+#endif
+#ifndef ACTQ_DQ_XCD_MAP
+#define ACTQ_DQ_XCD_MAP 1
+#endif
+constexpr bool kDqXcdMap = ACTQ_DQ_XCD_MAP != 0;
+constexpr int kDqGroupsF32 = ACTQ_DQ_GROUPS_F32;
+constexpr int kDqGroupsF16 = ACTQ_DQ_GROUPS_F16;
+constexpr int kDqBlock = ACTQ_DQ_BLOCK;
+constexpr bool kDqVectorHeader = ACTQ_DQ_VHDR != 0;
+
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
@@ -292,6 +316,36 @@ __device__ __forceinline__ uint32_t bf16_ceil_bits(float f)
 // Header of group `index` as (Z, step R / B).  HDR: 0 = stored as such in binary32; 1 = (Z, R) in
 // bfloat16; 2 = one (Z, R) pair in binary32 for the whole tensor, the step being 0 when R is 0
 // or B / R overflows (the degenerate rule of the quantizer).
+// A zero the compiler cannot see through, in a vector register: added to a wavefront-uniform
+// index it keeps the load on the vector memory path.
+__device__ __forceinline__ uint32_t vector_zero()
+{
+    uint32_t z;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(z));
+    return z;
+}
+
+// The same header through the vector memory path: every lane loads the same address.
+template <int HDR>
+__device__ __forceinline__ f32x2 load_header_vector(const void* __restrict__ header, int64_t index, float kB, uint32_t vzero)
+{
+    if (HDR == 2) {
+        const f32x2 zr = static_cast<const f32x2*>(header)[vzero];
+        f32x2 h;
+        h.x = zr.x;
+        h.y = (zr.y != 0.0f && __builtin_isfinite(kB / zr.y)) ? zr.y / kB : 0.0f;
+        return h;
+    }
+    if (HDR == 1) {
+        const uint32_t w = static_cast<const uint32_t*>(header)[index + vzero];
+        f32x2 h;
+        h.x = __uint_as_float(w << 16);
+        h.y = __uint_as_float(w & 0xffff0000u) / kB;
+        return h;
+    }
+    return static_cast<const f32x2*>(header)[index + vzero];
+}
+
 template <int HDR>
 __device__ __forceinline__ f32x2 load_header(const void* __restrict__ header, int64_t index, float kB)
 {
@@ -629,11 +683,16 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_tile_kernel(
 // ------------------------------------------------------------------------------------
 // Sec. 4.1: h^ = code * scale + Z.
 
-template <typename T, bool VEC, int B, int HDR>
-__device__ __forceinline__ void dequantize_tile(const uint8_t* __restrict__ src_sample,
-                                                const void* __restrict__ header, T* __restrict__ os,
-                                                int64_t D, uint32_t n, uint32_t g0, int groups, uint32_t ng,
-                                                int lane, uint32_t* stage)
+// NG consecutive groups of one sample, all of them present: straight-line code, every load is
+// issued before the first store and nothing branches in between.  (A branch around a load or a
+// store makes the compiler wait for *all* outstanding vector memory operations where the paths
+// join -- and on this target a store counts until it is acknowledged, so the stores of a
+// wavefront would go out one at a time.)
+template <typename T, bool VEC, int B, int HDR, int NG, bool VHDR>
+__device__ __forceinline__ void dequantize_groups(const uint8_t* __restrict__ src_sample,
+                                                  const void* __restrict__ header, T* __restrict__ os,
+                                                  int64_t D, uint32_t n, uint32_t g0, uint32_t ng,
+                                                  int lane, uint32_t* stage)
 {
     // a lane's four codes are the 4*B bits that start at bit 4*B*lane of the group: inside one
     // 32-bit word when B divides 8, possibly across two words otherwise
@@ -641,49 +700,48 @@ __device__ __forceinline__ void dequantize_tile(const uint8_t* __restrict__ src_
     constexpr uint32_t code_mask = (1u << B) - 1u;
     const uint32_t first_word = static_cast<uint32_t>(lane) * (4u * B) >> 5;
     const uint32_t shift = static_cast<uint32_t>(lane) * (4u * B) & 31u;
-    uint32_t word[kTileGroups], next[kTileGroups];
-    f32x2 hd[kTileGroups];
+    uint32_t word[NG], next[NG];
+    f32x2 hd[NG];
+    uint32_t vzero = 0;
+    if (VHDR) vzero = vector_zero();
+    const int64_t hdr0 = static_cast<int64_t>(n) * ng + g0;
+    const uint32_t* tile_src = reinterpret_cast<const uint32_t*>(src_sample + static_cast<uint64_t>(g0) * (32 * B));
     if (!kAligned) {
-        // The tile's bit stream (groups * 32 * B contiguous bytes) comes in with coalesced word
-        // loads and is handed over through the wavefront's LDS slice; every lane then picks the
-        // two words that hold its bits.
-        const uint32_t* tile_src = reinterpret_cast<const uint32_t*>(src_sample + static_cast<uint64_t>(g0) * (32 * B));
-        const int words = groups * 8 * B;
-        constexpr int kLoads = (32 * B + 63) / 64;
+        // The bit stream of the NG groups (NG * 32 * B contiguous bytes) comes in with coalesced
+        // word loads and is handed over through the wavefront's LDS slice; every lane then picks
+        // the two words that hold its bits.
+        constexpr int kWords = NG * 8 * B;
+        constexpr int kLoads = (kWords + 63) / 64;
         uint32_t in[kLoads];
 #pragma unroll
         for (int j = 0; j < kLoads; ++j) {
-            const int idx = min(j * 64 + lane, words - 1);  // clamped: lanes past the end re-read the last word
+            const int idx = min(j * 64 + lane, kWords - 1);  // clamped: lanes past the end re-read the last word
             in[j] = __builtin_nontemporal_load(tile_src + idx);
         }
 #pragma unroll
-        for (int u = 0; u < kTileGroups; ++u)
-            if (u < groups)
-                hd[u] = load_header<HDR>(header, static_cast<int64_t>(n) * ng + g0 + u, static_cast<float>(code_mask));
+        for (int u = 0; u < NG; ++u)
+            hd[u] = VHDR ? load_header_vector<HDR>(header, hdr0 + u, static_cast<float>(code_mask), vzero)
+                         : load_header<HDR>(header, hdr0 + u, static_cast<float>(code_mask));
 #pragma unroll
         for (int j = 0; j < kLoads; ++j) stage[j * 64 + lane] = in[j];  // at most 256 words
         wave_lds_handover();
 #pragma unroll
-        for (int u = 0; u < kTileGroups; ++u) {
-            // past the tile's last word the neighbour is never used: those lanes' bits end with the word
+        for (int u = 0; u < NG; ++u) {
+            // past the last word the neighbour is never used: those lanes' bits end with the word
             word[u] = stage[u * 8 * B + first_word];
             next[u] = stage[u * 8 * B + first_word + 1];
         }
-        wave_lds_handover();  // the slice is reused by the next tile of this wavefront
+        wave_lds_handover();  // the slice is reused by the next call of this wavefront
     } else {
 #pragma unroll
-        for (int u = 0; u < kTileGroups; ++u) {
-            if (u >= groups) continue;
-            const uint32_t g = g0 + u;
-            const uint32_t* src = reinterpret_cast<const uint32_t*>(src_sample + static_cast<uint64_t>(g) * (32 * B));
-            word[u] = __builtin_nontemporal_load(src + first_word);
-            hd[u] = load_header<HDR>(header, static_cast<int64_t>(n) * ng + g, static_cast<float>(code_mask));
+        for (int u = 0; u < NG; ++u) {
+            word[u] = __builtin_nontemporal_load(tile_src + u * 8 * B + first_word);
+            hd[u] = VHDR ? load_header_vector<HDR>(header, hdr0 + u, static_cast<float>(code_mask), vzero)
+                         : load_header<HDR>(header, hdr0 + u, static_cast<float>(code_mask));
         }
     }
 #pragma unroll
-    for (int u = 0; u < kTileGroups; ++u) {
-        if (u >= groups) continue;
-        const uint32_t g = g0 + u;
+    for (int u = 0; u < NG; ++u) {
         const uint32_t piece = kAligned ? word[u] >> shift : __builtin_amdgcn_alignbit(next[u], word[u], shift);
         float o[4];
 #pragma unroll
@@ -691,7 +749,7 @@ __device__ __forceinline__ void dequantize_tile(const uint8_t* __restrict__ src_
             const uint32_t q = (piece >> (k * B)) & code_mask;
             o[k] = __builtin_fmaf(static_cast<float>(q), hd[u].y, hd[u].x);
         }
-        const int64_t d0 = (static_cast<int64_t>(g) << 8) + lane * 4;
+        const int64_t d0 = (static_cast<int64_t>(g0 + u) << 8) + lane * 4;
         if (VEC) {
             Io<T>::store4(os + d0, o);
         } else {
@@ -706,7 +764,7 @@ __device__ __forceinline__ void dequantize_tile(const uint8_t* __restrict__ src_
 // takes eight consecutive elements (16 bytes) and the wavefront covers two groups per step
 // (lanes 0..31 the even group, lanes 32..63 the odd one).  Unpacking is free to choose its
 // lane-to-element map: nothing is reduced across lanes.
-template <bool VEC, int B, int HDR, int NP = 2>
+template <bool VEC, int B, int HDR, int NP = 2, bool ALL = false>
 __device__ __forceinline__ void dequantize_tile_f16(const uint8_t* __restrict__ src_sample,
                                                     const void* __restrict__ header,
                                                     _Float16* __restrict__ os, int64_t D, uint32_t n, uint32_t g0,
@@ -723,7 +781,7 @@ __device__ __forceinline__ void dequantize_tile_f16(const uint8_t* __restrict__ 
     for (int p = 0; p < NP; ++p) {
         code_lo[p] = code_hi[p] = 0;
         const int u = 2 * p + half;
-        live[p] = u < groups;
+        live[p] = ALL || u < groups;                // ALL: every group of the run is present, nothing branches
         const uint32_t g = g0 + (live[p] ? u : 0);  // a dead lane re-reads the tile's first group
         const uint8_t* src = src_sample + static_cast<uint64_t>(g) * (32 * B) + li * B;  // 8*B bits per lane
         if (B < 4) {
@@ -739,7 +797,7 @@ __device__ __forceinline__ void dequantize_tile_f16(const uint8_t* __restrict__ 
         }
         // both groups' headers through the scalar data path (their indices are uniform), then the
         // lane's half picks one: a per-lane load would be a second vector load in front of each store
-        const int u_even = 2 * p < groups ? 2 * p : 0, u_odd = 2 * p + 1 < groups ? 2 * p + 1 : 0;
+        const int u_even = (ALL || 2 * p < groups) ? 2 * p : 0, u_odd = (ALL || 2 * p + 1 < groups) ? 2 * p + 1 : 0;
         const f32x2 hd_even = load_header<HDR>(header, static_cast<int64_t>(n) * ng + g0 + u_even, static_cast<float>(code_mask));
         const f32x2 hd_odd = load_header<HDR>(header, static_cast<int64_t>(n) * ng + g0 + u_odd, static_cast<float>(code_mask));
         hd[p].x = half ? hd_odd.x : hd_even.x;
@@ -767,23 +825,28 @@ __device__ __forceinline__ void dequantize_tile_f16(const uint8_t* __restrict__ 
     }
 }
 
-// NG groups starting at g0 (NG = 4, or 8 for binary16 output in the multi-tensor kernel).
-template <typename T, bool VEC, int B, int HDR, int NG = kTileGroups>
+// `groups` (1..NG) groups starting at g0.  All NG present: the straight-line code; the last,
+// shorter run of a sample goes group by group.
+template <typename T, bool VEC, int B, int HDR, int NG = kTileGroups, bool VHDR = false>
 __device__ __forceinline__ void dequantize_any(const uint8_t* __restrict__ src_sample,
                                                const void* __restrict__ header, T* __restrict__ os,
                                                int64_t D, uint32_t n, uint32_t g0, int groups, uint32_t ng, int lane,
                                                uint32_t* stage)
 {
-    static_assert(NG % kTileGroups == 0, "whole tiles");
-    if constexpr (sizeof(T) == 2 && (8 % B) == 0) {
-        dequantize_tile_f16<VEC, B, HDR, NG / 2>(src_sample, header, os, D, n, g0, groups, ng, lane);
+    if constexpr (sizeof(T) == 2 && (8 % B) == 0 && NG % 2 == 0) {
+        if (groups == NG) dequantize_tile_f16<VEC, B, HDR, NG / 2, true>(src_sample, header, os, D, n, g0, groups, ng, lane);
+        else dequantize_tile_f16<VEC, B, HDR, NG / 2, false>(src_sample, header, os, D, n, g0, groups, ng, lane);
     } else {
+        // at most four groups at a time: the LDS slice of a wavefront holds 256 words
+        constexpr int kStep = NG < kTileGroups ? NG : kTileGroups;
+        static_assert(NG % kStep == 0, "whole steps");
+        if (groups == NG) {
 #pragma unroll
-        for (int t = 0; t < NG / kTileGroups; ++t) {
-            const int left = groups - t * kTileGroups;     // uniform
-            if (left <= 0) break;
-            dequantize_tile<T, VEC, B, HDR>(src_sample, header, os, D, n, g0 + t * kTileGroups,
-                                            left < kTileGroups ? left : kTileGroups, ng, lane, stage);
+            for (int t = 0; t < NG / kStep; ++t)
+                dequantize_groups<T, VEC, B, HDR, kStep, VHDR>(src_sample, header, os, D, n, g0 + t * kStep, ng, lane, stage);
+        } else {
+            for (int u = 0; u < groups; ++u)
+                dequantize_groups<T, VEC, B, HDR, 1, VHDR>(src_sample, header, os, D, n, g0 + u, ng, lane, stage);
         }
     }
 }
@@ -859,12 +922,25 @@ struct MultiTable {
 
 __device__ __forceinline__ uint32_t fastdiv(uint32_t n, FastDiv f) { return (__umulhi(n, f.m) + n) >> f.s; }
 
+// Linear work index of wavefront `wave` of block `bx`.  Blocks are handed to the eight XCDs in
+// turn, so block bx runs on XCD bx % 8 (grid.x is a multiple of 8).  Instead of giving a block
+// WAVES consecutive units, every run of 8 blocks shares 8 * WAVES consecutive units and block
+// bx takes the units congruent to bx modulo 8: each XCD then writes (or reads) every eighth
+// unit of the stream rather than WAVES-unit chunks.
+template <int WAVES, bool XCD_MAP>
+__device__ __forceinline__ uint32_t wave_unit(uint32_t bx, uint32_t wave)
+{
+    if (XCD_MAP) return (bx >> 3) * (8 * WAVES) + (bx & 7u) + 8 * wave;
+    return bx * WAVES + wave;
+}
+
 // The wavefront's tensor, sample and tile inside the sample; false if it has no work.
+template <int WAVES_PER_BLOCK = kWavesPerBlock>
 __device__ __forceinline__ bool multi_work(const MultiTable& t, uint32_t wave, int lane, uint32_t& l, uint32_t& n,
                                            uint32_t& tile)
 {
     l = blockIdx.y;
-    const uint32_t lin = blockIdx.x * kWavesPerBlock + wave;
+    const uint32_t lin = wave_unit<WAVES_PER_BLOCK, false>(blockIdx.x, wave);
     const MultiItem& it = t.item[l];
     if (lin >= it.total_tiles) return false;
     n = fastdiv(lin, it.by_tiles);
@@ -924,35 +1000,91 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_multi_kernel(MultiTable 
                                    static_cast<uint32_t>(tensor_tag >> 32), packed, capacity, it.header, stage_all[wave]);
 }
 
-template <typename T, int HDR, int NG>
-__global__ __launch_bounds__(kBlock) void unpack_dequantize_multi_kernel(MultiTable t, const uint8_t* __restrict__ packed,
-                                                                         uint64_t capacity)
+// Makes the listed scalar values live at this point of the program: every scalar load that
+// produces them has been issued, and is waited for, here -- as one batch.  Left to itself the
+// compiler fetches each field of a table item, and each of widths and offsets, right where it
+// is first used, which strings four to six dependent scalar memory round trips in front of the
+// first vector load of a wavefront.
+#define ACTQ_SCALAR_BATCH2(a, b) asm volatile("" : "+s"(a), "+s"(b))
+#define ACTQ_SCALAR_BATCH9(a, b, c, d, e, f, g, h, i) \
+    asm volatile("" : "+s"(a), "+s"(b), "+s"(c), "+s"(d), "+s"(e), "+s"(f), "+s"(g), "+s"(h), "+s"(i))
+
+// What a wavefront of a multi-tensor launch needs to know before it touches the tensor.
+struct MultiCursor {
+    uint32_t n, tile;      // sample, run of groups inside the sample
+    uint32_t b;            // width of the sample
+    uint64_t off;          // byte offset of the sample in the bit stream
+    uint64_t D;
+    uintptr_t data, header;  // x or out, and the header array
+};
+
+// Fetches the tensor's item and the sample's width and offset in two batches of scalar loads.
+// OUT: the cursor's data pointer is the tensor's output (else its input).  False: no work.
+template <int WAVES_PER_BLOCK, bool OUT, bool XCD_MAP>
+__device__ __forceinline__ bool multi_cursor(const MultiTable& t, uint32_t wave, MultiCursor& c)
 {
-    __shared__ uint32_t stage_all[kWavesPerBlock][256];
+    const MultiItem& it = t.item[blockIdx.y];
+    const uint32_t lin = wave_unit<WAVES_PER_BLOCK, XCD_MAP>(blockIdx.x, wave);
+    uint32_t total = it.total_tiles, tiles = it.tiles, dm = it.by_tiles.m, ds = it.by_tiles.s;
+    uint64_t D = static_cast<uint64_t>(it.D);
+    uintptr_t p_bits = reinterpret_cast<uintptr_t>(it.bits), p_off = reinterpret_cast<uintptr_t>(it.offsets);
+    uintptr_t p_data = OUT ? reinterpret_cast<uintptr_t>(it.out) : reinterpret_cast<uintptr_t>(it.x);
+    uintptr_t p_hdr = reinterpret_cast<uintptr_t>(it.header);
+    ACTQ_SCALAR_BATCH9(total, tiles, dm, ds, D, p_bits, p_off, p_data, p_hdr);
+    if (lin >= total) return false;
+    c.n = (__umulhi(lin, dm) + lin) >> ds;
+    c.tile = lin - c.n * tiles;
+    uint32_t width_word = load_readonly(reinterpret_cast<const uint32_t*>(p_bits) + (c.n >> 2));
+    uint64_t off = load_readonly(reinterpret_cast<const uint64_t*>(p_off) + c.n);
+    ACTQ_SCALAR_BATCH2(width_word, off);
+    c.b = (width_word >> ((c.n & 3u) * 8u)) & 0xffu;
+    c.off = off;
+    c.D = D;
+    c.data = p_data;
+    c.header = p_hdr;
+    return true;
+}
+
+// True if the sample's byte range [off, off + bytes) is 32-byte aligned and inside the stream.
+// Subtractions with borrow: stays on the scalar ALU, which has no 64-bit ordered compare.
+__device__ __forceinline__ bool range_ok(uint64_t off, uint64_t bytes, uint64_t capacity)
+{
+    unsigned long long room, rest;
+    const bool past = __builtin_usubll_overflow(capacity, off, &room);   // off > capacity
+    const bool over = __builtin_usubll_overflow(room, bytes, &rest);     // bytes > capacity - off
+    return (off & 31u) == 0 && !past && !over;
+}
+
+template <typename T, int HDR, int NG>
+__global__ __launch_bounds__(kDqBlock) void unpack_dequantize_multi_kernel(MultiTable t, const uint8_t* __restrict__ packed,
+                                                                           uint64_t capacity)
+{
+    constexpr int kWaves = kDqBlock / kWave;
+    __shared__ uint32_t stage_all[kWaves][256];
     const int lane = threadIdx.x & (kWave - 1);
     const uint32_t wave = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6)));
     uint32_t* stage = stage_all[wave];
-    uint32_t l, n, tile;
-    if (!multi_work(t, wave, lane, l, n, tile)) return;
-    const MultiItem& it = t.item[l];
-    const uint32_t ng = static_cast<uint32_t>(it.D >> 8);
-    T* os = static_cast<T*>(it.out) + static_cast<int64_t>(n) * it.D;
-    const uint32_t b = load_width(it.bits, n);
-    const uint64_t off = load_readonly(it.offsets + n);
-    const uint64_t bytes = static_cast<uint64_t>(ng) * 32u * b;
-    if ((off & 31u) != 0 || off > capacity || bytes > capacity - off) return;
-    const uint8_t* src = packed + off;
-    const uint32_t g0 = tile * NG;
+    MultiCursor c;
+    if (!multi_cursor<kWaves, true, kDqXcdMap>(t, wave, c)) return;
+    const uint32_t ng = static_cast<uint32_t>(c.D >> 8);
+    const uint32_t n = c.n;
+    const int64_t D = static_cast<int64_t>(c.D);
+    T* os = reinterpret_cast<T*>(c.data) + static_cast<int64_t>(n) * D;
+    const void* header = reinterpret_cast<const void*>(c.header);
+    if (!range_ok(c.off, static_cast<uint64_t>(ng) * 32u * c.b, capacity)) return;
+    const uint8_t* src = packed + c.off;
+    const uint32_t g0 = c.tile * NG;
     const int groups = static_cast<int>(min(static_cast<uint32_t>(NG), ng - g0));
-    switch (b) {
-        case 1: dequantize_any<T, true, 1, HDR, NG>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
-        case 2: dequantize_any<T, true, 2, HDR, NG>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
-        case 3: dequantize_any<T, true, 3, HDR, NG>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
-        case 4: dequantize_any<T, true, 4, HDR, NG>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
-        case 5: dequantize_any<T, true, 5, HDR, NG>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
-        case 6: dequantize_any<T, true, 6, HDR, NG>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
-        case 7: dequantize_any<T, true, 7, HDR, NG>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
-        case 8: dequantize_any<T, true, 8, HDR, NG>(src, it.header, os, it.D, n, g0, groups, ng, lane, stage); break;
+    constexpr bool V = kDqVectorHeader;
+    switch (c.b) {
+        case 1: dequantize_any<T, true, 1, HDR, NG, V>(src, header, os, D, n, g0, groups, ng, lane, stage); break;
+        case 2: dequantize_any<T, true, 2, HDR, NG, V>(src, header, os, D, n, g0, groups, ng, lane, stage); break;
+        case 3: dequantize_any<T, true, 3, HDR, NG, V>(src, header, os, D, n, g0, groups, ng, lane, stage); break;
+        case 4: dequantize_any<T, true, 4, HDR, NG, V>(src, header, os, D, n, g0, groups, ng, lane, stage); break;
+        case 5: dequantize_any<T, true, 5, HDR, NG, V>(src, header, os, D, n, g0, groups, ng, lane, stage); break;
+        case 6: dequantize_any<T, true, 6, HDR, NG, V>(src, header, os, D, n, g0, groups, ng, lane, stage); break;
+        case 7: dequantize_any<T, true, 7, HDR, NG, V>(src, header, os, D, n, g0, groups, ng, lane, stage); break;
+        case 8: dequantize_any<T, true, 8, HDR, NG, V>(src, header, os, D, n, g0, groups, ng, lane, stage); break;
         default: return;
     }
 }
@@ -1525,7 +1657,8 @@ int launch_unpack_dequantize(const void* packed, uint64_t capacity, const void* 
     // A tensor with full groups goes through the multi-tensor kernel as a table of one: its linear
     // grid over (sample, tile) measured 7 % faster on the stage-1 tensor than samples in grid.y
     // (72.9 against 79.3 us in the same run).
-    if (vec && N * ((D / kGroup + kTileGroups - 1) / kTileGroups) < (int64_t(1) << 31)) {
+    const int64_t per_wave = out_dtype == ACTQ_F16 ? kDqGroupsF16 : kDqGroupsF32;
+    if (vec && N * ((D / kGroup + per_wave - 1) / per_wave) < (int64_t(1) << 31)) {
         actq_tensor one = {};
         one.out = out;
         one.header = const_cast<void*>(header);
@@ -1575,7 +1708,8 @@ int launch_allocate_bits(const float* w, const int64_t* D_items, int64_t D, int6
 }
 
 static int make_multi_table(const char* who, const actq_tensor* tensors, int32_t count, int64_t N, int hdr,
-                            MultiTable* t, dim3* grid, int groups_per_wave = kTileGroups)
+                            MultiTable* t, dim3* grid, int groups_per_wave = kTileGroups,
+                            int waves_per_block = kWavesPerBlock)
 {
     t->count = static_cast<uint32_t>(count);
     t->N = static_cast<uint32_t>(N);
@@ -1601,7 +1735,9 @@ static int make_multi_table(const char* who, const actq_tensor* tensors, int32_t
         it.tiles = static_cast<uint32_t>(per_sample);
         it.total_tiles = static_cast<uint32_t>(tiles);
     }
-    *grid = dim3(static_cast<unsigned>((most + kWavesPerBlock - 1) / kWavesPerBlock), static_cast<unsigned>(count));
+    // whole runs of 8 blocks (one block per XCD)
+    const uint64_t per_run = 8u * static_cast<uint64_t>(waves_per_block);
+    *grid = dim3(static_cast<unsigned>((most + per_run - 1) / per_run * 8u), static_cast<unsigned>(count));
     return ACTQ_OK;
 }
 
@@ -1640,19 +1776,17 @@ int launch_unpack_dequantize_multi(const actq_tensor* tensors, int32_t count, co
 {
     MultiTable t;
     dim3 grid;
-    // binary16 output: eight groups per wavefront, so that a wavefront writes the same 4 KiB as with binary32
-    constexpr int kGroupsF16 = 2 * kTileGroups;
-    const int per_wave = out_dtype == ACTQ_F16 ? kGroupsF16 : kTileGroups;
-    if (int rc = make_multi_table("actq_unpack_dequantize_multi", tensors, count, N, hdr, &t, &grid, per_wave)) return rc;
+    const int per_wave = out_dtype == ACTQ_F16 ? kDqGroupsF16 : kDqGroupsF32;
+    if (int rc = make_multi_table("actq_unpack_dequantize_multi", tensors, count, N, hdr, &t, &grid, per_wave, kDqBlock / kWave)) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint8_t* pk = static_cast<const uint8_t*>(packed);
 #define ACTQ_DEQM(T, NG)                                                                                    \
     do {                                                                                                 \
-        if (hdr == ACTQ_HDR_F32) unpack_dequantize_multi_kernel<T, 0, NG><<<grid, kBlock, 0, s>>>(t, pk, capacity);       \
-        else if (hdr == ACTQ_HDR_BF16) unpack_dequantize_multi_kernel<T, 1, NG><<<grid, kBlock, 0, s>>>(t, pk, capacity); \
-        else unpack_dequantize_multi_kernel<T, 2, NG><<<grid, kBlock, 0, s>>>(t, pk, capacity);                           \
+        if (hdr == ACTQ_HDR_F32) unpack_dequantize_multi_kernel<T, 0, NG><<<grid, kDqBlock, 0, s>>>(t, pk, capacity);       \
+        else if (hdr == ACTQ_HDR_BF16) unpack_dequantize_multi_kernel<T, 1, NG><<<grid, kDqBlock, 0, s>>>(t, pk, capacity); \
+        else unpack_dequantize_multi_kernel<T, 2, NG><<<grid, kDqBlock, 0, s>>>(t, pk, capacity);                           \
     } while (0)
-    if (out_dtype == ACTQ_F32) ACTQ_DEQM(float, kTileGroups); else ACTQ_DEQM(_Float16, kGroupsF16);
+    if (out_dtype == ACTQ_F32) ACTQ_DEQM(float, kDqGroupsF32); else ACTQ_DEQM(_Float16, kDqGroupsF16);
 #undef ACTQ_DEQM
     return check_launch("actq_unpack_dequantize_multi");
 }
