@@ -122,9 +122,12 @@ int actq_group_stats(const void* x, actq_dtype dt, int64_t N, int64_t D, int32_t
  *   noise_bits = 16: counter (d>>3, n, lo32(tag), hi32(tag)), element d takes
  *                    word (d>>1)&3, low half if d is even, high half if odd,
  *                    noise = half * 2^-16, and code = floor(u + noise), the sum
- *                    being one binary32 addition (it rounds up exactly when
- *                    noise >= 1 - frac(u)).  This is the fast mode: one
- *                    generator call serves eight elements.
+ *                    being one binary32 addition rounded to nearest.  Over the
+ *                    65,536 noise values the code is ceil(u) with a probability
+ *                    within 2^-16 of frac(u) (the noise grid and the rounding of
+ *                    the sum both stay inside that bound), an integer u keeps its
+ *                    code, and the code never exceeds B.  This is the fast mode:
+ *                    one generator call serves eight elements.
  * key = (lo32(seed), hi32(seed)).  `tag` separates tensors (layers) that share
  * a seed.  Requires N < 2^32 and D < 2^34.
  *

@@ -222,11 +222,13 @@ static void group_scale(float B, float range, float* inv_out, float* scale_out)
  * u - floor(u) and floor(u) otherwise.  Two realisations of that rule:
  *   24-bit noise: compare the noise with the fractional part, code = floor(u) + [noise < frac];
  *   16-bit noise: add the noise and floor, code = floor(u + noise), the sum being one binary32
- *                 addition.  (floor(u + U) with U uniform on [0,1) rounds up exactly when
- *                 U >= 1 - frac, i.e. with probability frac.)  With noise on a 2^-16 grid and
- *                 u <= 255 the sum of an integer u and the noise is exact, so grid points keep
- *                 their code, and u + noise <= B + 1 - 2^-16 is representable, so the code
- *                 never exceeds B. */
+ *                 addition rounded to nearest.  (In exact arithmetic floor(u + U) with U uniform
+ *                 on [0,1) rounds up when U >= 1 - frac, i.e. with probability frac.  Here the
+ *                 noise lies on a 2^-16 grid and the sum is rounded, so the probability of
+ *                 rounding up over the 65,536 noise values is frac only to within 2^-16: that is
+ *                 the bound the tests enumerate.)  With u <= 255 the sum of an integer u and the
+ *                 noise is exact, so grid points keep their code, and u + noise <= B + 1 - 2^-16
+ *                 is representable, so the code never exceeds B. */
 static unsigned stochastic_code(float h, float mn, float inv, float B, float noise, int noise_bits)
 {
     float centred = h - mn;

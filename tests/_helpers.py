@@ -72,3 +72,35 @@ def witness_noise_words(seed: int, tag: int, n: int, counter0: int) -> np.ndarra
     off = 4 * (counter0 + (n << 32))
     assert off < (1 << 64)
     return witness_words([(seed, tag, off)])[0]
+
+
+def clamp_case(noise_bits: int, seed: int = 321, D: int = 1 << 18):
+    """A one-sample tensor of D elements (8 bits) whose group maxima overshoot B = 255 by one
+    ulp after the two roundings of (h - Z) * (B / R), placed on exactly those elements whose
+    noise is extreme enough to turn the overshoot into code 256 if the scaled value were not
+    clamped (Sec. 4.1 scaling; noise below that ulp when compared, within that ulp of 1 when
+    added).  Returns (x [1, D] float32, the indices of those elements)."""
+    import oracle
+    B = np.float32(255.0)
+    rng = np.random.default_rng(0)
+    r = None
+    for cand in rng.uniform(0.5, 2.0, 200000).astype(np.float32):
+        if np.float32(cand * np.float32(B / cand)) > B:
+            r = cand
+            break
+    assert r is not None
+    over = float(np.float32(r * np.float32(B / r))) - 255.0     # one ulp of 255 = 2^-16
+    assert over > 0
+    if noise_bits == 24:
+        hits = [d for d in range(D) if oracle.noise(seed, 0, 0, d, 24) < over]
+    else:
+        hits = [d for d in range(D) if oracle.noise(seed, 0, 0, d, 16) >= 1.0 - over]
+    assert hits, "no element with extreme enough noise; enlarge D"
+    x = np.zeros((1, D), dtype=np.float32)
+    x[0, 1::2] = r / 2
+    for d in hits:
+        x[0, d] = r
+        g = d // 256
+        if x[0, g * 256:(g + 1) * 256].min() != 0.0:
+            x[0, g * 256 + (1 if d % 256 == 0 else 0)] = 0.0
+    return x, hits

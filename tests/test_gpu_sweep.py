@@ -1,0 +1,109 @@
+"""Full-size parity in the library's working mode (16-bit noise), the ResNet-50 sweep exactly as
+bench.py runs it, and the constructed clamp case on the GPU.  Everything goes through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2104_14129_amd import binding as B
+from paper_2104_14129_amd import synth
+from paper_2104_14129_amd.plan import TensorSetPlan, size_classes
+from _gpu import GpuRun
+from _helpers import clamp_case
+from test_gpu_parity import _round_trip, _round_trip_bf16
+
+pytestmark = pytest.mark.gpu
+
+
+def test_config3_r50_stem_f16_full_size_noise16():
+    wl = synth.r50_stem_f16()
+    x = synth.make_input(wl)
+    print(f"[full-size] {wl.name} noise_bits=16", flush=True)
+    _round_trip(x.reshape(wl.N, wl.D), wl.bits, wl.philox_seed, wl.tag, 16, (torch.float16,))
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+def test_config4_fpn_full_size_noise16(variant):
+    wl = synth.fpn(variant)
+    x = synth.make_input(wl)
+    print(f"[full-size] {wl.name} noise_bits=16", flush=True)
+    _round_trip(x.reshape(wl.N, wl.D), wl.bits, wl.philox_seed, wl.tag, 16, (torch.float32,))
+
+
+def test_bf16_header_config2_full_size_noise24():
+    wl = synth.r50_stage1()
+    x = synth.make_input(wl)
+    _round_trip_bf16(x.reshape(wl.N, wl.D), wl.bits, wl.philox_seed, wl.tag, 24)
+
+
+@pytest.mark.parametrize("noise_bits", [24, 16])
+def test_scaled_value_is_clamped_to_B_on_the_gpu(noise_bits):
+    """Sec. 4.1 scaling: the group maximum can land one ulp above B; placed on elements whose noise
+    would then produce code B + 1, every such element must still get code B = 255."""
+    x, hits = clamp_case(noise_bits)
+    bits = np.array([8], dtype=np.uint8)
+    run = GpuRun(x, bits)
+    packed, header = run.quantize(321, 0, noise_bits)
+    codes = packed.reshape(1, -1)                      # 8 bits: the stream is the byte array of codes
+    assert all(codes[0, d] == 255 for d in hits)
+    want = oracle.quantize_codes(x, bits, 321, noise_bits=noise_bits)
+    assert np.array_equal(codes[:, :x.shape[1]], want)
+
+
+def test_size_classes_partition_every_tensor_once():
+    Ds = [c * h * w for c, h, w in synth.resnet50_conv_input_shapes()]
+    classes = size_classes(Ds)
+    assert sorted(l for c in classes for l in c) == list(range(53))
+    assert [len(c) for c in classes] == [4, 6, 17, 10, 11, 5]
+    assert all(len(c) <= B.MAX_TENSORS_PER_CALL for c in size_classes([256] * 100))
+
+
+@pytest.mark.parametrize("N", [256])
+def test_resnet50_sweep_exactly_as_the_bench_runs_it(N):
+    """The 53 tensors at batch 256 through the launches bench.py times: group_stats_multi,
+    actq_allocate_bits_device over all 13,568 (layer, sample) items with per-item sizes,
+    quantize_pack_multi and unpack_dequantize_multi per size class into one shared bit stream with
+    16-bit noise and tag 1000 * class + position.  Every layer's statistics, widths, offsets,
+    headers, packed bytes and outputs are compared with the oracle."""
+    dev = torch.device("cuda:0")
+    G = 256
+    Dl = [c * h * w for c, h, w in synth.resnet50_conv_input_shapes()]
+    L = len(Dl)
+    gen = torch.Generator(device=dev)
+    xs = []
+    for l, D in enumerate(Dl):
+        gen.manual_seed(1000 + l)
+        xs.append(torch.randn((N, D), generator=gen, device=dev, dtype=torch.float32).clamp_min_(0))
+    w_host = synth.lognormal_sensitivities(N * L, seed=5)
+    D_host = np.repeat(np.array(Dl, dtype=np.int64), N)
+    budget = 2 * int(D_host.sum())
+    plan = TensorSetPlan(xs, N, budget // 8 + 4096, noise_bits=16, seed=15, G=G)
+    plan.packed.fill_(0xA5)
+    plan.group_stats()
+    plan.allocate(torch.from_numpy(w_host).to(dev), torch.from_numpy(D_host).to(dev), budget)
+    plan.quantize_pack()
+    plan.unpack_dequantize()
+    torch.cuda.synchronize()
+    total, status = (int(v) for v in plan.result.cpu())
+    assert status == 0
+    bits_all = plan.bits.cpu().numpy()
+    offs_all = plan.offsets.cpu().numpy()
+    assert np.array_equal(bits_all, oracle.allocate_bits(w_host, D_host, budget))
+    packed = plan.packed.cpu().numpy()
+    assert (packed[total:] == 0xA5).all(), "the quantizer wrote past the allocated stream"
+    base = 0
+    for l, D in enumerate(Dl):
+        print(f"[sweep] layer {l} D={D}", flush=True)
+        x_np = xs[l].cpu().numpy()
+        b_np = np.ascontiguousarray(bits_all[l * N:(l + 1) * N])
+        omin, orange = oracle.group_stats(x_np, G)
+        assert np.array_equal(plan.gmin[l].cpu().numpy().view(np.uint32), omin.reshape(-1).view(np.uint32)), l
+        assert np.array_equal(plan.grange[l].cpu().numpy().view(np.uint32), orange.reshape(-1).view(np.uint32)), l
+        opk, ohd, ooff = oracle.quantize_pack(x_np, b_np, 15, plan.tags[l], G, 16)
+        assert np.array_equal(offs_all[l * N:(l + 1) * N].view(np.uint64), ooff + np.uint64(base)), l
+        assert np.array_equal(plan.header[l].cpu().numpy().view(np.uint32), ohd.reshape(-1).view(np.uint32)), l
+        assert np.array_equal(packed[base:base + opk.size], opk), l
+        want = oracle.unpack_dequantize(opk, ohd, b_np, ooff, N, D, G)
+        assert np.array_equal(plan.outs[l].cpu().numpy().view(np.uint32), want.view(np.uint32)), l
+        base += opk.size
+    assert base == total

@@ -12,7 +12,7 @@ import pytest
 
 import oracle
 from paper_2104_14129_amd import synth
-from _helpers import philox_witness, round_fraction_to_f32, witness_noise_words
+from _helpers import clamp_case, philox_witness, round_fraction_to_f32, witness_noise_words
 
 WIDTHS = (1, 2, 3, 4, 5, 6, 7, 8)
 
@@ -368,29 +368,8 @@ def test_scaled_value_is_clamped_to_B_before_rounding(noise_bits):
     maximum.  Without the clamp that element would get code B + 1 whenever its noise is
     extreme enough (below that ulp when compared, within that ulp of 1 when added); the test
     places the maximum exactly on such elements."""
-    B = np.float32(255.0)
-    rng = np.random.default_rng(0)
-    r = None
-    for cand in rng.uniform(0.5, 2.0, 200000).astype(np.float32):
-        if np.float32(cand * np.float32(B / cand)) > B:
-            r = cand
-            break
-    assert r is not None
-    over = float(np.float32(r * np.float32(B / r))) - 255.0     # one ulp of 255 = 2^-16
-    assert over > 0
-    seed, D = 321, 1 << 18
-    if noise_bits == 24:
-        hits = [d for d in range(D) if oracle.noise(seed, 0, 0, d, 24) < over]
-    else:
-        hits = [d for d in range(D) if oracle.noise(seed, 0, 0, d, 16) >= 1.0 - over]
-    assert hits, "no element with extreme enough noise; enlarge D"
-    x = np.zeros((1, D), dtype=np.float32)
-    x[0, 1::2] = r / 2
-    for d in hits:
-        x[0, d] = r
-        g = d // 256
-        if x[0, g * 256:(g + 1) * 256].min() != 0.0:
-            x[0, g * 256 + (1 if d % 256 == 0 else 0)] = 0.0
+    seed = 321
+    x, hits = clamp_case(noise_bits, seed)
     codes = oracle.quantize_codes(x, np.array([8], dtype=np.uint8), seed, noise_bits=noise_bits)
     assert all(codes[0, d] == 255 for d in hits)
 
