@@ -325,9 +325,9 @@ def sweep(args, torch, B, synth, dev, single_thread=None):
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
+        import oracle
         # The oracle (all OpenMP threads) on whole layers of the same inputs and widths, layer by layer so
         # that host memory stays bounded, until about `--cpu-seconds` of oracle time are spent.
-        import oracle
         spent, done_bytes, done_layers = 0.0, 0, 0
         order = sorted(range(L), key=lambda l: Dl[l])          # small layers first: the sample spans every size
         for l in order:

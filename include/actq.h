@@ -62,6 +62,12 @@ typedef enum actq_header_format {
 /* Library version, major*10000 + minor*100 + patch. */
 int actq_version(void);
 
+/* Hex digest of the sources and build flags this binary was compiled from (set by the build
+ * script; "unknown" for a hand build).  The Python binding compares it with the digest of the
+ * sources beside it, so that an edited kernel is never tested against a stale binary.  The
+ * pointer is to static storage. */
+const char* actq_source_hash(void);
+
 /* Text of the last error raised on this thread ("" if none).  The pointer stays
  * valid until the next failing call on the same thread. */
 const char* actq_last_error(void);

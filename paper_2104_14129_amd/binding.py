@@ -22,7 +22,7 @@ G_DEFAULT = 256
 ACTQ_HDR_F32, ACTQ_HDR_BF16, ACTQ_HDR_TENSOR = 0, 1, 2
 ACTQ_WIDTHS_POW2, ACTQ_WIDTHS_ALL = 0x116, 0x1FE  # allowed-width sets of the allocator (bit b = b bits)
 
-EXPORTS = ("actq_version", "actq_last_error", "actq_packed_bytes", "actq_header_bytes", "actq_group_stats",
+EXPORTS = ("actq_version", "actq_source_hash", "actq_last_error", "actq_packed_bytes", "actq_header_bytes", "actq_group_stats",
            "actq_quantize_pack", "actq_unpack_dequantize", "actq_sample_sensitivity", "actq_allocate_bits",
            "actq_allocate_bits_device", "actq_relu_mask_bytes", "actq_relu_forward", "actq_relu_backward",
            "actq_pool2d_output_size", "actq_maxpool2d_forward", "actq_maxpool2d_backward", "actq_tensor_stats",
@@ -38,15 +38,56 @@ class ActqError(RuntimeError):
 _lib = None
 
 
+def _digest_in_file(path: str):
+    """The source digest baked into a built library, read from the file (nothing is loaded)."""
+    marker = b"actq-source-digest:"
+    try:
+        with open(path, "rb") as f:
+            blob = f.read()
+    except OSError:
+        return None
+    at = blob.find(marker)
+    if at < 0:
+        return None
+    end = blob.find(b"\0", at)
+    return blob[at + len(marker):end].decode(errors="replace")
+
+
+def _load_checked() -> ctypes.CDLL:
+    """libactq.so, built from exactly the sources beside it: a missing library is built; one whose
+    baked-in source digest differs from the sources' is rebuilt when a compiler is there and refused
+    otherwise (an edited kernel must never be tested or timed against a stale binary)."""
+    from . import build as _build
+    want = _build.source_hash()
+    have = _digest_in_file(LIB_PATH)
+    if have != want:
+        try:
+            _build.build()
+        except Exception as exc:
+            if not os.path.exists(LIB_PATH):
+                raise
+            raise RuntimeError(f"{LIB_PATH} was built from other sources (digest {have}, sources {want}) "
+                               f"and cannot be rebuilt here: {exc}") from exc
+    L = ctypes.CDLL(LIB_PATH)
+    L.actq_source_hash.restype = ctypes.c_char_p
+    L.actq_source_hash.argtypes = []
+    have = L.actq_source_hash().decode()
+    if have != want:
+        raise RuntimeError(f"{LIB_PATH} reports source digest {have}, the sources beside it have {want}")
+    return L
+
+
+def source_hash() -> str:
+    """Digest baked into the loaded library (equal to the digest of the sources beside it)."""
+    return lib().actq_source_hash().decode()
+
+
 def lib() -> ctypes.CDLL:
-    """Loads libactq.so (building it first only when no built library exists)."""
+    """Loads libactq.so, checked against the sources it sits beside."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(LIB_PATH):
-        from . import build as _build
-        _build.build()
-    L = ctypes.CDLL(LIB_PATH)
+    L = _load_checked()
     c = ctypes
     vp, i64, i32, u64 = c.c_void_p, c.c_int64, c.c_int32, c.c_uint64
     L.actq_version.restype = c.c_int

@@ -27,6 +27,21 @@ HIPCC_FLAGS = [
 ]
 
 
+def source_hash() -> str:
+    """Digest of everything the binary depends on: the sources, the public and internal headers
+    and the compiler flags."""
+    import hashlib
+    h = hashlib.sha256()
+    files = [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC)) if f.endswith((".hip", ".cpp", ".h"))]
+    files.append(os.path.join(ROOT, "include", "actq.h"))
+    for path in files:
+        h.update(os.path.basename(path).encode())
+        with open(path, "rb") as f:
+            h.update(f.read())
+    h.update(" ".join(HIPCC_FLAGS).encode())
+    return h.hexdigest()[:16]
+
+
 def hipcc() -> str:
     exe = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
     if not os.path.exists(exe):
@@ -37,7 +52,8 @@ def hipcc() -> str:
 def build(verbose: bool = False) -> str:
     """Compile every source of the library; always recompiles."""
     tmp = LIB + f".{os.getpid()}.tmp"
-    cmd = [hipcc(), *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-x", "hip"]
+    cmd = [hipcc(), *HIPCC_FLAGS, f'-DACTQ_SOURCE_HASH="{source_hash()}"',
+           "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-x", "hip"]
     cmd += [os.path.join(CSRC, s) for s in SOURCES]
     cmd += ["-o", tmp]
     if verbose:

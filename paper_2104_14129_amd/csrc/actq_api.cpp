@@ -81,7 +81,14 @@ bool make_ladder(uint32_t widths, Ladder* out)
 
 extern "C" {
 
-int actq_version(void) { return 300; }
+int actq_version(void) { return 400; }
+
+#ifndef ACTQ_SOURCE_HASH
+#define ACTQ_SOURCE_HASH "unknown"
+#endif
+// the digest follows a fixed marker, so that it can also be read from the file without loading it
+static const char g_source_digest[] = "actq-source-digest:" ACTQ_SOURCE_HASH;
+const char* actq_source_hash(void) { return g_source_digest + sizeof("actq-source-digest:") - 1; }
 
 int actq_header_bytes(int64_t N, int64_t D, int32_t G, actq_header_format hf, uint64_t* bytes_host)
 {
@@ -193,7 +200,9 @@ int actq_allocate_bits(const float* w, const int64_t* D, int64_t M, int64_t budg
         return fail(ACTQ_EINVAL, "actq_allocate_bits: widths mask 0x%x must be a non-empty subset of bits 1..8", widths);
     __int128 used = 0;
     for (int64_t i = 0; i < M; ++i) {
-        if (!(w[i] >= 0.0f) || !std::isfinite(w[i]))
+        uint32_t pattern;
+        std::memcpy(&pattern, &w[i], sizeof pattern);
+        if (!valid_sensitivity_bits(pattern))
             return fail(ACTQ_EINVAL, "actq_allocate_bits: w[%lld] must be finite and >= 0", (long long)i);
         if (D[i] <= 0) return fail(ACTQ_EINVAL, "actq_allocate_bits: D[%lld] must be positive", (long long)i);
         used += static_cast<__int128>(D[i]) * lad.width[0];

@@ -3,12 +3,25 @@
 #define ACTQ_INTERNAL_H
 
 #include <cstdint>
+#include <cstring>
+
+#include <hip/hip_runtime.h>
 
 #include "actq.h"
 
 namespace actq {
 
 constexpr int kGroup = 256;  // the one supported group size: one wavefront x 4 elements
+
+// A sensitivity is valid if it is finite and not negative (-0.0 counts as zero).  Decided on the
+// bit pattern: this library is compiled under the assumption that its floating-point data holds
+// no NaN, which lets the compiler fold away a NaN test written as a comparison.
+__host__ __device__ inline bool valid_sensitivity_bits(uint32_t bits)
+{
+    const bool finite = (bits & 0x7f800000u) != 0x7f800000u;   // exponent all ones: infinity or NaN
+    const bool negative = (bits >> 31) != 0 && bits != 0x80000000u;
+    return finite && !negative;
+}
 
 // Records a message for actq_last_error() and returns `code`.
 int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));

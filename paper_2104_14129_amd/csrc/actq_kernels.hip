@@ -1351,7 +1351,7 @@ __global__ __launch_bounds__(kAllocBlock) void allocate_bits_kernel(const float*
         const bool live = i < a.M;
         const float wi = live ? w[i] : 0.0f;
         const int64_t Di = live ? (a.D_items ? a.D_items[i] : a.D) : 0;
-        const bool ok = live && wi >= 0.0f && __builtin_isfinite(wi) && Di > 0 && Di < (int64_t(1) << 34);
+        const bool ok = live && valid_sensitivity_bits(__float_as_uint(wi)) && Di > 0 && Di < (int64_t(1) << 34);
         bad = bad || (live && !ok);
         cached_w[j] = static_cast<double>(wi);
         cached_D[j] = ok ? static_cast<double>(Di) : 0.0;
@@ -1365,7 +1365,7 @@ __global__ __launch_bounds__(kAllocBlock) void allocate_bits_kernel(const float*
     for (int64_t i = tid + static_cast<int64_t>(CACHED) * threads; i < a.M; i += threads) {
         const float wi = w[i];
         const int64_t Di = a.D_items ? a.D_items[i] : a.D;
-        if (!(wi >= 0.0f) || !__builtin_isfinite(wi) || Di <= 0 || Di >= (int64_t(1) << 34)) bad = true;
+        if (!valid_sensitivity_bits(__float_as_uint(wi)) || Di <= 0 || Di >= (int64_t(1) << 34)) bad = true;
         else my_elems += static_cast<uint64_t>(Di);
     }
     const bool invalid = __syncthreads_or(bad ? 1 : 0) != 0;

@@ -167,45 +167,63 @@ def decompress(c: SavedContext) -> torch.Tensor:
 
 # ----------------------------------------------------------------------------- functions
 
+def _keep(ctx, c: SavedContext, *tensors) -> None:
+    """Hands the compressed context to autograd: its tensors are released when the graph is, so a
+    second backward pass over a retained graph finds them again."""
+    streams = c.host if c.host is not None else (c.packed, c.header)
+    ctx.context_meta = (c.shape, c.dtype, c.N, c.D, c.hf, c.ready, c.host is not None)
+    ctx.save_for_backward(c.bits, c.offsets, streams[0], streams[1], *tensors)
+
+
+def _recall(ctx):
+    """(dequantized context, the other saved tensors)."""
+    bits, offsets, s0, s1, *tensors = ctx.saved_tensors
+    c = SavedContext()
+    c.shape, c.dtype, c.N, c.D, c.hf, c.ready, swapped = ctx.context_meta
+    c.bits, c.offsets = bits, offsets
+    c.host, c.packed, c.header = ((s0, s1), None, None) if swapped else (None, s0, s1)
+    return decompress(c), tensors
+
+
 class _QLinearFn(torch.autograd.Function):
     @staticmethod
     def forward(ctx, x, weight, bias):
-        ctx.saved = compress(x)
-        ctx.save_for_backward(weight)
+        _keep(ctx, compress(x), weight)
         ctx.has_bias = bias is not None
         return F.linear(x, weight, bias)
 
     @staticmethod
     def backward(ctx, grad_y):
-        (weight,) = ctx.saved_tensors
-        x = decompress(ctx.saved)
-        ctx.saved = None
+        x, (weight,) = _recall(ctx)
+        # under autocast the output (and so grad_y) is narrower than the saved input and the weight:
+        # the stock backward then computes in grad_y's type and returns gradients of the operands' types
         g2 = grad_y.reshape(-1, grad_y.shape[-1])
-        grad_x = grad_y.matmul(weight) if ctx.needs_input_grad[0] else None
-        grad_w = g2.t().matmul(x.reshape(-1, x.shape[-1])) if ctx.needs_input_grad[1] else None
-        grad_b = g2.sum(0) if ctx.has_bias and ctx.needs_input_grad[2] else None
+        grad_x = grad_y.matmul(weight.to(grad_y.dtype)).to(x.dtype) if ctx.needs_input_grad[0] else None
+        grad_w = (g2.t().matmul(x.reshape(-1, x.shape[-1]).to(grad_y.dtype)).to(weight.dtype)
+                  if ctx.needs_input_grad[1] else None)
+        grad_b = g2.sum(0).to(weight.dtype) if ctx.has_bias and ctx.needs_input_grad[2] else None
         return grad_x, grad_w, grad_b
 
 
 class _QConv2dFn(torch.autograd.Function):
     @staticmethod
     def forward(ctx, x, weight, bias, stride, padding, dilation, groups):
-        ctx.saved = compress(x)
-        ctx.save_for_backward(weight)
+        _keep(ctx, compress(x), weight)
         ctx.geometry = (stride, padding, dilation, groups)
         ctx.bias_sizes = None if bias is None else [bias.shape[0]]
         return F.conv2d(x, weight, bias, stride, padding, dilation, groups)
 
     @staticmethod
     def backward(ctx, grad_y):
-        (weight,) = ctx.saved_tensors
+        x, (weight,) = _recall(ctx)
         stride, padding, dilation, groups = ctx.geometry
-        x = decompress(ctx.saved)
-        ctx.saved = None
         mask = [ctx.needs_input_grad[0], ctx.needs_input_grad[1], ctx.bias_sizes is not None and ctx.needs_input_grad[2]]
-        gx, gw, gb = torch.ops.aten.convolution_backward(grad_y.contiguous(), x, weight, ctx.bias_sizes, list(stride),
-                                                         list(padding), list(dilation), False, [0, 0], groups, mask)
-        return gx, gw, gb, None, None, None, None
+        ct = grad_y.dtype                                # the compute type (narrower under autocast)
+        gx, gw, gb = torch.ops.aten.convolution_backward(grad_y.contiguous(), x.to(ct), weight.to(ct), ctx.bias_sizes,
+                                                         list(stride), list(padding), list(dilation), False, [0, 0],
+                                                         groups, mask)
+        return (None if gx is None else gx.to(x.dtype), None if gw is None else gw.to(weight.dtype),
+                None if gb is None else gb.to(weight.dtype), None, None, None, None)
 
 
 class _QBatchNormFn(torch.autograd.Function):
@@ -213,20 +231,17 @@ class _QBatchNormFn(torch.autograd.Function):
     def forward(ctx, x, weight, bias, running_mean, running_var, training, momentum, eps):
         y, mean, invstd = torch.ops.aten.native_batch_norm(x, weight, bias, running_mean, running_var, training,
                                                            momentum, eps)
-        ctx.saved = compress(x)
-        ctx.save_for_backward(weight, running_mean, running_var, mean, invstd)
+        _keep(ctx, compress(x), weight, running_mean, running_var, mean, invstd)
         ctx.training, ctx.eps = training, eps
         return y
 
     @staticmethod
     def backward(ctx, grad_y):
-        weight, running_mean, running_var, mean, invstd = ctx.saved_tensors
-        x = decompress(ctx.saved)
-        ctx.saved = None
+        x, (weight, running_mean, running_var, mean, invstd) = _recall(ctx)
         mask = [ctx.needs_input_grad[0], weight is not None and ctx.needs_input_grad[1],
                 weight is not None and ctx.needs_input_grad[2]]
-        gx, gw, gb = torch.ops.aten.native_batch_norm_backward(grad_y.contiguous(), x, weight, running_mean, running_var,
-                                                               mean, invstd, ctx.training, ctx.eps, mask)
+        gx, gw, gb = torch.ops.aten.native_batch_norm_backward(grad_y.contiguous().to(x.dtype), x, weight, running_mean,
+                                                               running_var, mean, invstd, ctx.training, ctx.eps, mask)
         return gx, gw, gb, None, None, None, None, None
 
 
@@ -236,12 +251,13 @@ class _QReLUFn(torch.autograd.Function):
     @staticmethod
     def forward(ctx, x):
         y, mask = B.relu_forward(x.contiguous())
-        ctx.mask = mask
+        ctx.save_for_backward(mask)
         return y
 
     @staticmethod
     def backward(ctx, grad_y):
-        return B.relu_backward(ctx.mask, grad_y.contiguous())
+        (mask,) = ctx.saved_tensors
+        return B.relu_backward(mask, grad_y.contiguous())
 
 
 class _QMaxPool2dFn(torch.autograd.Function):
@@ -250,13 +266,15 @@ class _QMaxPool2dFn(torch.autograd.Function):
     @staticmethod
     def forward(ctx, x, kernel, stride, padding, dilation):
         y, arg = B.maxpool2d_forward(x.contiguous(), kernel, stride, padding, dilation)
-        ctx.arg, ctx.geometry = arg, (int(x.shape[-2]), int(x.shape[-1]), kernel, stride, padding, dilation)
+        ctx.save_for_backward(arg)
+        ctx.geometry = (int(x.shape[-2]), int(x.shape[-1]), kernel, stride, padding, dilation)
         return y
 
     @staticmethod
     def backward(ctx, grad_y):
+        (arg,) = ctx.saved_tensors
         H, W, kernel, stride, padding, dilation = ctx.geometry
-        return B.maxpool2d_backward(ctx.arg, grad_y.contiguous(), H, W, kernel, stride, padding, dilation), None, None, None, None
+        return B.maxpool2d_backward(arg, grad_y.contiguous(), H, W, kernel, stride, padding, dilation), None, None, None, None
 
 
 # ----------------------------------------------------------------------------- modules

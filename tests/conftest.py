@@ -27,3 +27,12 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+def pytest_report_header(config):
+    """Which library binary the tests run against, and the digest of the sources it was built from."""
+    try:
+        from paper_2104_14129_amd import binding as B
+        return f"libactq: {B.LIB_PATH} (source digest {B.source_hash()}, version {B.version()})"
+    except Exception as exc:     # reported, never hidden: the ABI tests fail on their own
+        return f"libactq: not loadable ({type(exc).__name__}: {exc})"

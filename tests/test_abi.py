@@ -247,3 +247,22 @@ def test_multi_tensor_calls_validate_before_launching():
     assert deq(table(), dt=2) == E and deq(table(), packed=None) == E
     for k, v in [("out", None), ("out", FAKE + 8), ("header", None), ("bits", None), ("offsets", None), ("D", 257)]:
         assert deq(table(**{k: v})) == E, (k, v)
+
+
+def test_the_loaded_library_was_built_from_the_sources_beside_it():
+    """The binary carries a digest of its sources and flags; the binding refuses (or rebuilds) a
+    library whose digest differs, so an edited kernel is never tested against a stale binary."""
+    from paper_2104_14129_amd import build as lib_build
+    assert B.source_hash() == lib_build.source_hash()
+    assert B._digest_in_file(B.LIB_PATH) == lib_build.source_hash()
+    # a binary with another digest is told apart without loading it
+    import tempfile
+    blob = open(B.LIB_PATH, "rb").read()
+    marker = b"actq-source-digest:"
+    at = blob.index(marker) + len(marker)
+    other = blob[:at] + (b"0" if blob[at:at + 1] != b"0" else b"1") + blob[at + 1:]
+    with tempfile.NamedTemporaryFile(suffix=".so") as f:
+        f.write(other)
+        f.flush()
+        assert B._digest_in_file(f.name) != lib_build.source_hash()
+    assert B._digest_in_file("/nonexistent/libactq.so") is None

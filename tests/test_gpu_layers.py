@@ -239,3 +239,43 @@ def test_a_small_network_trains_with_compressed_activations():
     assert compressed[0] == pytest.approx(stock[0], rel=1e-4)       # same forward at the first step
     assert compressed[-1] < 0.3 * compressed[0]                      # it learns
     assert compressed[-1] < stock[-1] + 0.3                          # about as well as full precision
+
+
+def test_a_retained_graph_can_be_walked_twice():
+    """The compressed context is handed to autograd, so it lives as long as the graph: a second
+    backward pass over a retained graph dequantizes the same context and gives the same gradients."""
+    torch.manual_seed(3)
+    L.config.mixed, L.config.bits = False, 4.0
+    net = nn.Sequential(L.QConv2d(3, 8, 3, padding=1), L.QBatchNorm2d(8), L.QReLU(), L.QMaxPool2d(2),
+                        nn.Flatten(), L.QLinear(8 * 8 * 8, 5)).to(DEV)
+    x = torch.randn(4, 3, 16, 16, device=DEV, requires_grad=True)
+    loss = net(x).square().sum()
+    first = torch.autograd.grad(loss, [x, *net.parameters()], retain_graph=True)
+    second = torch.autograd.grad(loss, [x, *net.parameters()])
+    for a, b in zip(first, second):       # the stock convolution backward may add in a different order
+        assert torch.allclose(a, b, rtol=1e-4, atol=1e-5 * float(a.abs().max()))
+
+
+def test_layers_run_under_autocast():
+    """Under autocast the layer's output, and so the incoming gradient, is binary16 while the saved
+    input and the weights are binary32: the backward computes in the gradient's type and returns
+    gradients of the operands' types, as the stock layers do."""
+    torch.manual_seed(4)
+    L.config.mixed, L.config.bits = False, 8.0
+    stock = nn.Sequential(nn.Conv2d(3, 8, 3, padding=1), nn.ReLU(), nn.Flatten(), nn.Linear(8 * 12 * 12, 6)).to(DEV)
+    ours = nn.Sequential(L.QConv2d(3, 8, 3, padding=1), L.QReLU(), nn.Flatten(), L.QLinear(8 * 12 * 12, 6)).to(DEV)
+    ours.load_state_dict(stock.state_dict())
+    x = torch.randn(5, 3, 12, 12, device=DEV)
+    grads = []
+    for net in (stock, ours):
+        xin = x.clone().requires_grad_(True)
+        with torch.autocast("cuda", dtype=torch.float16):
+            y = net(xin)
+            assert y.dtype == torch.float16
+            loss = y.float().square().mean()
+        loss.backward()
+        assert xin.grad.dtype == torch.float32 and all(p.grad.dtype == torch.float32 for p in net.parameters())
+        grads.append([xin.grad.clone()] + [p.grad.clone() for p in net.parameters()])
+    # 8-bit contexts of binary16-rounded activations: the gradients agree to binary16 accuracy
+    for a, b in zip(*grads):
+        assert torch.allclose(a, b, rtol=5e-2, atol=5e-3 * float(a.abs().max()))
