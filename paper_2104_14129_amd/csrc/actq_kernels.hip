@@ -934,45 +934,120 @@ __device__ __forceinline__ uint32_t wave_unit(uint32_t bx, uint32_t wave)
     return bx * WAVES + wave;
 }
 
-// The wavefront's tensor, sample and tile inside the sample; false if it has no work.
-template <int WAVES_PER_BLOCK = kWavesPerBlock>
-__device__ __forceinline__ bool multi_work(const MultiTable& t, uint32_t wave, int lane, uint32_t& l, uint32_t& n,
-                                           uint32_t& tile)
+// Makes the listed scalar values live at this point of the program: every scalar load that
+// produces them has been issued, and is waited for, here -- as one batch.  Left to itself the
+// compiler fetches each field of a table item, and each of widths and offsets, right where it
+// is first used, which strings four to six dependent scalar memory round trips in front of the
+// first vector load of a wavefront.
+#define ACTQ_SCALAR_BATCH2(a, b) asm volatile("" : "+s"(a), "+s"(b))
+#define ACTQ_SCALAR_BATCH10(a, b, c, d, e, f, g, h, i, j) \
+    asm volatile("" : "+s"(a), "+s"(b), "+s"(c), "+s"(d), "+s"(e), "+s"(f), "+s"(g), "+s"(h), "+s"(i), "+s"(j))
+
+// What a wavefront of a multi-tensor launch knows after one batch of scalar loads from the
+// table: its sample and its run of groups inside the sample, and the tensor's pointers.
+struct MultiCursor {
+    uint32_t n, tile;        // sample, run of groups inside the sample
+    uint64_t D;
+    uintptr_t x, out, header, gmin, grange, bits, offsets;
+};
+
+// A pointer that went through an integer register has lost its address space, and the compiler
+// would emit flat memory instructions for it (which also tick the LDS counter).  Everything the
+// table points to is device memory: the pointer is rebuilt as a global one, and the conversion
+// to a generic pointer lets the compiler carry that knowledge to every use.
+template <typename P>
+__device__ __forceinline__ P* device_pointer(uintptr_t a)
 {
-    l = blockIdx.y;
-    const uint32_t lin = wave_unit<WAVES_PER_BLOCK, false>(blockIdx.x, wave);
-    const MultiItem& it = t.item[l];
-    if (lin >= it.total_tiles) return false;
-    n = fastdiv(lin, it.by_tiles);
-    tile = lin - n * it.tiles;
+    typedef P __attribute__((address_space(1))) * global_pointer;
+    return (P*)((global_pointer)a);
+}
+
+// False: the wavefront has no work.  XCD_MAP: the order of wave_unit.
+template <int WAVES_PER_BLOCK, bool XCD_MAP>
+__device__ __forceinline__ bool multi_cursor(const MultiTable& t, uint32_t wave, MultiCursor& c)
+{
+    const MultiItem& it = t.item[blockIdx.y];
+    const uint32_t lin = wave_unit<WAVES_PER_BLOCK, XCD_MAP>(blockIdx.x, wave);
+    // tiles: low word the runs per sample, high word all runs of the tensor
+    uint64_t tiles = (static_cast<uint64_t>(it.total_tiles) << 32) | it.tiles;
+    uint64_t div = (static_cast<uint64_t>(it.by_tiles.s) << 32) | it.by_tiles.m;
+    c.D = static_cast<uint64_t>(it.D);
+    c.x = reinterpret_cast<uintptr_t>(it.x);
+    c.out = reinterpret_cast<uintptr_t>(it.out);
+    c.header = reinterpret_cast<uintptr_t>(it.header);
+    c.gmin = reinterpret_cast<uintptr_t>(it.gmin);
+    c.grange = reinterpret_cast<uintptr_t>(it.grange);
+    c.bits = reinterpret_cast<uintptr_t>(it.bits);
+    c.offsets = reinterpret_cast<uintptr_t>(it.offsets);
+    ACTQ_SCALAR_BATCH10(tiles, div, c.D, c.x, c.out, c.header, c.gmin, c.grange, c.bits, c.offsets);
+    if (lin >= static_cast<uint32_t>(tiles >> 32)) return false;
+    c.n = (__umulhi(lin, static_cast<uint32_t>(div)) + lin) >> static_cast<uint32_t>(div >> 32);
+    c.tile = lin - c.n * static_cast<uint32_t>(tiles);
     return true;
 }
 
+// Width and byte offset of the cursor's sample, as one batch of scalar loads.
+__device__ __forceinline__ void sample_width_offset(const MultiCursor& c, uint32_t& b, uint64_t& off)
+{
+    uint32_t width_word = load_readonly(reinterpret_cast<const uint32_t*>(c.bits) + (c.n >> 2));
+    off = load_readonly(reinterpret_cast<const uint64_t*>(c.offsets) + c.n);
+    ACTQ_SCALAR_BATCH2(width_word, off);
+    b = (width_word >> ((c.n & 3u) * 8u)) & 0xffu;
+}
+
+// True if the sample's byte range [off, off + bytes) is 32-byte aligned and inside the stream.
+__device__ __forceinline__ bool range_ok(uint64_t off, uint64_t bytes, uint64_t capacity)
+{
+    return (off & 31u) == 0 && off <= capacity && bytes <= capacity - off;
+}
+
+#ifndef ACTQ_GS_TILES
+#define ACTQ_GS_TILES 1
+#endif
+#ifndef ACTQ_GS_BLOCK
+#define ACTQ_GS_BLOCK 256
+#endif
+#ifndef ACTQ_GS_XCD_MAP
+#define ACTQ_GS_XCD_MAP 0
+#endif
+constexpr int kGsTiles = ACTQ_GS_TILES;    // tiles (of four groups) per wavefront of the statistics kernel
+constexpr int kGsBlock = ACTQ_GS_BLOCK;
+
 template <typename T>
-__global__ __launch_bounds__(kBlock) void group_stats_multi_kernel(MultiTable t)
+__global__ __launch_bounds__(kGsBlock) void group_stats_multi_kernel(MultiTable t)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const uint32_t wave = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6)));
-    uint32_t l, n, tile;
-    if (!multi_work(t, wave, lane, l, n, tile)) return;
-    const MultiItem& it = t.item[l];
-    const uint32_t ng = static_cast<uint32_t>(it.D >> 8);
-    const T* xs = static_cast<const T*>(it.x) + static_cast<int64_t>(n) * it.D;
-    const uint32_t g0 = tile * kTileGroups;
-    const int groups = static_cast<int>(min(static_cast<uint32_t>(kTileGroups), ng - g0));
-    float v[kTileGroups][4];
+    MultiCursor c;
+    if (!multi_cursor<kGsBlock / kWave, ACTQ_GS_XCD_MAP != 0>(t, wave, c)) return;
+    const uint32_t n = c.n;
+    const int64_t D = static_cast<int64_t>(c.D);
+    const uint32_t ng = static_cast<uint32_t>(c.D >> 8);
+    const T* xs = device_pointer<const T>(c.x) + static_cast<int64_t>(n) * D;
+    float v[kGsTiles][kTileGroups][4];
     bool ok[kTileGroups][4];
-    load_tile<T, true>(xs, g0, groups, lane, it.D, v, ok);
-    float lo[kTileGroups], hi[kTileGroups];
-    lane_min_max<true>(v, ok, lo, hi);
-    float mn, mx;
-    tile_min_max(lo, hi, lane, mn, mx);
-    mn += 0.0f;  // -0.0 -> +0.0
-    const int row = lane >> 4;
-    if ((lane & 15) == 0 && row < groups) {
-        const int64_t gi = static_cast<int64_t>(n) * ng + g0 + row;
-        it.gmin[gi] = mn;
-        it.grange[gi] = (mx - mn) + 0.0f;
+    int groups[kGsTiles];
+#pragma unroll
+    for (int k = 0; k < kGsTiles; ++k) {
+        const uint32_t g0 = (c.tile * kGsTiles + k) * kTileGroups;
+        groups[k] = g0 < ng ? static_cast<int>(min(static_cast<uint32_t>(kTileGroups), ng - g0)) : 0;
+        // a tile past the end of the sample re-reads the sample's first tile (its results are not stored)
+        load_tile<T, true>(xs, groups[k] ? g0 : 0u, groups[k] ? groups[k] : 1, lane, D, v[k], ok);
+    }
+#pragma unroll
+    for (int k = 0; k < kGsTiles; ++k) {
+        const uint32_t g0 = (c.tile * kGsTiles + k) * kTileGroups;
+        float lo[kTileGroups], hi[kTileGroups];
+        lane_min_max<true>(v[k], ok, lo, hi);
+        float mn, mx;
+        tile_min_max(lo, hi, lane, mn, mx);
+        mn += 0.0f;  // -0.0 -> +0.0
+        const int row = lane >> 4;
+        if ((lane & 15) == 0 && row < groups[k]) {
+            const int64_t gi = static_cast<int64_t>(n) * ng + g0 + row;
+            device_pointer<float>(c.gmin)[gi] = mn;
+            device_pointer<float>(c.grange)[gi] = (mx - mn) + 0.0f;
+        }
     }
 }
 
@@ -983,76 +1058,24 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_multi_kernel(MultiTable 
     __shared__ uint32_t stage_all[kWavesPerBlock][256];
     const int lane = threadIdx.x & (kWave - 1);
     const uint32_t wave = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6)));
+    MultiCursor mc;
+    if (!multi_cursor<kWavesPerBlock, false>(t, wave, mc)) return;
     Cursor c;
-    uint32_t l;
-    if (!multi_work(t, wave, lane, l, c.n, c.t)) return;
-    const MultiItem& it = t.item[l];
+    c.n = mc.n;
+    c.t = mc.tile;
     StreamGeometry geo;
-    geo.D = it.D;
+    geo.D = static_cast<int64_t>(mc.D);
     geo.N = t.N;
-    geo.ng = static_cast<uint32_t>(it.D >> 8);
+    geo.ng = static_cast<uint32_t>(mc.D >> 8);
     geo.tiles_per_sample = (geo.ng + kTileGroups - 1) / kTileGroups;
     geo.hdr_mode = t.hdr_mode;
-    const uint64_t tensor_tag = tag + l;  // every tensor of the launch draws its own noise
+    const uint64_t tensor_tag = tag + blockIdx.y;  // every tensor of the launch draws its own noise
     TileRegs r;
-    fetch<T, true>(static_cast<const T*>(it.x), geo, it.bits, it.offsets, lane, c, r);
+    fetch<T, true>(device_pointer<const T>(mc.x), geo, device_pointer<const uint8_t>(mc.bits),
+                   device_pointer<const uint64_t>(mc.offsets), lane, c, r);
     quantize_one<NOISE_BITS, true>(r, c, geo, lane, k0, k1, static_cast<uint32_t>(tensor_tag),
-                                   static_cast<uint32_t>(tensor_tag >> 32), packed, capacity, it.header, stage_all[wave]);
-}
-
-// Makes the listed scalar values live at this point of the program: every scalar load that
-// produces them has been issued, and is waited for, here -- as one batch.  Left to itself the
-// compiler fetches each field of a table item, and each of widths and offsets, right where it
-// is first used, which strings four to six dependent scalar memory round trips in front of the
-// first vector load of a wavefront.
-#define ACTQ_SCALAR_BATCH2(a, b) asm volatile("" : "+s"(a), "+s"(b))
-#define ACTQ_SCALAR_BATCH9(a, b, c, d, e, f, g, h, i) \
-    asm volatile("" : "+s"(a), "+s"(b), "+s"(c), "+s"(d), "+s"(e), "+s"(f), "+s"(g), "+s"(h), "+s"(i))
-
-// What a wavefront of a multi-tensor launch needs to know before it touches the tensor.
-struct MultiCursor {
-    uint32_t n, tile;      // sample, run of groups inside the sample
-    uint32_t b;            // width of the sample
-    uint64_t off;          // byte offset of the sample in the bit stream
-    uint64_t D;
-    uintptr_t data, header;  // x or out, and the header array
-};
-
-// Fetches the tensor's item and the sample's width and offset in two batches of scalar loads.
-// OUT: the cursor's data pointer is the tensor's output (else its input).  False: no work.
-template <int WAVES_PER_BLOCK, bool OUT, bool XCD_MAP>
-__device__ __forceinline__ bool multi_cursor(const MultiTable& t, uint32_t wave, MultiCursor& c)
-{
-    const MultiItem& it = t.item[blockIdx.y];
-    const uint32_t lin = wave_unit<WAVES_PER_BLOCK, XCD_MAP>(blockIdx.x, wave);
-    uint32_t total = it.total_tiles, tiles = it.tiles, dm = it.by_tiles.m, ds = it.by_tiles.s;
-    uint64_t D = static_cast<uint64_t>(it.D);
-    uintptr_t p_bits = reinterpret_cast<uintptr_t>(it.bits), p_off = reinterpret_cast<uintptr_t>(it.offsets);
-    uintptr_t p_data = OUT ? reinterpret_cast<uintptr_t>(it.out) : reinterpret_cast<uintptr_t>(it.x);
-    uintptr_t p_hdr = reinterpret_cast<uintptr_t>(it.header);
-    ACTQ_SCALAR_BATCH9(total, tiles, dm, ds, D, p_bits, p_off, p_data, p_hdr);
-    if (lin >= total) return false;
-    c.n = (__umulhi(lin, dm) + lin) >> ds;
-    c.tile = lin - c.n * tiles;
-    uint32_t width_word = load_readonly(reinterpret_cast<const uint32_t*>(p_bits) + (c.n >> 2));
-    uint64_t off = load_readonly(reinterpret_cast<const uint64_t*>(p_off) + c.n);
-    ACTQ_SCALAR_BATCH2(width_word, off);
-    c.b = (width_word >> ((c.n & 3u) * 8u)) & 0xffu;
-    c.off = off;
-    c.D = D;
-    c.data = p_data;
-    c.header = p_hdr;
-    return true;
-}
-
-// True if the sample's byte range [off, off + bytes) is 32-byte aligned and inside the stream.
-// Subtractions with borrow: stays on the scalar ALU, which has no 64-bit ordered compare.
-__device__ __forceinline__ bool range_ok(uint64_t off, uint64_t bytes, uint64_t capacity)
-{
-    unsigned long long room, rest;
-    const bool past = __builtin_usubll_overflow(capacity, off, &room);   // off > capacity
-    const bool over = __builtin_usubll_overflow(room, bytes, &rest);     // bytes > capacity - off
-    return (off & 31u) == 0 && !past && !over;
+                                   static_cast<uint32_t>(tensor_tag >> 32), packed, capacity,
+                                   device_pointer<void>(mc.header), stage_all[wave]);
 }
 
 template <typename T, int HDR, int NG>
@@ -1065,18 +1088,21 @@ __global__ __launch_bounds__(kDqBlock) void unpack_dequantize_multi_kernel(Multi
     const uint32_t wave = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6)));
     uint32_t* stage = stage_all[wave];
     MultiCursor c;
-    if (!multi_cursor<kWaves, true, kDqXcdMap>(t, wave, c)) return;
+    if (!multi_cursor<kWaves, kDqXcdMap>(t, wave, c)) return;
+    uint32_t b;
+    uint64_t off;
+    sample_width_offset(c, b, off);
     const uint32_t ng = static_cast<uint32_t>(c.D >> 8);
     const uint32_t n = c.n;
     const int64_t D = static_cast<int64_t>(c.D);
-    T* os = reinterpret_cast<T*>(c.data) + static_cast<int64_t>(n) * D;
-    const void* header = reinterpret_cast<const void*>(c.header);
-    if (!range_ok(c.off, static_cast<uint64_t>(ng) * 32u * c.b, capacity)) return;
-    const uint8_t* src = packed + c.off;
+    T* os = device_pointer<T>(c.out) + static_cast<int64_t>(n) * D;
+    const void* header = device_pointer<const void>(c.header);
+    if (!range_ok(off, static_cast<uint64_t>(ng) * 32u * b, capacity)) return;
+    const uint8_t* src = packed + off;
     const uint32_t g0 = c.tile * NG;
     const int groups = static_cast<int>(min(static_cast<uint32_t>(NG), ng - g0));
     constexpr bool V = kDqVectorHeader;
-    switch (c.b) {
+    switch (b) {
         case 1: dequantize_any<T, true, 1, HDR, NG, V>(src, header, os, D, n, g0, groups, ng, lane, stage); break;
         case 2: dequantize_any<T, true, 2, HDR, NG, V>(src, header, os, D, n, g0, groups, ng, lane, stage); break;
         case 3: dequantize_any<T, true, 3, HDR, NG, V>(src, header, os, D, n, g0, groups, ng, lane, stage); break;
@@ -1745,10 +1771,10 @@ int launch_group_stats_multi(const actq_tensor* tensors, int32_t count, int dtyp
 {
     MultiTable t;
     dim3 grid;
-    if (int rc = make_multi_table("actq_group_stats_multi", tensors, count, N, 0, &t, &grid)) return rc;
+    if (int rc = make_multi_table("actq_group_stats_multi", tensors, count, N, 0, &t, &grid, kGsTiles * kTileGroups, kGsBlock / kWave)) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (dtype == ACTQ_F32) group_stats_multi_kernel<float><<<grid, kBlock, 0, s>>>(t);
-    else group_stats_multi_kernel<_Float16><<<grid, kBlock, 0, s>>>(t);
+    if (dtype == ACTQ_F32) group_stats_multi_kernel<float><<<grid, kGsBlock, 0, s>>>(t);
+    else group_stats_multi_kernel<_Float16><<<grid, kGsBlock, 0, s>>>(t);
     return check_launch("actq_group_stats_multi");
 }
 

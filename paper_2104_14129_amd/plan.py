@@ -17,16 +17,19 @@ import ctypes
 from . import binding as B
 
 
-def size_classes(Ds, max_per_call: int = B.MAX_TENSORS_PER_CALL):
-    """Tensor indices grouped by element count, largest first; a size that occurs once joins the
-    next larger class (its surplus blocks exit at once), and no class exceeds `max_per_call`."""
+def size_classes(Ds, max_per_call: int = B.MAX_TENSORS_PER_CALL, small: int = 0):
+    """Tensor indices grouped by element count, largest first.  A size that occurs once, or a
+    class whose element counts add up to less than `small`, joins the next larger class (a launch
+    is sized for its largest tensor and the surplus blocks of smaller ones exit at once, which is
+    cheaper than a launch of its own that cannot fill the chip); no class exceeds `max_per_call`."""
     by_size = {}
     for l, D in enumerate(Ds):
         by_size.setdefault(int(D), []).append(l)
     classes = []
     for D in sorted(by_size, reverse=True):
         members = by_size[D]
-        if classes and len(members) == 1 and len(classes[-1]) < max_per_call:
+        joins = len(members) == 1 or D * len(members) < small
+        if classes and joins and len(classes[-1]) + len(members) <= max_per_call:
             classes[-1] = classes[-1] + members
             continue
         for i in range(0, len(members), max_per_call):
@@ -44,7 +47,8 @@ class TensorSetPlan:
     """
 
     def __init__(self, xs, N: int, packed_capacity: int, noise_bits: int = 16, hf: int = B.ACTQ_HDR_F32,
-                 seed: int = 15, G: int = B.G_DEFAULT, tag_stride: int = 1000, with_outputs: bool = True):
+                 seed: int = 15, G: int = B.G_DEFAULT, tag_stride: int = 1000, with_outputs: bool = True,
+                 small_class_bytes: int = 200 << 20):
         import torch
         self.torch = torch
         self.xs = list(xs)
@@ -65,7 +69,8 @@ class TensorSetPlan:
         self.grange = [torch.empty(N * (D // G), dtype=torch.float32, device=dev) for D in self.Ds]
         self.header = [torch.empty(N * (D // G) * 2, dtype=hdr_dtype, device=dev) for D in self.Ds]
         self.outs = [torch.empty((N, D), dtype=self.dtype, device=dev) for D in self.Ds] if with_outputs else None
-        self.classes = size_classes(self.Ds)
+        # a class below ~200 MB cannot keep the chip busy for longer than a launch takes to start and drain
+        self.classes = size_classes(self.Ds, small=small_class_bytes // (N * self.xs[0].element_size()))
         self.tags = {}
         self._tables, self._tag0 = [], []
         for k, members in enumerate(self.classes):

@@ -54,7 +54,9 @@ def test_size_classes_partition_every_tensor_once():
     Ds = [c * h * w for c, h, w in synth.resnet50_conv_input_shapes()]
     classes = size_classes(Ds)
     assert sorted(l for c in classes for l in c) == list(range(53))
-    assert [len(c) for c in classes] == [4, 6, 17, 10, 11, 5]
+    assert [len(c) for c in classes] == [4, 6, 17, 10, 11, 5]       # the stem joins the 200,704-element class
+    merged = size_classes(Ds, small=(200 << 20) // (256 * 4))
+    assert [len(c) for c in merged] == [4, 6, 17, 10, 16] and sorted(l for c in merged for l in c) == list(range(53))
     assert all(len(c) <= B.MAX_TENSORS_PER_CALL for c in size_classes([256] * 100))
 
 
