@@ -635,8 +635,17 @@ __device__ __forceinline__ float from_left_lane(float v)
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), kWaveShiftRight1, 0xf, 0xf, false));
 }
 
+#ifndef ACTQ_POOL_FWD_BLOCK
+#define ACTQ_POOL_FWD_BLOCK 256
+#endif
+#ifndef ACTQ_POOL_BWD_BLOCK
+#define ACTQ_POOL_BWD_BLOCK 256
+#endif
+constexpr int kPoolFwdBlock = ACTQ_POOL_FWD_BLOCK;   // threads per block of the streaming pooling kernels
+constexpr int kPoolBwdBlock = ACTQ_POOL_BWD_BLOCK;
+
 template <typename T, int K, int P, int R>
-__global__ __launch_bounds__(kBlock) void maxpool2d_forward_stream_kernel(const T* __restrict__ x, Pool g, StreamPool q,
+__global__ __launch_bounds__(kPoolFwdBlock) void maxpool2d_forward_stream_kernel(const T* __restrict__ x, Pool g, StreamPool q,
                                                                           T* __restrict__ y,
                                                                           uint8_t* __restrict__ argmax)
 {
@@ -645,7 +654,7 @@ __global__ __launch_bounds__(kBlock) void maxpool2d_forward_stream_kernel(const 
     constexpr int NR = 2 * R + K - 2;    // input rows per lane
     typedef T vec_in __attribute__((ext_vector_type(E)));
     typedef T vec_out __attribute__((ext_vector_type(NO)));
-    const uint32_t idx = blockIdx.x * kBlock + threadIdx.x;
+    const uint32_t idx = blockIdx.x * kPoolFwdBlock + threadIdx.x;
     const bool live = idx < q.total;
     // lanes past the end repeat the last lane's loads (every lane takes part in the shift) and store nothing
     const uint32_t id = live ? idx : q.total - 1;
@@ -815,7 +824,7 @@ __device__ __forceinline__ uint32_t from_right_lane(uint32_t v)
 }
 
 template <typename T, int K, int P>
-__global__ __launch_bounds__(kBlock) void maxpool2d_backward_stream_kernel(const uint8_t* __restrict__ argmax,
+__global__ __launch_bounds__(kPoolBwdBlock) void maxpool2d_backward_stream_kernel(const uint8_t* __restrict__ argmax,
                                                                            const T* __restrict__ grad_y, Pool g,
                                                                            StreamPool q, T* __restrict__ grad_x)
 {
@@ -825,7 +834,7 @@ __global__ __launch_bounds__(kBlock) void maxpool2d_backward_stream_kernel(const
     typedef T vec_in __attribute__((ext_vector_type(E)));
     typedef T vec_out __attribute__((ext_vector_type(NO)));
     typedef typename std::conditional<NO == 2, uint16_t, uint32_t>::type code_word;
-    const uint32_t idx = blockIdx.x * kBlock + threadIdx.x;
+    const uint32_t idx = blockIdx.x * kPoolBwdBlock + threadIdx.x;
     const bool live = idx < q.total;
     const uint32_t id = live ? idx : q.total - 1;   // every lane takes part in the shift
     const uint32_t strip = fastdiv(id, q.by_chunks);             // output row over all planes
@@ -936,9 +945,9 @@ static void maxpool_forward_typed(const T* x, int64_t planes, const PoolShape& p
         q.total = static_cast<uint32_t>(planes * q.rows_per_plane * q.chunks_per_row);
         dim3 unused;
         const Pool g = make_pool(p, planes, 1, &unused);
-        const unsigned blocks = (q.total + kBlock - 1) / kBlock;
-        if (p.kh == 3) maxpool2d_forward_stream_kernel<T, 3, 1, kStreamRows><<<blocks, kBlock, 0, s>>>(x, g, q, y, argmax);
-        else maxpool2d_forward_stream_kernel<T, 2, 0, kStreamRows><<<blocks, kBlock, 0, s>>>(x, g, q, y, argmax);
+        const unsigned blocks = (q.total + kPoolFwdBlock - 1) / kPoolFwdBlock;
+        if (p.kh == 3) maxpool2d_forward_stream_kernel<T, 3, 1, kStreamRows><<<blocks, kPoolFwdBlock, 0, s>>>(x, g, q, y, argmax);
+        else maxpool2d_forward_stream_kernel<T, 2, 0, kStreamRows><<<blocks, kPoolFwdBlock, 0, s>>>(x, g, q, y, argmax);
         return;
     }
     if (four_geometry) {
@@ -989,9 +998,9 @@ static void maxpool_backward_typed(const uint8_t* argmax, const T* grad_y, int64
         q.total = static_cast<uint32_t>(planes * q.rows_per_plane * q.chunks_per_row);
         dim3 unused;
         const Pool g = make_pool(p, planes, 1, &unused);
-        const unsigned blocks = (q.total + kBlock - 1) / kBlock;
-        if (p.kh == 3) maxpool2d_backward_stream_kernel<T, 3, 1><<<blocks, kBlock, 0, s>>>(argmax, grad_y, g, q, grad_x);
-        else maxpool2d_backward_stream_kernel<T, 2, 0><<<blocks, kBlock, 0, s>>>(argmax, grad_y, g, q, grad_x);
+        const unsigned blocks = (q.total + kPoolBwdBlock - 1) / kPoolBwdBlock;
+        if (p.kh == 3) maxpool2d_backward_stream_kernel<T, 3, 1><<<blocks, kPoolBwdBlock, 0, s>>>(argmax, grad_y, g, q, grad_x);
+        else maxpool2d_backward_stream_kernel<T, 2, 0><<<blocks, kPoolBwdBlock, 0, s>>>(argmax, grad_y, g, q, grad_x);
         return;
     }
     if (oct_geometry) {

@@ -57,7 +57,14 @@ constexpr int kMaxMulti = ACTQ_MAX_TENSORS_PER_CALL;  // tensors of one multi-te
 #ifndef ACTQ_DQ_XCD_MAP
 #define ACTQ_DQ_XCD_MAP 1
 #endif
-constexpr bool kDqXcdMap = ACTQ_DQ_XCD_MAP != 0;
+constexpr int kDqXcdMap = ACTQ_DQ_XCD_MAP;
+#ifndef ACTQ_DQ_RUN
+#define ACTQ_DQ_RUN 1
+#endif
+#ifndef ACTQ_QP_XCD_MAP
+#define ACTQ_QP_XCD_MAP 0
+#endif
+constexpr int kQpXcdMap = ACTQ_QP_XCD_MAP;
 constexpr int kDqGroupsF32 = ACTQ_DQ_GROUPS_F32;
 constexpr int kDqGroupsF16 = ACTQ_DQ_GROUPS_F16;
 constexpr int kDqBlock = ACTQ_DQ_BLOCK;
@@ -491,12 +498,14 @@ __device__ __forceinline__ void encode_tile(const TileRegs& td, const uint32_t (
     if (!hdr_tensor && (lane & 15) == 0 && row < groups) {
         const int64_t gi = static_cast<int64_t>(n) * ng + g0 + row;
         if (hdr_bf16) {
-            __builtin_nontemporal_store(zb | (rb << 16), static_cast<uint32_t*>(header) + gi);
+            static_cast<uint32_t*>(header)[gi] = zb | (rb << 16);
         } else {
             f32x2 h;
             h.x = mn;
             h.y = scale;
-            __builtin_nontemporal_store(h, static_cast<f32x2*>(header) + gi);
+            // an ordinary (cached) store: the 8-byte pairs of neighbouring tiles meet in the L2 and
+            // leave as whole lines; as non-temporal stores they reached HBM piecemeal (+2 % on the sweep)
+            static_cast<f32x2*>(header)[gi] = h;
         }
     }
 
@@ -923,14 +932,20 @@ struct MultiTable {
 __device__ __forceinline__ uint32_t fastdiv(uint32_t n, FastDiv f) { return (__umulhi(n, f.m) + n) >> f.s; }
 
 // Linear work index of wavefront `wave` of block `bx`.  Blocks are handed to the eight XCDs in
-// turn, so block bx runs on XCD bx % 8 (grid.x is a multiple of 8).  Instead of giving a block
-// WAVES consecutive units, every run of 8 blocks shares 8 * WAVES consecutive units and block
-// bx takes the units congruent to bx modulo 8: each XCD then writes (or reads) every eighth
-// unit of the stream rather than WAVES-unit chunks.
-template <int WAVES, bool XCD_MAP>
+// turn, so block bx runs on XCD bx % 8 (grid.x is a multiple of 8 * RUN).
+// XCD_MAP 0: RUN consecutive blocks' worth of units (RUN * WAVES units) stay on one XCD -- RUN = 1
+//   is the plain order, block bx takes units bx * WAVES ...  A longer run keeps whole cache lines
+//   of the small per-group outputs inside one XCD's L2, so that they reach HBM as fewer, fuller writes.
+// XCD_MAP 1: every run of 8 blocks shares 8 * WAVES consecutive units and block bx takes the
+//   units congruent to bx modulo 8: each XCD then writes every eighth unit of the stream.
+template <int WAVES, int XCD_MAP, int RUN = 1>
 __device__ __forceinline__ uint32_t wave_unit(uint32_t bx, uint32_t wave)
 {
-    if (XCD_MAP) return (bx >> 3) * (8 * WAVES) + (bx & 7u) + 8 * wave;
+    if (XCD_MAP == 1) return (bx >> 3) * (8 * WAVES) + (bx & 7u) + 8 * wave;
+    if (RUN > 1) {
+        const uint32_t k = bx >> 3;   // position among the blocks of this XCD
+        return (((k / RUN) * 8 + (bx & 7u)) * RUN + (k % RUN)) * WAVES + wave;
+    }
     return bx * WAVES + wave;
 }
 
@@ -963,11 +978,11 @@ __device__ __forceinline__ P* device_pointer(uintptr_t a)
 }
 
 // False: the wavefront has no work.  XCD_MAP: the order of wave_unit.
-template <int WAVES_PER_BLOCK, bool XCD_MAP>
+template <int WAVES_PER_BLOCK, int XCD_MAP, int RUN = 1>
 __device__ __forceinline__ bool multi_cursor(const MultiTable& t, uint32_t wave, MultiCursor& c)
 {
     const MultiItem& it = t.item[blockIdx.y];
-    const uint32_t lin = wave_unit<WAVES_PER_BLOCK, XCD_MAP>(blockIdx.x, wave);
+    const uint32_t lin = wave_unit<WAVES_PER_BLOCK, XCD_MAP, RUN>(blockIdx.x, wave);
     // tiles: low word the runs per sample, high word all runs of the tensor
     uint64_t tiles = (static_cast<uint64_t>(it.total_tiles) << 32) | it.tiles;
     uint64_t div = (static_cast<uint64_t>(it.by_tiles.s) << 32) | it.by_tiles.m;
@@ -1010,6 +1025,12 @@ __device__ __forceinline__ bool range_ok(uint64_t off, uint64_t bytes, uint64_t 
 #ifndef ACTQ_GS_XCD_MAP
 #define ACTQ_GS_XCD_MAP 0
 #endif
+#ifndef ACTQ_GS_RUN
+#define ACTQ_GS_RUN 16
+#endif
+#ifndef ACTQ_QP_RUN
+#define ACTQ_QP_RUN 16
+#endif
 constexpr int kGsTiles = ACTQ_GS_TILES;    // tiles (of four groups) per wavefront of the statistics kernel
 constexpr int kGsBlock = ACTQ_GS_BLOCK;
 
@@ -1019,7 +1040,7 @@ __global__ __launch_bounds__(kGsBlock) void group_stats_multi_kernel(MultiTable 
     const int lane = threadIdx.x & (kWave - 1);
     const uint32_t wave = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6)));
     MultiCursor c;
-    if (!multi_cursor<kGsBlock / kWave, ACTQ_GS_XCD_MAP != 0>(t, wave, c)) return;
+    if (!multi_cursor<kGsBlock / kWave, ACTQ_GS_XCD_MAP, ACTQ_GS_RUN>(t, wave, c)) return;
     const uint32_t n = c.n;
     const int64_t D = static_cast<int64_t>(c.D);
     const uint32_t ng = static_cast<uint32_t>(c.D >> 8);
@@ -1059,7 +1080,7 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_multi_kernel(MultiTable 
     const int lane = threadIdx.x & (kWave - 1);
     const uint32_t wave = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6)));
     MultiCursor mc;
-    if (!multi_cursor<kWavesPerBlock, false>(t, wave, mc)) return;
+    if (!multi_cursor<kWavesPerBlock, kQpXcdMap, ACTQ_QP_RUN>(t, wave, mc)) return;
     Cursor c;
     c.n = mc.n;
     c.t = mc.tile;
@@ -1088,7 +1109,7 @@ __global__ __launch_bounds__(kDqBlock) void unpack_dequantize_multi_kernel(Multi
     const uint32_t wave = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6)));
     uint32_t* stage = stage_all[wave];
     MultiCursor c;
-    if (!multi_cursor<kWaves, kDqXcdMap>(t, wave, c)) return;
+    if (!multi_cursor<kWaves, kDqXcdMap, ACTQ_DQ_RUN>(t, wave, c)) return;
     uint32_t b;
     uint64_t off;
     sample_width_offset(c, b, off);
@@ -1601,9 +1622,31 @@ bool vector_ok(int64_t D) { return D % kGroup == 0; }
 
 }  // namespace
 
+#ifndef ACTQ_SINGLE_VIA_MULTI
+#define ACTQ_SINGLE_VIA_MULTI 1
+#endif
+
+// A binary32 tensor of full groups goes through the multi-tensor kernels as a table of one: their
+// linear grid over (sample, tile) and its XCD-aware order measured faster than samples in grid.y
+// (group_stats 65 -> 63 us on the stage-1 tensor; binary16 input gained nothing and its quantizer,
+// bound by the vector ALU, lost 3 % to the longer prologue).
+static bool as_table_of_one(int dtype, int64_t N, int64_t D, int64_t groups_per_wave)
+{
+    return ACTQ_SINGLE_VIA_MULTI && dtype == ACTQ_F32 && vector_ok(D) &&
+           N * ((D / kGroup + groups_per_wave - 1) / groups_per_wave) < (int64_t(1) << 31);
+}
+
 int launch_group_stats(const void* x, int dtype, int64_t N, int64_t D, float* gmin, float* grange,
                        void* stream)
 {
+    if (as_table_of_one(dtype, N, D, kGsTiles * kTileGroups)) {
+        actq_tensor one = {};
+        one.x = x;
+        one.gmin = gmin;
+        one.grange = grange;
+        one.D = D;
+        return launch_group_stats_multi(&one, 1, dtype, N, stream);
+    }
     Geometry geo;
     dim3 grid;
     if (int rc = make_geometry("actq_group_stats", N, D, &geo, &grid)) return rc;
@@ -1654,6 +1697,15 @@ int launch_quantize_pack(const void* x, int dtype, int64_t N, int64_t D, const u
                          const uint64_t* offsets, uint64_t seed, uint64_t tag, int noise_bits,
                          void* packed, uint64_t capacity, void* header, int hdr, void* stream)
 {
+    if (as_table_of_one(dtype, N, D, kTileGroups)) {
+        actq_tensor one = {};
+        one.x = x;
+        one.header = header;
+        one.bits = bits;
+        one.offsets = offsets;
+        one.D = D;
+        return launch_quantize_pack_multi(&one, 1, dtype, N, seed, tag, noise_bits, packed, capacity, hdr, stream);
+    }
     const int64_t ng = (D + kGroup - 1) / kGroup;
     const int64_t tps = (ng + kTileGroups - 1) / kTileGroups;
     if (N * tps >= (int64_t(1) << 32))
@@ -1735,7 +1787,7 @@ int launch_allocate_bits(const float* w, const int64_t* D_items, int64_t D, int6
 
 static int make_multi_table(const char* who, const actq_tensor* tensors, int32_t count, int64_t N, int hdr,
                             MultiTable* t, dim3* grid, int groups_per_wave = kTileGroups,
-                            int waves_per_block = kWavesPerBlock)
+                            int waves_per_block = kWavesPerBlock, int run = 1)
 {
     t->count = static_cast<uint32_t>(count);
     t->N = static_cast<uint32_t>(N);
@@ -1761,9 +1813,10 @@ static int make_multi_table(const char* who, const actq_tensor* tensors, int32_t
         it.tiles = static_cast<uint32_t>(per_sample);
         it.total_tiles = static_cast<uint32_t>(tiles);
     }
-    // whole runs of 8 blocks (one block per XCD)
-    const uint64_t per_run = 8u * static_cast<uint64_t>(waves_per_block);
-    *grid = dim3(static_cast<unsigned>((most + per_run - 1) / per_run * 8u), static_cast<unsigned>(count));
+    // whole runs of 8 * run blocks (`run` blocks per XCD): every order of wave_unit covers a run exactly
+    const uint64_t blocks_per_run = 8u * static_cast<uint64_t>(run);
+    const uint64_t per_run = blocks_per_run * static_cast<uint64_t>(waves_per_block);
+    *grid = dim3(static_cast<unsigned>((most + per_run - 1) / per_run * blocks_per_run), static_cast<unsigned>(count));
     return ACTQ_OK;
 }
 
@@ -1771,7 +1824,7 @@ int launch_group_stats_multi(const actq_tensor* tensors, int32_t count, int dtyp
 {
     MultiTable t;
     dim3 grid;
-    if (int rc = make_multi_table("actq_group_stats_multi", tensors, count, N, 0, &t, &grid, kGsTiles * kTileGroups, kGsBlock / kWave)) return rc;
+    if (int rc = make_multi_table("actq_group_stats_multi", tensors, count, N, 0, &t, &grid, kGsTiles * kTileGroups, kGsBlock / kWave, ACTQ_GS_RUN)) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (dtype == ACTQ_F32) group_stats_multi_kernel<float><<<grid, kGsBlock, 0, s>>>(t);
     else group_stats_multi_kernel<_Float16><<<grid, kGsBlock, 0, s>>>(t);
@@ -1783,7 +1836,7 @@ int launch_quantize_pack_multi(const actq_tensor* tensors, int32_t count, int dt
 {
     MultiTable t;
     dim3 grid;
-    if (int rc = make_multi_table("actq_quantize_pack_multi", tensors, count, N, hdr, &t, &grid)) return rc;
+    if (int rc = make_multi_table("actq_quantize_pack_multi", tensors, count, N, hdr, &t, &grid, kTileGroups, kWavesPerBlock, ACTQ_QP_RUN)) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint32_t k0 = static_cast<uint32_t>(seed), k1 = static_cast<uint32_t>(seed >> 32);
     uint8_t* pk = static_cast<uint8_t*>(packed);
@@ -1803,7 +1856,7 @@ int launch_unpack_dequantize_multi(const actq_tensor* tensors, int32_t count, co
     MultiTable t;
     dim3 grid;
     const int per_wave = out_dtype == ACTQ_F16 ? kDqGroupsF16 : kDqGroupsF32;
-    if (int rc = make_multi_table("actq_unpack_dequantize_multi", tensors, count, N, hdr, &t, &grid, per_wave, kDqBlock / kWave)) return rc;
+    if (int rc = make_multi_table("actq_unpack_dequantize_multi", tensors, count, N, hdr, &t, &grid, per_wave, kDqBlock / kWave, ACTQ_DQ_RUN)) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint8_t* pk = static_cast<const uint8_t*>(packed);
 #define ACTQ_DEQM(T, NG)                                                                                    \
