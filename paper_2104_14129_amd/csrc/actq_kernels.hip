@@ -21,6 +21,17 @@
 //   * packed codes go through a wavefront-private LDS slice so that the bit stream leaves
 //     as one fully coalesced store per tile whatever the width.
 //
+// Beyond the arithmetic, three things about the memory system decide the speed (all measured
+// on tensors that do not fit the caches):
+//   * small writes that reach HBM in the middle of a read stream are expensive out of all
+//     proportion (the statistics, 0.8 % of the bytes, cost 10 % of the time): they are issued
+//     as ordinary cached stores and the tiles are dealt to the eight XCDs in long runs, so that
+//     whole lines of them collect in one L2 (wave_unit);
+//   * a write stream is fastest when every XCD writes every eighth 4 KiB page of it (the
+//     dequantizer's order), and a branch between the loads and the stores of a wavefront makes
+//     the compiler serialise the stores (dequantize_groups);
+//   * the scalar loads at the start of a wavefront are issued in batches (ACTQ_SCALAR_BATCH*).
+//
 // This file must be compiled with -ffp-contract=off: the scaling step is a subtraction
 // and a multiplication that are rounded separately.
 #include <hip/hip_runtime.h>
@@ -39,36 +50,21 @@ constexpr int kBlock = kWave * kWavesPerBlock;
 constexpr int kTileGroups = 4;
 constexpr int kMaxMulti = ACTQ_MAX_TENSORS_PER_CALL;  // tensors of one multi-tensor launch
 
-// Shape of the dequantizer's launch (full-group tensors): groups per wavefront for binary32 and
-// binary16 output, threads per block, and whether the group headers come through the vector
-// memory path (one lane-uniform load per group) or the scalar data path.
-#ifndef ACTQ_DQ_GROUPS_F32
-#define ACTQ_DQ_GROUPS_F32 4
-#endif
-#ifndef ACTQ_DQ_GROUPS_F16
-#define ACTQ_DQ_GROUPS_F16 8
-#endif
-#ifndef ACTQ_DQ_BLOCK
-#define ACTQ_DQ_BLOCK 256
-#endif
-#ifndef ACTQ_DQ_VHDR
-#define ACTQ_DQ_VHDR 1
-#endif
-#ifndef ACTQ_DQ_XCD_MAP
-#define ACTQ_DQ_XCD_MAP 1
-#endif
-constexpr int kDqXcdMap = ACTQ_DQ_XCD_MAP;
-#ifndef ACTQ_DQ_RUN
-#define ACTQ_DQ_RUN 1
-#endif
-#ifndef ACTQ_QP_XCD_MAP
-#define ACTQ_QP_XCD_MAP 0
-#endif
-constexpr int kQpXcdMap = ACTQ_QP_XCD_MAP;
-constexpr int kDqGroupsF32 = ACTQ_DQ_GROUPS_F32;
-constexpr int kDqGroupsF16 = ACTQ_DQ_GROUPS_F16;
-constexpr int kDqBlock = ACTQ_DQ_BLOCK;
-constexpr bool kDqVectorHeader = ACTQ_DQ_VHDR != 0;
+// Launch shapes of the multi-tensor kernels (which also serve single binary32 tensors of full
+// groups).  Each value was chosen by A/B runs on the 53-tensor ResNet-50 sweep at batch 256,
+// alternatives in brackets.
+constexpr int kDqGroupsF32 = 4;         // dequantizer: groups per wavefront, binary32 output [2, 1: slower]
+constexpr int kDqGroupsF16 = 8;         //              binary16 output: the same 4 KiB per wavefront
+constexpr int kDqBlock = 256;           //              threads per block [512 alike; 1024, 128, 64 slower]
+constexpr bool kDqVectorHeader = true;  //              group headers by lane-uniform vector loads [scalar loads: 10 % slower on cold data]
+constexpr int kDqXcdMap = 1;            //              tiles dealt to the XCDs modulo 8 [plain order: 13 % slower]
+constexpr int kDqRun = 1;
+constexpr int kGsTiles = 1;             // statistics: tiles per wavefront [2: slower]
+constexpr int kGsBlock = 256;           //             threads per block [64 .. 1024: alike or slower]
+constexpr int kGsXcdMap = 0;
+constexpr int kGsRun = 16;              //             consecutive workgroups' tiles per XCD [1: 5 % slower; 8, 32 near; not powers of two: slower]
+constexpr int kQpXcdMap = 0;            // quantizer [tiles modulo 8: slower]
+constexpr int kQpRun = 16;              //           [1: 3 % slower; 32 alike]
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
@@ -896,13 +892,13 @@ __global__ __launch_bounds__(kBlock) void unpack_dequantize_kernel(
 // Several tensors in one launch.  A network saves dozens of activations of very different
 // sizes (a ResNet-50 step: 53, from 26 MB to 822 MB at batch 256); one launch per tensor leaves
 // the chip draining and refilling 53 times per pass, and the small tensors cannot fill it at
-// all.  Here blockIdx.y is the tensor and blockIdx.x runs over its tiles, sample after sample,
-// so the launch walks HBM in the order of back-to-back single-tensor launches, without the
-// gaps.  grid.x is sized for the largest tensor of the call and the surplus blocks of smaller
-// ones exit at once, so a call should group tensors of similar size.  The start of a wavefront
-// is as short as in the single-tensor kernels: one uniform load of the tensor's item from the
-// kernel arguments, then the widths and the data; a multiply-high division splits the linear
-// tile index into sample and tile.
+// all.  Here blockIdx.y is the tensor and blockIdx.x runs over its tiles, sample after sample
+// (in an order that depends on the kernel, see wave_unit), so the launch walks HBM like
+// back-to-back single-tensor launches, without the gaps.  grid.x is sized for the largest
+// tensor of the call and the surplus blocks of smaller ones exit at once, so a call should
+// group tensors of similar size.  The start of a wavefront is short: one batch of scalar loads
+// for the tensor's item from the kernel arguments, one for the sample's width and offset, then
+// the data; a multiply-high division splits the linear tile index into sample and tile.
 // (Measured alternatives on the 53-tensor sweep: samples in grid.y with all tensors' tiles side
 // by side in grid.x -- 53 concurrent streams -- made every kernel 5-20 % slower than single
 // launches; one linear grid over all tensors with a ballot over prefix sums to find the tensor
@@ -1016,23 +1012,6 @@ __device__ __forceinline__ bool range_ok(uint64_t off, uint64_t bytes, uint64_t 
     return (off & 31u) == 0 && off <= capacity && bytes <= capacity - off;
 }
 
-#ifndef ACTQ_GS_TILES
-#define ACTQ_GS_TILES 1
-#endif
-#ifndef ACTQ_GS_BLOCK
-#define ACTQ_GS_BLOCK 256
-#endif
-#ifndef ACTQ_GS_XCD_MAP
-#define ACTQ_GS_XCD_MAP 0
-#endif
-#ifndef ACTQ_GS_RUN
-#define ACTQ_GS_RUN 16
-#endif
-#ifndef ACTQ_QP_RUN
-#define ACTQ_QP_RUN 16
-#endif
-constexpr int kGsTiles = ACTQ_GS_TILES;    // tiles (of four groups) per wavefront of the statistics kernel
-constexpr int kGsBlock = ACTQ_GS_BLOCK;
 
 template <typename T>
 __global__ __launch_bounds__(kGsBlock) void group_stats_multi_kernel(MultiTable t)
@@ -1040,7 +1019,7 @@ __global__ __launch_bounds__(kGsBlock) void group_stats_multi_kernel(MultiTable 
     const int lane = threadIdx.x & (kWave - 1);
     const uint32_t wave = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6)));
     MultiCursor c;
-    if (!multi_cursor<kGsBlock / kWave, ACTQ_GS_XCD_MAP, ACTQ_GS_RUN>(t, wave, c)) return;
+    if (!multi_cursor<kGsBlock / kWave, kGsXcdMap, kGsRun>(t, wave, c)) return;
     const uint32_t n = c.n;
     const int64_t D = static_cast<int64_t>(c.D);
     const uint32_t ng = static_cast<uint32_t>(c.D >> 8);
@@ -1080,7 +1059,7 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_multi_kernel(MultiTable 
     const int lane = threadIdx.x & (kWave - 1);
     const uint32_t wave = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6)));
     MultiCursor mc;
-    if (!multi_cursor<kWavesPerBlock, kQpXcdMap, ACTQ_QP_RUN>(t, wave, mc)) return;
+    if (!multi_cursor<kWavesPerBlock, kQpXcdMap, kQpRun>(t, wave, mc)) return;
     Cursor c;
     c.n = mc.n;
     c.t = mc.tile;
@@ -1109,7 +1088,7 @@ __global__ __launch_bounds__(kDqBlock) void unpack_dequantize_multi_kernel(Multi
     const uint32_t wave = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6)));
     uint32_t* stage = stage_all[wave];
     MultiCursor c;
-    if (!multi_cursor<kWaves, kDqXcdMap, ACTQ_DQ_RUN>(t, wave, c)) return;
+    if (!multi_cursor<kWaves, kDqXcdMap, kDqRun>(t, wave, c)) return;
     uint32_t b;
     uint64_t off;
     sample_width_offset(c, b, off);
@@ -1622,17 +1601,13 @@ bool vector_ok(int64_t D) { return D % kGroup == 0; }
 
 }  // namespace
 
-#ifndef ACTQ_SINGLE_VIA_MULTI
-#define ACTQ_SINGLE_VIA_MULTI 1
-#endif
-
 // A binary32 tensor of full groups goes through the multi-tensor kernels as a table of one: their
 // linear grid over (sample, tile) and its XCD-aware order measured faster than samples in grid.y
 // (group_stats 65 -> 63 us on the stage-1 tensor; binary16 input gained nothing and its quantizer,
 // bound by the vector ALU, lost 3 % to the longer prologue).
 static bool as_table_of_one(int dtype, int64_t N, int64_t D, int64_t groups_per_wave)
 {
-    return ACTQ_SINGLE_VIA_MULTI && dtype == ACTQ_F32 && vector_ok(D) &&
+    return dtype == ACTQ_F32 && vector_ok(D) &&
            N * ((D / kGroup + groups_per_wave - 1) / groups_per_wave) < (int64_t(1) << 31);
 }
 
@@ -1824,7 +1799,7 @@ int launch_group_stats_multi(const actq_tensor* tensors, int32_t count, int dtyp
 {
     MultiTable t;
     dim3 grid;
-    if (int rc = make_multi_table("actq_group_stats_multi", tensors, count, N, 0, &t, &grid, kGsTiles * kTileGroups, kGsBlock / kWave, ACTQ_GS_RUN)) return rc;
+    if (int rc = make_multi_table("actq_group_stats_multi", tensors, count, N, 0, &t, &grid, kGsTiles * kTileGroups, kGsBlock / kWave, kGsRun)) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (dtype == ACTQ_F32) group_stats_multi_kernel<float><<<grid, kGsBlock, 0, s>>>(t);
     else group_stats_multi_kernel<_Float16><<<grid, kGsBlock, 0, s>>>(t);
@@ -1836,7 +1811,7 @@ int launch_quantize_pack_multi(const actq_tensor* tensors, int32_t count, int dt
 {
     MultiTable t;
     dim3 grid;
-    if (int rc = make_multi_table("actq_quantize_pack_multi", tensors, count, N, hdr, &t, &grid, kTileGroups, kWavesPerBlock, ACTQ_QP_RUN)) return rc;
+    if (int rc = make_multi_table("actq_quantize_pack_multi", tensors, count, N, hdr, &t, &grid, kTileGroups, kWavesPerBlock, kQpRun)) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint32_t k0 = static_cast<uint32_t>(seed), k1 = static_cast<uint32_t>(seed >> 32);
     uint8_t* pk = static_cast<uint8_t*>(packed);
@@ -1856,7 +1831,7 @@ int launch_unpack_dequantize_multi(const actq_tensor* tensors, int32_t count, co
     MultiTable t;
     dim3 grid;
     const int per_wave = out_dtype == ACTQ_F16 ? kDqGroupsF16 : kDqGroupsF32;
-    if (int rc = make_multi_table("actq_unpack_dequantize_multi", tensors, count, N, hdr, &t, &grid, per_wave, kDqBlock / kWave, ACTQ_DQ_RUN)) return rc;
+    if (int rc = make_multi_table("actq_unpack_dequantize_multi", tensors, count, N, hdr, &t, &grid, per_wave, kDqBlock / kWave, kDqRun)) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint8_t* pk = static_cast<const uint8_t*>(packed);
 #define ACTQ_DEQM(T, NG)                                                                                    \
