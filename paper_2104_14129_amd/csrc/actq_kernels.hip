@@ -291,6 +291,12 @@ __device__ __forceinline__ V load_readonly(const V* p)
     return *(constant_ptr)(reinterpret_cast<uintptr_t>(p));
 }
 
+// True if the sample's byte range [off, off + bytes) is 32-byte aligned and inside the stream.
+__device__ __forceinline__ bool range_ok(uint64_t off, uint64_t bytes, uint64_t capacity)
+{
+    return (off & 31u) == 0 && off <= capacity && bytes <= capacity - off;
+}
+
 // Width of sample n through the scalar data path: the 32-bit word that holds bits[n] (the
 // array is 4-byte aligned, so the word shares a page with bits[n] and the load cannot fault
 // even when N is not a multiple of four), then a shift.
@@ -661,6 +667,279 @@ __device__ __forceinline__ void quantize_one(const TileRegs& r, const Cursor& c,
     }
 }
 
+// ------------------------------------------------------------------------------------
+// binary16 input with 16-bit noise and the binary32 header: a lane-to-element map of its own.
+//
+// With two bytes per element the quantizer is bound by the vector ALU (every SIMD issues all
+// the time), so this path exists to issue fewer instructions for the same arithmetic:
+//   * a lane works on 32 consecutive elements, so a group is eight lanes and a wavefront
+//     takes a run of EIGHT groups: what is paid once per group and lane (the reduction across
+//     lanes, the two IEEE divisions, addresses, the header) is spread over twice the elements
+//     of the general path's tile.  32 elements are exactly what four Philox calls serve with
+//     16-bit noise: a lane uses all words of its own calls and nothing is traded between
+//     lanes.  The run's four kilobytes are loaded in address order and dealt to the lanes
+//     through the LDS (LDS instructions do not take vector-ALU issue slots);
+//   * a lane's 32 codes are 4 B consecutive bytes of the bit stream for every width B, stored
+//     by the lane itself: the codes do not pass through the LDS;
+//   * minimum and maximum are taken on the packed binary16 pairs as they arrive (min and max
+//     of binary16 values are exact in binary16) with the three-operand packed instructions,
+//     folded into one packed pair (min, -max) per lane, so the reduction over the eight
+//     lanes works on one register with three lane permutations;
+//   * the subtraction x - Z reads the binary16 half of the loaded word directly (a
+//     mixed-precision fma with the factor 1: fl32(x * 1 - Z) is the separately rounded
+//     subtraction), which removes the conversions to binary32 and the half extractions;
+//   * the clamp of the scaled value to B = 2^b - 1 is skipped for b <= 7, where it cannot
+//     change a code: with r the range and q = fl(B / r) (normal for any binary16 range),
+//     fl((x - Z) q) <= fl(r q) <= fl(B (1 + 2^-24)) <= B + ulp(B), and with ulp(B) <= 2^-17
+//     the sum B + ulp(B) + (1 - 2^-16) is a binary32 number below B + 1, so the floor is B
+//     with or without the clamp.  (For b = 8 one ulp is 2^-16 and the sum reaches 256: the
+//     clamp is kept.)
+// The arithmetic per element is that of encode_tile, bit for bit.  The last run of a sample
+// may hold fewer than eight groups: its spare lanes re-read the sample's last group and store
+// nothing.
+
+constexpr int kQpGroupsF16 = 8;   // groups per wavefront
+constexpr int kQpStageSlots = 272;   // 16-byte LDS slots per wavefront: the run's 256 pieces and one spare per sixteen
+
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x3 __attribute__((ext_vector_type(3)));
+
+__device__ __forceinline__ f16x2 as_f16x2(uint32_t u)
+{
+    f16x2 v;
+    __builtin_memcpy(&v, &u, 4);
+    return v;
+}
+
+__device__ __forceinline__ uint32_t as_u32(f16x2 v)
+{
+    uint32_t u;
+    __builtin_memcpy(&u, &v, 4);
+    return u;
+}
+
+template <int CTRL>
+__device__ __forceinline__ f16x2 dpp_f16x2(f16x2 v)
+{
+    return as_f16x2(dpp_u32<CTRL>(as_u32(v)));
+}
+
+// Minimum over each eight consecutive lanes, per packed half, in every one of the eight.
+__device__ __forceinline__ f16x2 eight_lane_min(f16x2 p)
+{
+    p = __builtin_elementwise_minimum(p, dpp_f16x2<kDppXor1>(p));
+    p = __builtin_elementwise_minimum(p, dpp_f16x2<kDppXor2>(p));
+    p = __builtin_elementwise_minimum(p, dpp_f16x2<kDppHalfMirror>(p));
+    return p;
+}
+
+// fl32(half - z) for the low (HIGH = false) or high half of `word`: one instruction, the half is
+// widened by the operand selector.  `one` is 1.0f in a register.
+template <bool HIGH>
+__device__ __forceinline__ float half_minus(uint32_t word, float one, float neg_z)
+{
+    float r;
+    if (HIGH) asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(r) : "v"(word), "v"(one), "v"(neg_z));
+    else asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel_hi:[1,0,0]" : "=v"(r) : "v"(word), "v"(one), "v"(neg_z));
+    return r;
+}
+
+// Code of the lane's element j (half j & 1 of loaded word j >> 1, the noise in the same half of
+// noise word j >> 1).
+template <int B>
+__device__ __forceinline__ uint32_t code_f16(const uint32_t (&xw)[16], const uint32_t (&rnd)[16], int j, float one,
+                                             float neg_mn, float inv)
+{
+    constexpr float kB = static_cast<float>((1 << B) - 1);
+    const float centred = (j & 1) ? half_minus<true>(xw[j >> 1], one, neg_mn) : half_minus<false>(xw[j >> 1], one, neg_mn);
+    float scaled = centred * inv;
+    if (B == 8) scaled = fminf(scaled, kB);
+    const uint32_t noise = (j & 1) ? rnd[j >> 1] >> 16 : rnd[j >> 1] & 0xffffu;
+    return static_cast<uint32_t>(__builtin_fmaf(static_cast<float>(noise), 1.52587890625e-05f, scaled));
+}
+
+// The lane's 32 codes, packed LSB first into the B words of `out`.
+template <int B>
+__device__ __forceinline__ void encode_lane_f16(const uint32_t (&xw)[16], const uint32_t (&rnd)[16], float neg_mn, float inv,
+                                                uint32_t (&out)[8])
+{
+    const float one = 1.0f;
+    if constexpr ((B & (B - 1)) == 0) {
+        // whole codes per word: word by word, last code first
+        constexpr int kPerWord = 32 / B;
+#pragma unroll
+        for (int w = 0; w < B; ++w) {
+            uint32_t acc = 0;
+#pragma unroll
+            for (int k = kPerWord - 1; k >= 0; --k) {
+                const uint32_t q = code_f16<B>(xw, rnd, w * kPerWord + k, one, neg_mn, inv);
+                if (k == kPerWord - 1) acc = q;
+                else asm("v_lshl_or_b32 %0, %1, %2, %3" : "=v"(acc) : "v"(acc), "n"(B), "v"(q));   // (acc << B) | q, kept one instruction per code
+            }
+            out[w] = acc;
+        }
+    } else {
+        // codes straddle words
+#pragma unroll
+        for (int w = 0; w < 8; ++w) out[w] = 0;
+#pragma unroll
+        for (int j = 0; j < 32; ++j) {
+            const uint32_t q = code_f16<B>(xw, rnd, j, one, neg_mn, inv);
+            const int w = (j * B) >> 5, sh = (j * B) & 31;
+            out[w] |= q << sh;
+            if (sh + B > 32) out[w + 1] |= q >> (32 - sh);
+            if ((j & 7) == 7) __builtin_amdgcn_sched_barrier(0);   // eight codes at a time keep the temporaries in registers
+        }
+    }
+}
+
+// 4 B bytes of a lane (words w[0 .. B-1]) to a 4-byte aligned address.
+template <int B>
+__device__ __forceinline__ void store_lane_words(uint8_t* dst, const uint32_t (&w)[8])
+{
+    typedef u32x4 __attribute__((aligned(4))) u32x4_a4;
+    typedef u32x2 __attribute__((aligned(4))) u32x2_a4;
+    constexpr int kQuads = B / 4, kRest = B % 4;
+#pragma unroll
+    for (int h = 0; h < kQuads; ++h) {
+        u32x4 v;
+        v.x = w[4 * h + 0];
+        v.y = w[4 * h + 1];
+        v.z = w[4 * h + 2];
+        v.w = w[4 * h + 3];
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x4_a4*>(dst + 16 * h));
+    }
+    uint8_t* rest = dst + 16 * kQuads;
+    if (kRest == 1) __builtin_nontemporal_store(w[4 * kQuads], reinterpret_cast<uint32_t*>(rest));
+    if (kRest == 2) {
+        u32x2 v;
+        v.x = w[4 * kQuads];
+        v.y = w[4 * kQuads + 1];
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x2_a4*>(rest));
+    }
+    if (kRest == 3) {
+        u32x2 v;
+        v.x = w[4 * kQuads];
+        v.y = w[4 * kQuads + 1];
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x2_a4*>(rest));
+        __builtin_nontemporal_store(w[4 * kQuads + 2], reinterpret_cast<uint32_t*>(rest + 8));
+    }
+}
+
+template <int B>
+__device__ __forceinline__ void encode_store_f16(const uint32_t (&xw)[16], const uint32_t (&rnd)[16], float neg_mn, float inv,
+                                                 bool valid, uint8_t* dst)
+{
+    uint32_t w[8];
+    encode_lane_f16<B>(xw, rnd, neg_mn, inv, w);
+    // the words are final here, for every lane: left alone, the compiler moves the encoding under the
+    // store's condition but keeps the 32 subtractions in front of it, and their results do not fit the registers
+#pragma unroll
+    for (int k = 0; k < B; ++k) asm volatile("" : "+v"(w[k]));
+    if (valid) store_lane_words<B>(dst, w);
+}
+
+// A run of up to eight full groups starting at g0 of sample n.  A sample whose width or byte
+// range is invalid is skipped, nothing is written.
+__device__ __forceinline__ void quantize_run_f16(const _Float16* __restrict__ xs, uint32_t n, uint32_t g0, uint32_t ng,
+                                                 int lane, uint32_t k0, uint32_t k1, uint32_t tag0, uint32_t tag1,
+                                                 const uint8_t* __restrict__ bits, const uint64_t* __restrict__ offsets,
+                                                 uint8_t* __restrict__ packed, uint64_t capacity,
+                                                 float* __restrict__ header, u32x4* stage)
+{
+    // lane l works on elements 32 (l & 7) .. + 31 of group g0 + (l >> 3): bytes 64 l .. 64 l + 63 of the run
+    uint32_t g = g0 + (static_cast<uint32_t>(lane) >> 3);
+    const bool valid = g < ng;
+    g = valid ? g : ng - 1;
+    const uint32_t chunk = (g << 3) + (static_cast<uint32_t>(lane) & 7u);   // 64-byte piece of the sample, four noise counters
+    // A full run arrives in the order of the addresses (load p takes kilobyte p, lane l its bytes
+    // 16 l .. 16 l + 15) and is dealt to the lanes through the LDS further down; loading a lane's own
+    // 64 bytes directly costs a third of the kernel's time (121 against 78 us on the ResNet-50 stem
+    // tensor: four loads whose lanes are 64 bytes apart touch 32 cache lines each).  Only a sample's
+    // last, shorter run is loaded that way.
+    const bool full = g0 + kQpGroupsF16 <= ng;   // the same for the whole wavefront
+    const uint32_t first = full ? (g0 << 5) + static_cast<uint32_t>(lane) : 4u * chunk;   // in 16-byte pieces of the sample
+    const uint32_t step = full ? 64u : 1u;
+    const u32x4* src = reinterpret_cast<const u32x4*>(xs);
+    u32x4 x[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) x[p] = __builtin_nontemporal_load(src + (static_cast<int64_t>(first) + p * step));
+    uint32_t width_word = load_readonly(reinterpret_cast<const uint32_t*>(bits) + (n >> 2));
+    uint64_t off = load_readonly(offsets + n);
+    // noise: counter = feature index / 8 = 4 chunk and the three after it
+    uint32_t rnd[16];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        uint32_t r[4];
+        philox4x32_10(4 * chunk + p, n, tag0, tag1, k0, k1, r);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) rnd[4 * p + k] = r[k];
+        // one call after the other (interleaved, the four calls' temporaries cost the eighth wavefront per
+        // SIMD), and here, in the shadow of the loads, not behind the look at the sample's width
+        asm volatile("" : "+v"(rnd[4 * p]), "+v"(rnd[4 * p + 1]), "+v"(rnd[4 * p + 2]), "+v"(rnd[4 * p + 3]));
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    if (full) {
+        // 16-byte piece i of the run sits at slot i + i / 16: one spare slot per 256 bytes, so that the
+        // sixteen lanes the LDS serves at a time hit every bank once on the way in and on the way out
+#pragma unroll
+        for (int p = 0; p < 4; ++p) stage[68 * p + lane + (lane >> 4)] = x[p];
+        wave_lds_handover();
+#pragma unroll
+        for (int p = 0; p < 4; ++p) x[p] = stage[4 * lane + p + (lane >> 2)];
+    }
+    uint32_t xw[16];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        xw[4 * p + 0] = x[p].x;
+        xw[4 * p + 1] = x[p].y;
+        xw[4 * p + 2] = x[p].z;
+        xw[4 * p + 3] = x[p].w;
+    }
+    // lane-local minimum and maximum per packed half, then (min, -max) as one pair over the eight lanes
+    f16x2 lo2 = as_f16x2(xw[0]), hi2 = as_f16x2(xw[0]);
+#pragma unroll
+    for (int k = 1; k < 16; ++k) {
+        lo2 = __builtin_elementwise_minimum(lo2, as_f16x2(xw[k]));
+        hi2 = __builtin_elementwise_maximum(hi2, as_f16x2(xw[k]));
+    }
+    f16x2 a, b2;
+    a[0] = lo2[0]; a[1] = -hi2[0];
+    b2[0] = lo2[1]; b2[1] = -hi2[1];
+    const f16x2 fold = eight_lane_min(__builtin_elementwise_minimum(a, b2));
+    const float mn = static_cast<float>(fold[0]) + 0.0f;   // -0.0 -> +0.0
+    const float mx = -static_cast<float>(fold[1]);
+    asm volatile("" : "+s"(width_word), "+s"(off));   // the scalar loads are waited for here, behind the noise
+    const uint32_t b = (width_word >> ((n & 3u) * 8u)) & 0xffu;
+    if (b < 1 || b > 8 || !range_ok(off, static_cast<uint64_t>(ng) * 32u * b, capacity)) return;
+    const float kB = static_cast<float>((1u << b) - 1u);
+    const float range = mx - mn;
+    float inv = kB / range;
+    float scale = range / kB;
+    if (!(range != 0.0f) || !__builtin_isfinite(inv)) {   // constant group, or B / R overflows
+        inv = 0.0f;
+        scale = 0.0f;
+    }
+    uint8_t* dst = packed + off + static_cast<uint64_t>(chunk) * (4u * b);
+    switch (b) {
+        case 1: encode_store_f16<1>(xw, rnd, -mn, inv, valid, dst); break;
+        case 2: encode_store_f16<2>(xw, rnd, -mn, inv, valid, dst); break;
+        case 3: encode_store_f16<3>(xw, rnd, -mn, inv, valid, dst); break;
+        case 4: encode_store_f16<4>(xw, rnd, -mn, inv, valid, dst); break;
+        case 5: encode_store_f16<5>(xw, rnd, -mn, inv, valid, dst); break;
+        case 6: encode_store_f16<6>(xw, rnd, -mn, inv, valid, dst); break;
+        case 7: encode_store_f16<7>(xw, rnd, -mn, inv, valid, dst); break;
+        default: encode_store_f16<8>(xw, rnd, -mn, inv, valid, dst); break;
+    }
+    if (valid && (lane & 7) == 0) {
+        f32x2 h;
+        h.x = mn;
+        h.y = scale;
+        reinterpret_cast<f32x2*>(header)[static_cast<int64_t>(n) * ng + g] = h;
+    }
+}
+
 // One tile per wavefront (grid.x = tiles of a sample, grid.y * grid.z = samples).  Short-lived
 // wavefronts lose the least HBM bandwidth to the small writes of codes and headers, and the
 // other resident wavefronts' loads hide a tile's ALU work.  (A persistent software pipeline
@@ -1006,12 +1285,6 @@ __device__ __forceinline__ void sample_width_offset(const MultiCursor& c, uint32
     b = (width_word >> ((c.n & 3u) * 8u)) & 0xffu;
 }
 
-// True if the sample's byte range [off, off + bytes) is 32-byte aligned and inside the stream.
-__device__ __forceinline__ bool range_ok(uint64_t off, uint64_t bytes, uint64_t capacity)
-{
-    return (off & 31u) == 0 && off <= capacity && bytes <= capacity - off;
-}
-
 
 template <typename T>
 __global__ __launch_bounds__(kGsBlock) void group_stats_multi_kernel(MultiTable t)
@@ -1076,6 +1349,25 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_multi_kernel(MultiTable 
     quantize_one<NOISE_BITS, true>(r, c, geo, lane, k0, k1, static_cast<uint32_t>(tensor_tag),
                                    static_cast<uint32_t>(tensor_tag >> 32), packed, capacity,
                                    device_pointer<void>(mc.header), stage_all[wave]);
+}
+
+// binary16 input, 16-bit noise, binary32 header: runs of kQpGroupsF16 groups (the table is built for
+// runs of that length).  Eight wavefronts per SIMD are asked for: the kernel lives on other
+// wavefronts' issue slots while one waits for its loads.
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) void quantize_pack_f16_multi_kernel(
+    MultiTable t, uint32_t k0, uint32_t k1, uint64_t tag, uint8_t* __restrict__ packed, uint64_t capacity)
+{
+    __shared__ u32x4 stage_all[kWavesPerBlock][kQpStageSlots];
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint32_t wave = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6)));
+    MultiCursor mc;
+    if (!multi_cursor<kWavesPerBlock, kQpXcdMap, kQpRun>(t, wave, mc)) return;
+    const uint64_t tensor_tag = tag + blockIdx.y;  // every tensor of the launch draws its own noise
+    quantize_run_f16(device_pointer<const _Float16>(mc.x) + static_cast<int64_t>(mc.n) * static_cast<int64_t>(mc.D), mc.n,
+                     mc.tile * kQpGroupsF16, static_cast<uint32_t>(mc.D >> 8), lane, k0, k1, static_cast<uint32_t>(tensor_tag),
+                     static_cast<uint32_t>(tensor_tag >> 32), device_pointer<const uint8_t>(mc.bits),
+                     device_pointer<const uint64_t>(mc.offsets), packed, capacity, device_pointer<float>(mc.header),
+                     stage_all[wave]);
 }
 
 template <typename T, int HDR, int NG>
@@ -1603,13 +1895,26 @@ bool vector_ok(int64_t D) { return D % kGroup == 0; }
 
 // A binary32 tensor of full groups goes through the multi-tensor kernels as a table of one: their
 // linear grid over (sample, tile) and its XCD-aware order measured faster than samples in grid.y
-// (group_stats 65 -> 63 us on the stage-1 tensor; binary16 input gained nothing and its quantizer,
-// bound by the vector ALU, lost 3 % to the longer prologue).
+// (group_stats 65 -> 63 us on the stage-1 tensor; binary16 input gained nothing there).
+static bool fits_table_of_one(int64_t N, int64_t D, int64_t groups_per_wave)
+{
+    return vector_ok(D) && N * ((D / kGroup + groups_per_wave - 1) / groups_per_wave) < (int64_t(1) << 31);
+}
+
 static bool as_table_of_one(int dtype, int64_t N, int64_t D, int64_t groups_per_wave)
 {
-    return dtype == ACTQ_F32 && vector_ok(D) &&
-           N * ((D / kGroup + groups_per_wave - 1) / groups_per_wave) < (int64_t(1) << 31);
+    return dtype == ACTQ_F32 && fits_table_of_one(N, D, groups_per_wave);
 }
+
+// Groups a wavefront of the multi-tensor quantizer takes: binary16 input with 16-bit noise and the
+// binary32 header has a kernel of its own that works on runs of eight.
+static bool quantize_by_runs(int dtype, int noise_bits, int hdr) { return dtype == ACTQ_F16 && noise_bits == 16 && hdr == 0; }
+
+static int quantize_groups_per_wave(int dtype, int noise_bits, int hdr)
+{
+    return quantize_by_runs(dtype, noise_bits, hdr) ? kQpGroupsF16 : kTileGroups;
+}
+
 
 int launch_group_stats(const void* x, int dtype, int64_t N, int64_t D, float* gmin, float* grange,
                        void* stream)
@@ -1672,7 +1977,9 @@ int launch_quantize_pack(const void* x, int dtype, int64_t N, int64_t D, const u
                          const uint64_t* offsets, uint64_t seed, uint64_t tag, int noise_bits,
                          void* packed, uint64_t capacity, void* header, int hdr, void* stream)
 {
-    if (as_table_of_one(dtype, N, D, kTileGroups)) {
+    // binary16 input with 16-bit noise and the binary32 header as well: its kernel is a multi-tensor one only
+    if ((dtype == ACTQ_F32 || quantize_by_runs(dtype, noise_bits, hdr)) &&
+        fits_table_of_one(N, D, quantize_groups_per_wave(dtype, noise_bits, hdr))) {
         actq_tensor one = {};
         one.x = x;
         one.header = header;
@@ -1811,7 +2118,8 @@ int launch_quantize_pack_multi(const actq_tensor* tensors, int32_t count, int dt
 {
     MultiTable t;
     dim3 grid;
-    if (int rc = make_multi_table("actq_quantize_pack_multi", tensors, count, N, hdr, &t, &grid, kTileGroups, kWavesPerBlock, kQpRun)) return rc;
+    const int per_wave = quantize_groups_per_wave(dtype, noise_bits, hdr);
+    if (int rc = make_multi_table("actq_quantize_pack_multi", tensors, count, N, hdr, &t, &grid, per_wave, kWavesPerBlock, kQpRun)) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint32_t k0 = static_cast<uint32_t>(seed), k1 = static_cast<uint32_t>(seed >> 32);
     uint8_t* pk = static_cast<uint8_t*>(packed);
@@ -1819,7 +2127,8 @@ int launch_quantize_pack_multi(const actq_tensor* tensors, int32_t count, int dt
         if (noise_bits == 16) quantize_pack_multi_kernel<float, 16><<<grid, kBlock, 0, s>>>(t, k0, k1, tag, pk, capacity);
         else quantize_pack_multi_kernel<float, 24><<<grid, kBlock, 0, s>>>(t, k0, k1, tag, pk, capacity);
     } else {
-        if (noise_bits == 16) quantize_pack_multi_kernel<_Float16, 16><<<grid, kBlock, 0, s>>>(t, k0, k1, tag, pk, capacity);
+        if (quantize_by_runs(dtype, noise_bits, hdr)) quantize_pack_f16_multi_kernel<<<grid, kBlock, 0, s>>>(t, k0, k1, tag, pk, capacity);
+        else if (noise_bits == 16) quantize_pack_multi_kernel<_Float16, 16><<<grid, kBlock, 0, s>>>(t, k0, k1, tag, pk, capacity);
         else quantize_pack_multi_kernel<_Float16, 24><<<grid, kBlock, 0, s>>>(t, k0, k1, tag, pk, capacity);
     }
     return check_launch("actq_quantize_pack_multi");

@@ -104,3 +104,27 @@ def clamp_case(noise_bits: int, seed: int = 321, D: int = 1 << 18):
         if x[0, g * 256:(g + 1) * 256].min() != 0.0:
             x[0, g * 256 + (1 if d % 256 == 0 else 0)] = 0.0
     return x, hits
+
+
+def overshoot_case_f16(b: int, seed: int = 321, D: int = 1 << 18):
+    """As clamp_case, for binary16 input, 16-bit noise and width b: a range r (a binary16 number)
+    with fl32(r * fl32(B / r)) one ulp above B = 2^b - 1, the group maximum placed on the elements
+    that draw the largest noise, 1 - 2^-16.  Returns (x [1, D] float16, those elements)."""
+    import oracle
+    B = np.float32((1 << b) - 1)
+    cands = np.arange(0x3800, 0x4000, dtype=np.uint16).view(np.float16)      # [0.5, 2)
+    c32 = cands.astype(np.float32)
+    over = (c32 * (B / c32).astype(np.float32)).astype(np.float32) > B
+    if not over.any():
+        return None, []
+    r = cands[np.flatnonzero(over)[0]]
+    hits = [d for d in range(D) if oracle.noise(seed, 0, 0, d, 16) >= 1.0 - 2.0 ** -16]
+    assert hits, "no element with the largest noise; enlarge D"
+    x = np.zeros((1, D), dtype=np.float16)
+    x[0, 1::2] = np.float16(float(r) / 2)
+    for d in hits:
+        x[0, d] = r
+        g = d // 256
+        if x[0, g * 256:(g + 1) * 256].min() != 0.0:
+            x[0, g * 256 + (1 if d % 256 == 0 else 0)] = 0.0
+    return x, hits

@@ -9,7 +9,7 @@ from paper_2104_14129_amd import binding as B
 from paper_2104_14129_amd import synth
 from paper_2104_14129_amd.plan import TensorSetPlan, size_classes
 from _gpu import GpuRun
-from _helpers import clamp_case
+from _helpers import clamp_case, overshoot_case_f16
 from test_gpu_parity import _round_trip, _round_trip_bf16
 
 pytestmark = pytest.mark.gpu
@@ -48,6 +48,25 @@ def test_scaled_value_is_clamped_to_B_on_the_gpu(noise_bits):
     assert all(codes[0, d] == 255 for d in hits)
     want = oracle.quantize_codes(x, bits, 321, noise_bits=noise_bits)
     assert np.array_equal(codes[:, :x.shape[1]], want)
+
+
+@pytest.mark.parametrize("b", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_binary16_overshoot_by_one_ulp_never_yields_code_B_plus_1(b):
+    """Sec. 4.1 scaling with binary16 input and 16-bit noise: the kernel for this mode clamps the
+    scaled value only for b = 8 (below that an overshoot of one ulp cannot reach B + 1); the group
+    maximum, one ulp above B after scaling where such a range exists, sits on the elements with the
+    largest noise, and the whole stream must equal the oracle's, which always clamps."""
+    x, hits = overshoot_case_f16(b)
+    if x is None:
+        pytest.skip("no binary16 range in [0.5, 2) overshoots for this width")
+    bits = np.array([b], dtype=np.uint8)
+    run = GpuRun(x, bits)
+    packed, header = run.quantize(321, 0, 16)
+    opacked, oheader, _ = oracle.quantize_pack(x, bits, 321, 0, noise_bits=16)
+    assert np.array_equal(header.view(np.uint32), oheader.view(np.uint32))
+    assert np.array_equal(packed, opacked)
+    want = oracle.quantize_codes(x, bits, 321, noise_bits=16)
+    assert all(want[0, d] == (1 << b) - 1 for d in hits)
 
 
 def test_size_classes_partition_every_tensor_once():
