@@ -940,6 +940,184 @@ __device__ __forceinline__ void quantize_run_f16(const _Float16* __restrict__ xs
     }
 }
 
+// ------------------------------------------------------------------------------------
+// binary32 input with the binary32 header: the same lane-to-element map for four-byte elements.
+//
+// A lane works on SIXTEEN consecutive elements, a group is one row of sixteen lanes and a
+// wavefront takes the tile's four groups: the four kilobytes are loaded in address order and
+// dealt to the lanes through the LDS exactly as above.  Sixteen elements are what two Philox
+// calls serve with 16-bit noise and four with 24-bit noise, so again nothing is traded between
+// lanes; the reduction is four row-local lane permutations on the lane's own minimum and
+// maximum; the division pair is per row.  A lane's sixteen codes are 2 B consecutive bytes of
+// the bit stream: two neighbouring lanes join theirs (for odd B the odd lane's bits are moved
+// up by sixteen) and the even lane stores the 4 B bytes.
+// The clamp stays for every width: B / R can be subnormal for a binary32 range, and then the
+// bound used above for binary16 input does not hold.
+
+// Minimum over the sixteen lanes of each row, in every lane of the row.
+__device__ __forceinline__ float row_min_f32(float v)
+{
+    v = fminf(v, dpp_f32<kDppXor1>(v));
+    v = fminf(v, dpp_f32<kDppXor2>(v));
+    v = fminf(v, dpp_f32<kDppHalfMirror>(v));
+    v = fminf(v, dpp_f32<kDppXor8>(v));
+    return v;
+}
+
+// Code of element j of the lane.  16-bit noise: half j & 1 of noise word j >> 1; 24-bit noise: the
+// upper 24 bits of noise word j.
+template <int NOISE_BITS, int B>
+__device__ __forceinline__ uint32_t code_f32(float x, const uint32_t* rnd, int j, float mn, float inv)
+{
+    constexpr float kB = static_cast<float>((1 << B) - 1);
+    const float centred = x - mn;
+    float scaled = centred * inv;
+    scaled = fminf(scaled, kB);  // the two roundings can overshoot B by an ulp
+    if (NOISE_BITS == 16) {
+        const uint32_t noise = (j & 1) ? rnd[j >> 1] >> 16 : rnd[j >> 1] & 0xffffu;
+        return static_cast<uint32_t>(__builtin_fmaf(static_cast<float>(noise), 1.52587890625e-05f, scaled));
+    }
+    const float frac = __builtin_amdgcn_fractf(scaled);  // exact for scaled >= 0
+    const uint32_t q = static_cast<uint32_t>(scaled);    // truncation = floor
+    return q + ((static_cast<float>(rnd[j] >> 8) < frac * 16777216.0f) ? 1u : 0u);
+}
+
+// The lane's sixteen codes, packed LSB first: 16 B bits in out[0 .. (B + 1) / 2 - 1], upper bits zero.
+template <int NOISE_BITS, int B>
+__device__ __forceinline__ void encode_lane_f32(const float (&v)[16], const uint32_t* rnd, float mn, float inv, uint32_t (&out)[4])
+{
+#pragma unroll
+    for (int w = 0; w < 4; ++w) out[w] = 0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        const uint32_t q = code_f32<NOISE_BITS, B>(v[j], rnd, j, mn, inv);
+        const int w = (j * B) >> 5, sh = (j * B) & 31;
+        out[w] |= q << sh;
+        if (sh + B > 32) out[w + 1] |= q >> (32 - sh);
+    }
+}
+
+template <int NOISE_BITS, int B>
+__device__ __forceinline__ void encode_store_f32(const float (&v)[16], const uint32_t* rnd, float mn, float inv,
+                                                 bool valid, int lane, uint8_t* dst_pair)
+{
+    uint32_t own[4];
+    encode_lane_f32<NOISE_BITS, B>(v, rnd, mn, inv, own);
+    constexpr int kOwn = (B + 1) / 2;   // words that hold the lane's 16 B bits
+    uint32_t nb[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int k = 0; k < kOwn; ++k) nb[k] = dpp_u32<kDppXor1>(own[k]);   // the neighbour's words (used by the even lane)
+    uint32_t w[8];
+    if (B % 2 == 0) {
+#pragma unroll
+        for (int k = 0; k < kOwn; ++k) {
+            w[k] = own[k];
+            w[kOwn + k] = nb[k];
+        }
+    } else {
+        // own bits end in the middle of word kOwn - 1: the neighbour's follow from bit 16 of it
+#pragma unroll
+        for (int k = 0; k < kOwn - 1; ++k) w[k] = own[k];
+        w[kOwn - 1] = own[kOwn - 1] | (nb[0] << 16);
+#pragma unroll
+        for (int k = 0; k + 1 < kOwn; ++k) w[kOwn + k] = __builtin_amdgcn_alignbit(nb[k + 1], nb[k], 16);
+    }
+    // the words are final here, for every lane (see encode_store_f16)
+#pragma unroll
+    for (int k = 0; k < B; ++k) asm volatile("" : "+v"(w[k]));
+    if (valid && (lane & 1) == 0) store_lane_words<B>(dst_pair, w);
+}
+
+// The tile of up to four full groups starting at g0 of sample n.  A sample whose width or byte
+// range is invalid is skipped, nothing is written.
+template <int NOISE_BITS>
+__device__ __forceinline__ void quantize_tile_f32(const float* __restrict__ xs, uint32_t n, uint32_t g0, uint32_t ng,
+                                                  int lane, uint32_t k0, uint32_t k1, uint32_t tag0, uint32_t tag1,
+                                                  const uint8_t* __restrict__ bits, const uint64_t* __restrict__ offsets,
+                                                  uint8_t* __restrict__ packed, uint64_t capacity,
+                                                  float* __restrict__ header, u32x4* stage)
+{
+    // lane l works on elements 16 (l & 15) .. + 15 of group g0 + (l >> 4): bytes 64 l .. 64 l + 63 of the tile
+    uint32_t g = g0 + (static_cast<uint32_t>(lane) >> 4);
+    const bool valid = g < ng;
+    g = valid ? g : ng - 1;
+    const uint32_t chunk = (g << 4) + (static_cast<uint32_t>(lane) & 15u);   // 64-byte piece of the sample
+    const bool full = g0 + kTileGroups <= ng;   // the same for the whole wavefront
+    const uint32_t first = full ? (g0 << 6) + static_cast<uint32_t>(lane) : 4u * chunk;   // in 16-byte pieces of the sample
+    const uint32_t step = full ? 64u : 1u;
+    const u32x4* src = reinterpret_cast<const u32x4*>(xs);
+    u32x4 x[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) x[p] = __builtin_nontemporal_load(src + (static_cast<int64_t>(first) + p * step));
+    uint32_t width_word = load_readonly(reinterpret_cast<const uint32_t*>(bits) + (n >> 2));
+    uint64_t off = load_readonly(offsets + n);
+    // noise: counter = feature index / 8 (16-bit noise: two calls) or / 4 (24-bit noise: four calls)
+    constexpr int kCalls = NOISE_BITS == 16 ? 2 : 4;
+    uint32_t rnd[4 * kCalls];
+#pragma unroll
+    for (int p = 0; p < kCalls; ++p) {
+        uint32_t r[4];
+        philox4x32_10(kCalls * chunk + p, n, tag0, tag1, k0, k1, r);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) rnd[4 * p + k] = r[k];
+        // one call after the other, in the shadow of the loads (see quantize_run_f16)
+        asm volatile("" : "+v"(rnd[4 * p]), "+v"(rnd[4 * p + 1]), "+v"(rnd[4 * p + 2]), "+v"(rnd[4 * p + 3]));
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    if (full) {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) stage[68 * p + lane + (lane >> 4)] = x[p];
+        wave_lds_handover();
+#pragma unroll
+        for (int p = 0; p < 4; ++p) x[p] = stage[4 * lane + p + (lane >> 2)];
+    }
+    float v[16];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        v[4 * p + 0] = __uint_as_float(x[p].x);
+        v[4 * p + 1] = __uint_as_float(x[p].y);
+        v[4 * p + 2] = __uint_as_float(x[p].z);
+        v[4 * p + 3] = __uint_as_float(x[p].w);
+    }
+    float lo = v[0], hi = v[0];
+#pragma unroll
+    for (int k = 1; k < 16; ++k) {
+        lo = fminf(lo, v[k]);
+        hi = fmaxf(hi, v[k]);
+    }
+    const float mn = row_min_f32(lo) + 0.0f;   // -0.0 -> +0.0
+    const float mx = -row_min_f32(-hi);
+    asm volatile("" : "+s"(width_word), "+s"(off));   // the scalar loads are waited for here, behind the noise
+    const uint32_t b = (width_word >> ((n & 3u) * 8u)) & 0xffu;
+    if (b < 1 || b > 8 || !range_ok(off, static_cast<uint64_t>(ng) * 32u * b, capacity)) return;
+    const float kB = static_cast<float>((1u << b) - 1u);
+    const float range = mx - mn;
+    float inv = kB / range;
+    float scale = range / kB;
+    if (!(range != 0.0f) || !__builtin_isfinite(inv)) {   // constant group, or B / R overflows
+        inv = 0.0f;
+        scale = 0.0f;
+    }
+    // the even lane of a pair stores both lanes' bytes: 4 b bytes from byte 2 b chunk of the sample's stream
+    uint8_t* dst = packed + off + static_cast<uint64_t>(chunk) * (2u * b);
+    switch (b) {
+        case 1: encode_store_f32<NOISE_BITS, 1>(v, rnd, mn, inv, valid, lane, dst); break;
+        case 2: encode_store_f32<NOISE_BITS, 2>(v, rnd, mn, inv, valid, lane, dst); break;
+        case 3: encode_store_f32<NOISE_BITS, 3>(v, rnd, mn, inv, valid, lane, dst); break;
+        case 4: encode_store_f32<NOISE_BITS, 4>(v, rnd, mn, inv, valid, lane, dst); break;
+        case 5: encode_store_f32<NOISE_BITS, 5>(v, rnd, mn, inv, valid, lane, dst); break;
+        case 6: encode_store_f32<NOISE_BITS, 6>(v, rnd, mn, inv, valid, lane, dst); break;
+        case 7: encode_store_f32<NOISE_BITS, 7>(v, rnd, mn, inv, valid, lane, dst); break;
+        default: encode_store_f32<NOISE_BITS, 8>(v, rnd, mn, inv, valid, lane, dst); break;
+    }
+    if (valid && (lane & 15) == 0) {
+        f32x2 h;
+        h.x = mn;
+        h.y = scale;
+        reinterpret_cast<f32x2*>(header)[static_cast<int64_t>(n) * ng + g] = h;
+    }
+}
+
 // One tile per wavefront (grid.x = tiles of a sample, grid.y * grid.z = samples).  Short-lived
 // wavefronts lose the least HBM bandwidth to the small writes of codes and headers, and the
 // other resident wavefronts' loads hide a tile's ALU work.  (A persistent software pipeline
@@ -1368,6 +1546,24 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
                      static_cast<uint32_t>(tensor_tag >> 32), device_pointer<const uint8_t>(mc.bits),
                      device_pointer<const uint64_t>(mc.offsets), packed, capacity, device_pointer<float>(mc.header),
                      stage_all[wave]);
+}
+
+// binary32 input, binary32 header: one tile of four groups per wavefront.
+template <int NOISE_BITS>
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) void quantize_pack_f32_multi_kernel(
+    MultiTable t, uint32_t k0, uint32_t k1, uint64_t tag, uint8_t* __restrict__ packed, uint64_t capacity)
+{
+    __shared__ u32x4 stage_all[kWavesPerBlock][kQpStageSlots];
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint32_t wave = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6)));
+    MultiCursor mc;
+    if (!multi_cursor<kWavesPerBlock, kQpXcdMap, kQpRun>(t, wave, mc)) return;
+    const uint64_t tensor_tag = tag + blockIdx.y;  // every tensor of the launch draws its own noise
+    quantize_tile_f32<NOISE_BITS>(device_pointer<const float>(mc.x) + static_cast<int64_t>(mc.n) * static_cast<int64_t>(mc.D), mc.n,
+                                  mc.tile * kTileGroups, static_cast<uint32_t>(mc.D >> 8), lane, k0, k1,
+                                  static_cast<uint32_t>(tensor_tag), static_cast<uint32_t>(tensor_tag >> 32),
+                                  device_pointer<const uint8_t>(mc.bits), device_pointer<const uint64_t>(mc.offsets), packed,
+                                  capacity, device_pointer<float>(mc.header), stage_all[wave]);
 }
 
 template <typename T, int HDR, int NG>
@@ -2123,7 +2319,10 @@ int launch_quantize_pack_multi(const actq_tensor* tensors, int32_t count, int dt
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint32_t k0 = static_cast<uint32_t>(seed), k1 = static_cast<uint32_t>(seed >> 32);
     uint8_t* pk = static_cast<uint8_t*>(packed);
-    if (dtype == ACTQ_F32) {
+    if (dtype == ACTQ_F32 && hdr == 0) {
+        if (noise_bits == 16) quantize_pack_f32_multi_kernel<16><<<grid, kBlock, 0, s>>>(t, k0, k1, tag, pk, capacity);
+        else quantize_pack_f32_multi_kernel<24><<<grid, kBlock, 0, s>>>(t, k0, k1, tag, pk, capacity);
+    } else if (dtype == ACTQ_F32) {
         if (noise_bits == 16) quantize_pack_multi_kernel<float, 16><<<grid, kBlock, 0, s>>>(t, k0, k1, tag, pk, capacity);
         else quantize_pack_multi_kernel<float, 24><<<grid, kBlock, 0, s>>>(t, k0, k1, tag, pk, capacity);
     } else {
