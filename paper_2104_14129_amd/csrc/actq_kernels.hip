@@ -20,8 +20,12 @@
 //     each row working on its own group, and broadcast with v_readlane;
 //   * packed codes go through a wavefront-private LDS slice so that the bit stream leaves
 //     as one fully coalesced store per tile whatever the width.
+// The quantizer has two more kernels for the cases that carry the traffic (full groups, binary32
+// header; see quantize_run_f16 and quantize_tile_f32): there the tile is loaded in address order,
+// dealt through the LDS so that a lane holds a contiguous piece of one group, and the lane keeps
+// its noise, its share of the reduction and its bytes of the bit stream to itself.
 //
-// Beyond the arithmetic, three things about the memory system decide the speed (all measured
+// Beyond the arithmetic, four things about the memory system decide the speed (all measured
 // on tensors that do not fit the caches):
 //   * small writes that reach HBM in the middle of a read stream are expensive out of all
 //     proportion (the statistics, 0.8 % of the bytes, cost 10 % of the time): they are issued
@@ -30,7 +34,9 @@
 //   * a write stream is fastest when every XCD writes every eighth 4 KiB page of it (the
 //     dequantizer's order), and a branch between the loads and the stores of a wavefront makes
 //     the compiler serialise the stores (dequantize_groups);
-//   * the scalar loads at the start of a wavefront are issued in batches (ACTQ_SCALAR_BATCH*).
+//   * the scalar loads at the start of a wavefront are issued in batches (ACTQ_SCALAR_BATCH*);
+//   * loads must cover whole cache lines per instruction: four 128-bit loads whose lanes are 64
+//     bytes apart cost the binary16 quantizer a third of its time (quantize_run_f16).
 //
 // This file must be compiled with -ffp-contract=off: the scaling step is a subtraction
 // and a multiplication that are rounded separately.
