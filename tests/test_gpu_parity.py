@@ -111,6 +111,32 @@ def test_degenerate_groups_negative_zero_and_subnormals():
         assert hd[1, 0, 1] == 0.0       # B / R overflowed: degenerate
 
 
+def test_degenerate_groups_binary16_with_16_bit_noise():
+    """The binary16 kernel's own corner cases: constant groups, zeros of both signs, subnormal data,
+    the largest finite values of both signs in one group (range 131008 in binary32), a last run of
+    fewer than eight groups."""
+    N, D = 5, 256 * 11
+    rng = np.random.default_rng(12)
+    x = rng.standard_normal((N, D)).astype(np.float16)
+    x[0, :256] = np.float16(3.25)                        # constant group
+    x[0, 256:512] = 0.0
+    x[0, 300] = -0.0                                     # min is -0.0
+    x[3, 512:768] = 0.0
+    x[3, 512:768:2] = -0.0                               # zeros of both signs: range is +0.0
+    x[1, :256] = (rng.integers(0, 2, 256) * 6e-8).astype(np.float16)        # range = smallest subnormal
+    x[1, 256:512] = (rng.integers(0, 1000, 256) * 6e-8).astype(np.float16)  # subnormal data
+    x[2, :256] = -np.abs(x[2, :256])
+    x[2, 10] = -0.0                                      # max is -0.0
+    x[4, :256] = (rng.uniform(-1, 1, 256) * 65504).astype(np.float16)
+    x[4, 0], x[4, 255] = np.float16(65504), np.float16(-65504)
+    x[4, 2560:] = np.float16(-7.5)                       # constant group in the short last run
+    for b in (1, 2, 3, 4, 5, 6, 7, 8):
+        run = _round_trip(x, np.full(N, b, dtype=np.uint8), seed=6, tag=1, noise_bits=16, out_dtypes=(torch.float16,))
+        hd = run.header.cpu().numpy().reshape(N, -1, 2)
+        assert hd[0, 0, 1] == 0.0 and hd[0, 1, 0] == 0.0 and not np.signbit(hd[0, 1, 0])
+        assert hd[4, 10, 0] == -7.5 and hd[4, 10, 1] == 0.0
+
+
 def test_grid_points_reconstruct_exactly_on_the_gpu():
     N, ng = 4, 8
     rng = np.random.default_rng(3)
