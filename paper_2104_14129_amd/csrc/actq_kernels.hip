@@ -1388,8 +1388,6 @@ struct MultiTable {
     MultiItem item[kMaxMulti];
 };
 
-__device__ __forceinline__ uint32_t fastdiv(uint32_t n, FastDiv f) { return (__umulhi(n, f.m) + n) >> f.s; }
-
 // Linear work index of wavefront `wave` of block `bx`.  Blocks are handed to the eight XCDs in
 // turn, so block bx runs on XCD bx % 8 (grid.x is a multiple of 8 * RUN).
 // XCD_MAP 0: RUN consecutive blocks' worth of units (RUN * WAVES units) stay on one XCD -- RUN = 1
