@@ -921,8 +921,12 @@ __device__ __forceinline__ void quantize_run_f16(const _Float16* __restrict__ xs
     if (b < 1 || b > 8 || !range_ok(off, static_cast<uint64_t>(ng) * 32u * b, capacity)) return;
     const float kB = static_cast<float>((1u << b) - 1u);
     const float range = mx - mn;
-    float inv = kB / range;
-    float scale = range / kB;
+    // one IEEE division for both quotients: lanes 0..3 of a group take B / R, lanes 4..7 R / B, and trade
+    const bool inv_side = (lane & 4) == 0;
+    const float quotient = (inv_side ? kB : range) / (inv_side ? range : kB);
+    const float traded = dpp_f32<kDppHalfMirror>(quotient);
+    float inv = inv_side ? quotient : traded;
+    float scale = inv_side ? traded : quotient;
     if (!(range != 0.0f) || !__builtin_isfinite(inv)) {   // constant group, or B / R overflows
         inv = 0.0f;
         scale = 0.0f;
@@ -1098,8 +1102,12 @@ __device__ __forceinline__ void quantize_tile_f32(const float* __restrict__ xs, 
     if (b < 1 || b > 8 || !range_ok(off, static_cast<uint64_t>(ng) * 32u * b, capacity)) return;
     const float kB = static_cast<float>((1u << b) - 1u);
     const float range = mx - mn;
-    float inv = kB / range;
-    float scale = range / kB;
+    // one IEEE division for both quotients: lanes 0..7 of a row take B / R, lanes 8..15 R / B, and trade
+    const bool inv_side = (lane & 8) == 0;
+    const float quotient = (inv_side ? kB : range) / (inv_side ? range : kB);
+    const float traded = dpp_f32<kDppXor8>(quotient);
+    float inv = inv_side ? quotient : traded;
+    float scale = inv_side ? traded : quotient;
     if (!(range != 0.0f) || !__builtin_isfinite(inv)) {   // constant group, or B / R overflows
         inv = 0.0f;
         scale = 0.0f;
