@@ -137,6 +137,28 @@ def test_degenerate_groups_binary16_with_16_bit_noise():
         assert hd[4, 10, 0] == -7.5 and hd[4, 10, 1] == 0.0
 
 
+@pytest.mark.parametrize("case", range(48))
+def test_random_full_group_shapes_against_the_oracle(case):
+    """Seeded random problems on the kernels that serve full groups: sample counts 1..9, 1..41 groups
+    per sample (runs and tiles of every remainder), both input types and noise modes, widths 1..8
+    per sample, per-sample scales over six orders of magnitude, some samples constant or all zero."""
+    rng = np.random.default_rng(7000 + case)
+    N = int(rng.integers(1, 10))
+    ng = int(rng.integers(1, 42))
+    dtype = np.float16 if case % 2 else np.float32
+    noise_bits = 16 if (case // 2) % 2 == 0 else 24
+    scale = np.exp(rng.uniform(-7, 7, (N, 1))) if dtype == np.float32 else np.exp(rng.uniform(-5, 5, (N, 1)))
+    x = (rng.standard_normal((N, ng * 256)) * scale).astype(dtype)
+    if N > 2:
+        x[1] = dtype(0.0)
+        x[2, :256] = dtype(1.5)
+    if case % 3 == 0:
+        x = np.maximum(x, dtype(0.0))     # post-ReLU data: many groups with minimum 0
+    bits = rng.integers(1, 9, N).astype(np.uint8)
+    _round_trip(x, bits, seed=int(rng.integers(0, 2 ** 63)), tag=int(rng.integers(0, 2 ** 40)), noise_bits=noise_bits,
+                out_dtypes=(torch.float32, torch.float16))
+
+
 def test_grid_points_reconstruct_exactly_on_the_gpu():
     N, ng = 4, 8
     rng = np.random.default_rng(3)
